@@ -1,0 +1,157 @@
+/*
+ * saber.h - C ABI of the MI355X (gfx950) sparsity-aware LDA sampler.
+ *
+ * The library runs the ESCA iteration of the paper (Alg. 1): an E-step in which
+ * every token draws a topic from p(k) ~ (A_dk + alpha) * Bhat_vk (Eq. 1) through
+ * the sparsity-aware split of Alg. 2, then an M-step that rebuilds the sparse
+ * document-topic counts A (CountByDZ), the dense word-topic counts B (CountByVZ),
+ * Bhat by Eq. 2 (Preprocess) and the per-word prefix-sum trees (BuildTree).
+ * All of it executes in hand-written HIP kernels; there is no CPU fallback.
+ *
+ * Conventions
+ *   - Every pointer argument is a HOST pointer unless its comment says "device".
+ *   - The caller owns all input and output buffers.  saber_init copies what it
+ *     needs; inputs may be freed when it returns.
+ *   - Indices are 0-based.  Tokens are identified by their position t in the
+ *     caller's doc-major word_ids array ("canonical token index").
+ *   - Every function returns SABER_OK (0) or a negative saber_status and never
+ *     throws; saber_last_error() gives a message for the calling thread's last
+ *     failure.  A context is not thread-safe: one thread at a time per context.
+ *   - Random numbers: Philox4x32-10, key = seed, counter = (t lo, t hi, iteration, 0);
+ *     word 0 decides the branch, word 1 the position; u = (word >> 8) * 2^-24.
+ *     Results therefore do not depend on the internal token order, tile sizes or
+ *     chunk count.
+ *   - Limits: 1 <= K <= 262144 (three searched tree levels of width 64),
+ *     T < 2^31, and the longest document must be shorter than 2^(32 - ceil(log2 K)).
+ */
+#ifndef SABER_H
+#define SABER_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct saber_ctx saber_ctx; /* opaque, owned by the library */
+
+typedef enum saber_status {
+    SABER_OK = 0,
+    SABER_EINVAL = -1,  /* null pointer, bad size, malformed CSR, word id or topic out of range */
+    SABER_ENOMEM = -2,  /* host or device allocation failed */
+    SABER_EDEVICE = -3, /* no usable GPU, or a HIP call failed */
+    SABER_ESTATE = -4,  /* call not valid in the context's current state */
+    SABER_ERANGE = -5   /* a size exceeds a documented limit */
+} saber_status;
+
+/* Tunables; none of them changes any result.  Zero / negative means "library default". */
+typedef struct saber_options {
+    int32_t n_chunks;       /* document chunks the corpus is cut into (Sec. 3.1.2); default 1 */
+    int32_t block_threads;  /* threads per workgroup of the sampling kernel (multiple of 64); default 256 */
+    int32_t tile_tokens;    /* most tokens of one word handled by one workgroup; default 2048 */
+    int32_t stage_phi;      /* 1: keep the word's Bhat row in LDS when it fits, 0: always gather from global; default 1 */
+    int32_t profile;        /* 1: time every kernel group with HIP events (see saber_get_stats); default 0 */
+    int32_t long_doc_tokens;/* documents longer than this use a 256-thread workgroup in CountByDZ; default 512 */
+    int32_t dz_lds_entries; /* LDS capacity (entries) of one CountByDZ workgroup before it falls back to
+                               accumulating in the global row; default 8192 */
+    int32_t reserved[9];
+} saber_options;
+
+/* Sums over the iterations run since the last saber_reset_stats.  The ms_* fields need profile=1. */
+typedef struct saber_stats {
+    int64_t iterations;       /* iterations counted */
+    double ms_sample;         /* E-step sampling kernel (all chunks) */
+    double ms_count_dz;       /* CountByDZ */
+    double ms_ck;             /* topic totals C_k */
+    double ms_phi;            /* Preprocess + BuildTree */
+    double ms_total;          /* whole iterations, first kernel to last */
+    int64_t sample_launches;  /* sampling-kernel launches timed */
+    int64_t sum_tokens;       /* tokens sampled */
+    int64_t sum_tokens_dense; /* of those, tokens that took the dense branch (problem 2) */
+    int64_t sum_row_entries;  /* sum over sampled tokens of K_d: entries of A_d each token's product loop read */
+    /* state after the last M-step: */
+    int64_t nnz_cd;           /* non-zeros of A */
+    int64_t next_row_entries; /* sum_d K_d * L_d: what the next E-step will read */
+    /* layout constants: */
+    int64_t tokens;           /* T */
+    int64_t words_present;    /* (word, chunk) pairs with at least one token */
+    int64_t tiles;            /* workgroups of one E-step */
+    int64_t reserved[8];
+} saber_stats;
+
+/* Fill *opt with the defaults. */
+void saber_options_default(saber_options *opt);
+
+/*
+ * Create a sampler for one corpus (problem statement of Sec. 2.1).
+ *   doc_ptr  [D+1]  doc_ptr[0]=0, non-decreasing, doc_ptr[D]=T; empty documents are legal
+ *   word_ids [T]    doc-major token list, each in [0,V)
+ *   K, alpha, beta  number of topics and the two Dirichlet parameters (alpha>0, beta>0)
+ * On return the state is "iteration 0": z_t = floor(PhiloxWord0(t, 0) * K / 2^32), and A, B, Bhat and
+ * the trees are built from it, so saber_counts / saber_loglik are valid immediately.
+ * opt may be NULL.  Errors: EINVAL, ERANGE, ENOMEM, EDEVICE.  *out is NULL on failure.
+ */
+int saber_init_ex(saber_ctx **out, const int64_t *doc_ptr, const int32_t *word_ids, int64_t D, int32_t V,
+                  int32_t K, float alpha, float beta, uint64_t seed, const saber_options *opt);
+int saber_init(saber_ctx **out, const int64_t *doc_ptr, const int32_t *word_ids, int64_t D, int32_t V,
+               int32_t K, float alpha, float beta, uint64_t seed);
+
+/* Run n iterations of Alg. 1 (E-step for every token on the frozen counts, then the M-step).
+ * Synchronous: all work has finished when it returns.  n = 0 is a no-op.  Errors: EINVAL (n<0), EDEVICE. */
+int saber_iterate(saber_ctx *ctx, int32_t n);
+
+/* Number of non-zeros of A (size of cd_topic / cd_count for saber_counts). */
+int saber_counts_nnz(saber_ctx *ctx, int64_t *nnz_cd);
+
+/*
+ * Copy out the count matrices of the last completed M-step.
+ *   cd_row_ptr [D+1], cd_topic [nnz], cd_count [nnz]: A in CSR, topics ascending within a row
+ *   cwk [V*K] row-major by word (B);  ck [K] topic totals sum_v B_vk
+ * Any of the five may be NULL to skip it (cd_topic and cd_count need cd_row_ptr).
+ */
+int saber_counts(saber_ctx *ctx, int64_t *cd_row_ptr, int32_t *cd_topic, int32_t *cd_count, int32_t *cwk,
+                 int64_t *ck);
+
+/*
+ * Per-token training log-likelihood on the counts of the last M-step:
+ *   (1/T) sum_t [ ln(S_t + Q_w) - ln(L_d + K alpha) ]  =  (1/T) sum_t ln sum_k theta_dk Bhat_wk
+ * (the paper names per-token log-likelihood as its quality metric in Sec. 4 and gives no formula;
+ * this is the predictive likelihood of the training tokens, a by-product of the sampler's normaliser).
+ */
+int saber_loglik(saber_ctx *ctx, double *per_token_ll);
+
+void saber_free(saber_ctx *ctx);
+
+/* Message of the calling thread's last failed call (static storage, never NULL). */
+const char *saber_last_error(void);
+
+/* ---- state exchange (checkpointing, and the hooks the parity tests need) ---- */
+
+/* Current assignments, z[T] in canonical token order. */
+int saber_get_z(saber_ctx *ctx, int32_t *z);
+/* Replace the assignments (each in [0,K)), set the iteration counter to iter and redo the M-step.
+ * The next E-step then uses Philox counter word 2 = iter + 1. */
+int saber_set_z(saber_ctx *ctx, const int32_t *z, uint32_t iter);
+/* Iteration counter (0 after init). */
+int saber_get_iteration(saber_ctx *ctx, uint32_t *iter);
+
+/*
+ * Normalisers of Alg. 2 for m tokens (canonical indices tok[m], each in [0,T)) on the current counts:
+ *   S = sum_k A_dk Bhat_vk,  Q = alpha sum_k Bhat_vk,  p_sparse = S / (S + Q).  Outputs may be NULL.
+ */
+int saber_token_probs(saber_ctx *ctx, const int64_t *tok, int64_t m, float *S, float *Q, float *p_sparse);
+
+/* Rows of Bhat (Eq. 2) and of the per-word inclusive prefix table (bottom tree level) for m words:
+ * phi[m*K], prefix[m*K]; either may be NULL. */
+int saber_get_phi(saber_ctx *ctx, const int32_t *words, int32_t m, float *phi, float *prefix);
+
+/* ---- measurement ---- */
+int saber_get_stats(saber_ctx *ctx, saber_stats *out);
+int saber_reset_stats(saber_ctx *ctx);
+/* HIP stream the library launches on (a hipStream_t), for callers that want to order work against it. */
+int saber_get_stream(saber_ctx *ctx, void **hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SABER_H */

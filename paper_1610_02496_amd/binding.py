@@ -1,0 +1,210 @@
+"""ctypes binding of the C ABI in ``include/saber.h``: argument marshalling only.
+
+Every step of the path runs in the HIP kernels of ``libsaber.so``.  There is no
+CPU fallback: if the library is missing or no GPU is present the calls raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+SABER_OK, SABER_EINVAL, SABER_ENOMEM, SABER_EDEVICE, SABER_ESTATE, SABER_ERANGE = 0, -1, -2, -3, -4, -5
+_STATUS = {0: "SABER_OK", -1: "SABER_EINVAL", -2: "SABER_ENOMEM", -3: "SABER_EDEVICE", -4: "SABER_ESTATE",
+           -5: "SABER_ERANGE"}
+
+# every symbol include/saber.h declares
+EXPORTS = ["saber_options_default", "saber_init_ex", "saber_init", "saber_iterate", "saber_counts_nnz",
+           "saber_counts", "saber_loglik", "saber_free", "saber_last_error", "saber_get_z", "saber_set_z",
+           "saber_get_iteration", "saber_token_probs", "saber_get_phi", "saber_get_stats", "saber_reset_stats",
+           "saber_get_stream"]
+
+
+class SaberError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__("%s: %s" % (_STATUS.get(code, str(code)), msg))
+        self.code = code
+
+
+class Options(ctypes.Structure):
+    _fields_ = [("n_chunks", ctypes.c_int32), ("block_threads", ctypes.c_int32), ("tile_tokens", ctypes.c_int32),
+                ("stage_phi", ctypes.c_int32), ("profile", ctypes.c_int32), ("long_doc_tokens", ctypes.c_int32),
+                ("dz_lds_entries", ctypes.c_int32), ("reserved", ctypes.c_int32 * 9)]
+
+
+class Stats(ctypes.Structure):
+    _fields_ = [("iterations", ctypes.c_int64), ("ms_sample", ctypes.c_double), ("ms_count_dz", ctypes.c_double),
+                ("ms_ck", ctypes.c_double), ("ms_phi", ctypes.c_double), ("ms_total", ctypes.c_double),
+                ("sample_launches", ctypes.c_int64), ("sum_tokens", ctypes.c_int64),
+                ("sum_tokens_dense", ctypes.c_int64), ("sum_row_entries", ctypes.c_int64),
+                ("nnz_cd", ctypes.c_int64), ("next_row_entries", ctypes.c_int64), ("tokens", ctypes.c_int64),
+                ("words_present", ctypes.c_int64), ("tiles", ctypes.c_int64), ("reserved", ctypes.c_int64 * 8)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_ if n != "reserved"}
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def load_library():
+    """Load libsaber.so (building it first only if it does not exist) and declare the signatures."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build()
+    L = ctypes.CDLL(_build.LIB)
+    vp, i32, i64, u32, u64, f32 = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32,
+                                   ctypes.c_uint64, ctypes.c_float)
+    sig = {
+        "saber_options_default": (None, [vp]),
+        "saber_init_ex": (ctypes.c_int, [vp, vp, vp, i64, i32, i32, f32, f32, u64, vp]),
+        "saber_init": (ctypes.c_int, [vp, vp, vp, i64, i32, i32, f32, f32, u64]),
+        "saber_iterate": (ctypes.c_int, [vp, i32]),
+        "saber_counts_nnz": (ctypes.c_int, [vp, vp]),
+        "saber_counts": (ctypes.c_int, [vp, vp, vp, vp, vp, vp]),
+        "saber_loglik": (ctypes.c_int, [vp, vp]),
+        "saber_free": (None, [vp]),
+        "saber_last_error": (ctypes.c_char_p, []),
+        "saber_get_z": (ctypes.c_int, [vp, vp]),
+        "saber_set_z": (ctypes.c_int, [vp, vp, u32]),
+        "saber_get_iteration": (ctypes.c_int, [vp, vp]),
+        "saber_token_probs": (ctypes.c_int, [vp, vp, i64, vp, vp, vp]),
+        "saber_get_phi": (ctypes.c_int, [vp, vp, i32, vp, vp]),
+        "saber_get_stats": (ctypes.c_int, [vp, vp]),
+        "saber_reset_stats": (ctypes.c_int, [vp]),
+        "saber_get_stream": (ctypes.c_int, [vp, vp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(L, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = L
+    return L
+
+
+def _check(rc):
+    if rc != SABER_OK:
+        raise SaberError(rc, load_library().saber_last_error().decode("utf-8", "replace"))
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data
+
+
+def options_default() -> Options:
+    o = Options()
+    load_library().saber_options_default(ctypes.addressof(o))
+    return o
+
+
+class Saber:
+    """One sampler context.  Method names follow the C ABI (saber_init -> constructor)."""
+
+    def __init__(self, doc_ptr, word_ids, V, K, alpha, beta, seed, **opts):
+        L = load_library()
+        self._doc_ptr = np.ascontiguousarray(doc_ptr, dtype=np.int64)
+        self._word_ids = np.ascontiguousarray(word_ids, dtype=np.int32)
+        self.D = int(self._doc_ptr.size - 1); self.V = int(V); self.K = int(K)
+        self.T = int(self._doc_ptr[-1]) if self._doc_ptr.size else 0
+        o = options_default()
+        for k, v in opts.items():
+            if not hasattr(o, k):
+                raise TypeError("unknown option %r" % k)
+            setattr(o, k, int(v))
+        h = ctypes.c_void_p()
+        self._h = None
+        _check(L.saber_init_ex(ctypes.addressof(h), _ptr(self._doc_ptr), _ptr(self._word_ids), self.D, self.V, self.K,
+                               np.float32(alpha), np.float32(beta), int(seed), ctypes.addressof(o)))
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            load_library().saber_free(self._h); self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def iterate(self, n=1):
+        _check(load_library().saber_iterate(self._h, int(n)))
+
+    def counts_nnz(self) -> int:
+        n = ctypes.c_int64()
+        _check(load_library().saber_counts_nnz(self._h, ctypes.addressof(n)))
+        return n.value
+
+    def counts(self, want_cd=True, want_cwk=True, want_ck=True):
+        """Returns (cd_row_ptr, cd_topic, cd_count, cwk[V,K], ck[K]); skipped parts are None."""
+        cd_ptr = topic = count = cwk = ck = None
+        if want_cd:
+            nnz = self.counts_nnz()
+            cd_ptr = np.zeros(self.D + 1, dtype=np.int64)
+            topic = np.zeros(nnz, dtype=np.int32); count = np.zeros(nnz, dtype=np.int32)
+        if want_cwk:
+            cwk = np.zeros((self.V, self.K), dtype=np.int32)
+        if want_ck:
+            ck = np.zeros(self.K, dtype=np.int64)
+        _check(load_library().saber_counts(self._h, _ptr(cd_ptr), _ptr(topic), _ptr(count), _ptr(cwk), _ptr(ck)))
+        return cd_ptr, topic, count, cwk, ck
+
+    def loglik(self) -> float:
+        v = ctypes.c_double()
+        _check(load_library().saber_loglik(self._h, ctypes.addressof(v)))
+        return v.value
+
+    def get_z(self):
+        z = np.zeros(self.T, dtype=np.int32)
+        _check(load_library().saber_get_z(self._h, _ptr(z)))
+        return z
+
+    def set_z(self, z, iteration=0):
+        z = np.ascontiguousarray(z, dtype=np.int32)
+        if z.size != self.T:
+            raise ValueError("z must hold T values")
+        _check(load_library().saber_set_z(self._h, _ptr(z), int(iteration)))
+
+    def get_iteration(self) -> int:
+        v = ctypes.c_uint32()
+        _check(load_library().saber_get_iteration(self._h, ctypes.addressof(v)))
+        return v.value
+
+    def token_probs(self, tok):
+        tok = np.ascontiguousarray(tok, dtype=np.int64)
+        S = np.zeros(tok.size, dtype=np.float32); Q = np.zeros_like(S); p = np.zeros_like(S)
+        _check(load_library().saber_token_probs(self._h, _ptr(tok), tok.size, _ptr(S), _ptr(Q), _ptr(p)))
+        return S, Q, p
+
+    def get_phi(self, words):
+        words = np.ascontiguousarray(words, dtype=np.int32)
+        phi = np.zeros((words.size, self.K), dtype=np.float32); prefix = np.zeros_like(phi)
+        _check(load_library().saber_get_phi(self._h, _ptr(words), words.size, _ptr(phi), _ptr(prefix)))
+        return phi, prefix
+
+    def get_stats(self) -> dict:
+        s = Stats()
+        _check(load_library().saber_get_stats(self._h, ctypes.addressof(s)))
+        return s.as_dict()
+
+    def reset_stats(self):
+        _check(load_library().saber_reset_stats(self._h))
+
+    def get_stream(self) -> int:
+        v = ctypes.c_void_p()
+        _check(load_library().saber_get_stream(self._h, ctypes.addressof(v)))
+        return v.value or 0

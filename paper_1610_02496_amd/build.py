@@ -1,0 +1,43 @@
+"""Build the HIP library (libsaber.so) for gfx950 with hipcc, in-tree."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libsaber.so")
+SOURCES = [os.path.join(CSRC, "saber.hip")]
+DEPS = SOURCES + [os.path.join(CSRC, "saber_kernels.hpp"),
+                  os.path.join(os.path.dirname(HERE), "include", "saber.h")]
+
+HIPCC_FLAGS = [
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "-ffp-contract=off",                               # products and sums round separately, as documented
+    "-fhip-fp32-correctly-rounded-divide-sqrt",        # Eq. 2's division must be IEEE-rounded
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-Wall", "-Wno-unused-command-line-argument",
+]
+
+
+def stale() -> bool:
+    return not os.path.exists(LIB) or any(os.path.getmtime(LIB) < os.path.getmtime(d) for d in DEPS)
+
+
+def build(force: bool = True) -> str:
+    """Compile libsaber.so.  ``force=False`` rebuilds only when a source is newer than the library."""
+    if not force and not stale():
+        return LIB
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    tmp = LIB + ".tmp%d" % os.getpid()
+    cmd = [hipcc] + HIPCC_FLAGS + ["-o", tmp] + SOURCES
+    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    out = "\n".join(ln for ln in proc.stdout.splitlines() if "is not a recognized feature" not in ln)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + out)
+    os.replace(tmp, LIB)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build())

@@ -1,0 +1,688 @@
+// Host side of the C ABI declared in include/saber.h: validation, the device data layout, and the
+// per-iteration launch sequence of Alg. 1.  Every step of the path runs in the kernels of
+// saber_kernels.hpp; nothing here computes counts or samples on the CPU.
+#include "saber_kernels.hpp"
+#include "../../include/saber.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+using namespace saber;
+
+// ------------------------------------------------------------------------------------------------
+// errors
+// ------------------------------------------------------------------------------------------------
+static thread_local char g_err[512] = "";
+static int fail(int code, const char *fmt, ...) {
+    va_list ap; va_start(ap, fmt); vsnprintf(g_err, sizeof(g_err), fmt, ap); va_end(ap);
+    return code;
+}
+#define HIP_TRY(expr)                                                                                     \
+    do {                                                                                                  \
+        hipError_t e_ = (expr);                                                                           \
+        if (e_ != hipSuccess)                                                                             \
+            return fail(e_ == hipErrorOutOfMemory ? SABER_ENOMEM : SABER_EDEVICE, "%s failed: %s (%s:%d)", \
+                        #expr, hipGetErrorString(e_), __FILE__, __LINE__);                                \
+    } while (0)
+#define SABER_TRY(expr) do { int rc_ = (expr); if (rc_ != SABER_OK) return rc_; } while (0)
+
+extern "C" const char *saber_last_error(void) { return g_err; }
+
+// ------------------------------------------------------------------------------------------------
+// context
+// ------------------------------------------------------------------------------------------------
+struct Chunk {
+    int64_t d0 = 0, d1 = 0;   // document range
+    int64_t t0 = 0, ntok = 0; // canonical token range [t0, t0+ntok)
+    int64_t tile0 = 0, ntiles = 0, words_present = 0;
+};
+
+constexpr int kMaxTimedIters = 32;
+enum { EV_BEGIN = 0, EV_SAMPLE, EV_DZ, EV_CK, EV_PHI, EV_PER_ITER };
+
+struct saber_ctx {
+    int64_t D = 0, T = 0;
+    int32_t V = 0, K = 0, Kpad = 0, n3pad = 0, nwords = 0;
+    float alpha = 0, beta = 0, vbeta = 0;
+    uint64_t seed = 0;
+    uint32_t iter = 0, topic_bits = 0, topic_mask = 0;
+    bool z16 = false, staged = false;
+    saber_options opt{};
+    double ll_const = 0.0;            // sum_d L_d ln(L_d + K alpha)
+    int64_t max_doc_len = 0;
+    hipStream_t stream = nullptr;
+    // device arrays
+    void *z = nullptr;                // [T] uint16 or int32, canonical (document) order
+    int32_t *tok_doc = nullptr;       // [T] word-major inside every chunk
+    uint32_t *tok_t = nullptr;        // [T]
+    Tile *tiles = nullptr;
+    uint2 *docrec = nullptr;          // [D]
+    uint32_t *cd_ent = nullptr;       // [cd_cap]
+    int64_t cd_cap = 0;
+    int64_t *doc_ptr = nullptr;       // [D+1]
+    int32_t *short_docs = nullptr, *long_docs = nullptr;
+    int64_t n_short = 0, n_long = 0;
+    int32_t *cwk = nullptr;           // [V][Kpad]
+    uint32_t *ck = nullptr;           // [K]
+    float *phi = nullptr, *prefix = nullptr, *l3 = nullptr, *sumphi = nullptr;
+    unsigned long long *counters = nullptr; // [kMaxTimedIters] dense-branch counters, one per iteration slot
+    double *ll_partial = nullptr;     // [max tiles per chunk]
+    std::vector<Chunk> chunks;
+    int64_t total_tiles = 0, max_chunk_tiles = 0;
+    // measurement
+    hipEvent_t ev[kMaxTimedIters * EV_PER_ITER] = {};
+    bool have_events = false;
+    saber_stats stats{};
+    std::vector<int64_t> doc_len;     // host copy of the document lengths (statistics only)
+};
+
+template <typename T>
+static int dev_alloc(T **p, size_t n) {
+    *p = nullptr;
+    HIP_TRY(hipMalloc((void **)p, std::max<size_t>(n, 1) * sizeof(T)));
+    return SABER_OK;
+}
+static void dev_free(void *p) { if (p) (void)hipFree(p); }
+
+static inline int grid_for(int64_t n, int block, int cap = 65535 * 16) {
+    int64_t g = (n + block - 1) / block;
+    return (int)std::max<int64_t>(1, std::min<int64_t>(g, cap));
+}
+
+extern "C" void saber_options_default(saber_options *opt) {
+    if (!opt) return;
+    memset(opt, 0, sizeof(*opt));
+    opt->n_chunks = 1; opt->block_threads = 256; opt->tile_tokens = 2048; opt->stage_phi = 1; opt->profile = 0;
+    opt->long_doc_tokens = 512; opt->dz_lds_entries = 8192;
+}
+
+extern "C" void saber_free(saber_ctx *c) {
+    if (!c) return;
+    if (c->stream) (void)hipStreamSynchronize(c->stream);
+    dev_free(c->z); dev_free(c->tok_doc); dev_free(c->tok_t); dev_free(c->tiles); dev_free(c->docrec);
+    dev_free(c->cd_ent); dev_free(c->doc_ptr); dev_free(c->short_docs); dev_free(c->long_docs); dev_free(c->cwk);
+    dev_free(c->ck); dev_free(c->phi); dev_free(c->prefix); dev_free(c->l3); dev_free(c->sumphi);
+    dev_free(c->counters); dev_free(c->ll_partial);
+    if (c->have_events) for (auto &e : c->ev) if (e) (void)hipEventDestroy(e);
+    if (c->stream) (void)hipStreamDestroy(c->stream);
+    delete c;
+}
+
+// ------------------------------------------------------------------------------------------------
+// launch helpers
+// ------------------------------------------------------------------------------------------------
+static EStepParams make_params(saber_ctx *c, const Chunk &ch) {
+    EStepParams p{};
+    p.tiles = c->tiles + ch.tile0;
+    p.tok_doc = c->tok_doc + ch.t0; p.tok_t = c->tok_t + ch.t0;
+    p.docrec = c->docrec; p.cd_ent = c->cd_ent;
+    p.phi = c->phi; p.prefix = c->prefix; p.l3 = c->l3; p.sumphi = c->sumphi;
+    p.z = c->z; p.cwk = c->cwk;
+    p.t_base = ch.t0; p.K = c->K; p.Kpad = c->Kpad; p.n3pad = c->n3pad;
+    p.topic_bits = c->topic_bits; p.topic_mask = c->topic_mask; p.alpha = c->alpha;
+    p.seed_lo = (uint32_t)c->seed; p.seed_hi = (uint32_t)(c->seed >> 32); p.iter = c->iter;
+    return p;
+}
+
+template <int MODE>
+static int launch_estep(saber_ctx *c, const Chunk &ch, EStepParams &p) {
+    if (ch.ntiles == 0) return SABER_OK;
+    const dim3 grid((unsigned)ch.ntiles), block((unsigned)c->opt.block_threads);
+    const size_t lds = c->staged ? (size_t)c->Kpad * sizeof(float) : 0;
+    if (c->staged) {
+        if (c->z16) hipLaunchKernelGGL((estep_kernel<MODE, true, uint16_t>), grid, block, lds, c->stream, p);
+        else hipLaunchKernelGGL((estep_kernel<MODE, true, int32_t>), grid, block, lds, c->stream, p);
+    } else {
+        if (c->z16) hipLaunchKernelGGL((estep_kernel<MODE, false, uint16_t>), grid, block, lds, c->stream, p);
+        else hipLaunchKernelGGL((estep_kernel<MODE, false, int32_t>), grid, block, lds, c->stream, p);
+    }
+    HIP_TRY(hipGetLastError());
+    return SABER_OK;
+}
+
+static int launch_count_dz(saber_ctx *c) {
+    for (int pass = 0; pass < 2; pass++) {
+        const int64_t n = pass == 0 ? c->n_short : c->n_long;
+        const int32_t *list = pass == 0 ? c->short_docs : c->long_docs;
+        const int block = pass == 0 ? 64 : 256;
+        if (n == 0) continue;
+        // LDS: bitmap + rank prefix (2 * nwords) + the row under construction; a short document's row has at
+        // most long_doc_tokens entries, so its workgroup asks for no more than that
+        const int budget = std::max(0, (int)((63 * 1024 - 8 * (int64_t)c->nwords) / 4));
+        const int want = pass == 0 ? std::min(c->opt.long_doc_tokens, c->K) : c->opt.dz_lds_entries;
+        const int entries = std::min(want, budget);
+        const size_t lds = ((size_t)2 * c->nwords + (size_t)entries) * sizeof(uint32_t);
+        if (lds > 63 * 1024) {   // K > 2^17: the two bitmap arrays alone pass 64 KB; gfx950 has 160 KB per workgroup
+            const void *fn = c->z16 ? (const void *)count_dz_kernel<uint16_t> : (const void *)count_dz_kernel<int32_t>;
+            HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        }
+        const dim3 grid((unsigned)n), blk((unsigned)block);
+        if (c->z16)
+            hipLaunchKernelGGL((count_dz_kernel<uint16_t>), grid, blk, lds, c->stream, list, c->doc_ptr,
+                               (const uint16_t *)c->z, c->docrec, c->cd_ent, c->K, c->topic_bits, c->nwords,
+                               entries);
+        else
+            hipLaunchKernelGGL((count_dz_kernel<int32_t>), grid, blk, lds, c->stream, list, c->doc_ptr,
+                               (const int32_t *)c->z, c->docrec, c->cd_ent, c->K, c->topic_bits, c->nwords,
+                               entries);
+        HIP_TRY(hipGetLastError());
+    }
+    return SABER_OK;
+}
+
+// nnz(A) and sum_d K_d * L_d (the row entries the next E-step will read) into two device counters
+static int launch_row_stats(saber_ctx *c, unsigned long long *out2) {
+    if (c->D == 0) return SABER_OK;
+    hipLaunchKernelGGL(row_stats_kernel, dim3(grid_for(c->D, 256, 4096)), dim3(256), 0, c->stream, c->docrec,
+                       c->doc_ptr, c->D, out2);
+    HIP_TRY(hipGetLastError());
+    return SABER_OK;
+}
+
+static int launch_topic_totals(saber_ctx *c) {
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for(c->K, 256)), dim3(256), 0, c->stream, c->ck, 0u, (size_t)c->K);
+    HIP_TRY(hipGetLastError());
+    if (c->T == 0) return SABER_OK;
+    const int use_lds = (size_t)c->K * 4 <= 60 * 1024;
+    const int64_t per_block = 65536;
+    const int64_t nblocks = (c->T + per_block - 1) / per_block;
+    const size_t lds = use_lds ? (size_t)c->K * 4 : 0;
+    if (c->z16)
+        hipLaunchKernelGGL((topic_totals_kernel<uint16_t>), dim3((unsigned)nblocks), dim3(256), lds, c->stream,
+                           (const uint16_t *)c->z, c->T, per_block, c->ck, c->K, use_lds);
+    else
+        hipLaunchKernelGGL((topic_totals_kernel<int32_t>), dim3((unsigned)nblocks), dim3(256), lds, c->stream,
+                           (const int32_t *)c->z, c->T, per_block, c->ck, c->K, use_lds);
+    HIP_TRY(hipGetLastError());
+    return SABER_OK;
+}
+
+static int launch_phi(saber_ctx *c) {
+    hipLaunchKernelGGL(phi_prefix_kernel, dim3((unsigned)c->V), dim3(256), 0, c->stream, c->cwk, c->ck, c->phi,
+                       c->prefix, c->l3, c->sumphi, c->K, c->Kpad, c->n3pad, c->beta, c->vbeta, 1);
+    HIP_TRY(hipGetLastError());
+    return SABER_OK;
+}
+
+// B from scratch out of z (after init / set_z).  B must be all zero on entry (the Bhat kernel leaves it so).
+static int launch_count_vz(saber_ctx *c) {
+    for (const Chunk &ch : c->chunks) {
+        if (ch.ntiles == 0) continue;
+        if (c->z16)
+            hipLaunchKernelGGL((count_vz_kernel<uint16_t>), dim3((unsigned)ch.ntiles), dim3(256), 0, c->stream,
+                               c->tiles + ch.tile0, c->tok_t + ch.t0, (const uint16_t *)c->z, ch.t0, c->cwk, c->Kpad);
+        else
+            hipLaunchKernelGGL((count_vz_kernel<int32_t>), dim3((unsigned)ch.ntiles), dim3(256), 0, c->stream,
+                               c->tiles + ch.tile0, c->tok_t + ch.t0, (const int32_t *)c->z, ch.t0, c->cwk, c->Kpad);
+        HIP_TRY(hipGetLastError());
+    }
+    return SABER_OK;
+}
+
+// The M-step after the assignments changed outside an E-step: all four rebuilds of Alg. 1.
+static int full_mstep(saber_ctx *c) {
+    SABER_TRY(launch_count_dz(c));
+    SABER_TRY(launch_count_vz(c));
+    SABER_TRY(launch_topic_totals(c));
+    SABER_TRY(launch_phi(c));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    return SABER_OK;
+}
+
+// Workload numbers of the E-step that will read the current A: nnz(A) and sum_d K_d * L_d.
+static int refresh_workload_stats(saber_ctx *c) {
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, c->stream, (uint32_t *)c->counters, 0u, (size_t)8);
+    HIP_TRY(hipGetLastError());
+    SABER_TRY(launch_row_stats(c, c->counters + 1));
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    unsigned long long h[3];
+    HIP_TRY(hipMemcpy(h, c->counters, sizeof(h), hipMemcpyDeviceToHost));
+    c->stats.nnz_cd = (int64_t)h[1]; c->stats.next_row_entries = (int64_t)h[2];
+    return SABER_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// saber_init
+// ------------------------------------------------------------------------------------------------
+static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) {
+    const int64_t D = c->D, T = c->T; const int32_t V = c->V, K = c->K;
+    HIP_TRY(hipStreamCreate(&c->stream));
+    if (c->opt.profile) {
+        for (auto &e : c->ev) HIP_TRY(hipEventCreate(&e));
+        c->have_events = true;
+    }
+    // ---- chunks: contiguous document ranges of about equal token count (Sec. 3.1.2) ----
+    const int nch = std::max(1, c->opt.n_chunks);
+    c->chunks.clear();
+    {
+        int64_t d = 0;
+        for (int i = 0; i < nch; i++) {
+            Chunk ch; ch.d0 = d; ch.t0 = doc_ptr[d];
+            if (i == nch - 1) d = D;
+            else {
+                const int64_t target = (T * (int64_t)(i + 1)) / nch;
+                while (d < D && doc_ptr[d + 1] <= target) d++;
+            }
+            ch.d1 = d; ch.ntok = doc_ptr[d] - ch.t0;
+            if (ch.d1 > ch.d0) c->chunks.push_back(ch);
+        }
+    }
+    // ---- word-major token arrays and tiles per chunk (host counting sort; layout only) ----
+    std::vector<int32_t> h_tok_doc((size_t)std::max<int64_t>(T, 1));
+    std::vector<uint32_t> h_tok_t((size_t)std::max<int64_t>(T, 1));
+    std::vector<Tile> h_tiles;
+    std::vector<int64_t> wcount((size_t)V + 1);
+    const int tile_tokens = c->opt.tile_tokens;
+    for (Chunk &ch : c->chunks) {
+        std::fill(wcount.begin(), wcount.end(), 0);
+        for (int64_t t = ch.t0; t < ch.t0 + ch.ntok; t++) wcount[(size_t)word_ids[t] + 1]++;
+        for (int32_t v = 0; v < V; v++) wcount[(size_t)v + 1] += wcount[(size_t)v];
+        const size_t first_tile = h_tiles.size();
+        for (int32_t v = 0; v < V; v++) {
+            const int64_t b = wcount[(size_t)v], e = wcount[(size_t)v + 1];
+            if (e > b) ch.words_present++;
+            for (int64_t s = b; s < e; s += tile_tokens)
+                h_tiles.push_back(Tile{v, (int32_t)s, (int32_t)std::min<int64_t>(tile_tokens, e - s), 0});
+        }
+        for (int64_t d = ch.d0; d < ch.d1; d++)
+            for (int64_t t = doc_ptr[d]; t < doc_ptr[d + 1]; t++) {
+                const int64_t pos = ch.t0 + wcount[(size_t)word_ids[t]]++;
+                h_tok_doc[(size_t)pos] = (int32_t)d; h_tok_t[(size_t)pos] = (uint32_t)(t - ch.t0);
+            }
+        // heavy tiles first so the tail of the launch is made of small ones (Sec. 3.4)
+        std::stable_sort(h_tiles.begin() + (ptrdiff_t)first_tile, h_tiles.end(),
+                         [](const Tile &a, const Tile &b) { return a.count > b.count; });
+        ch.tile0 = (int64_t)first_tile; ch.ntiles = (int64_t)(h_tiles.size() - first_tile);
+        c->max_chunk_tiles = std::max(c->max_chunk_tiles, ch.ntiles);
+    }
+    c->total_tiles = (int64_t)h_tiles.size();
+    // ---- rows of A: fixed, 128-byte aligned slots of capacity min(L_d, K) (Sec. 3.4 aligns rows likewise) ----
+    std::vector<uint2> h_rec((size_t)std::max<int64_t>(D, 1));
+    std::vector<int32_t> h_short, h_long;
+    c->doc_len.resize((size_t)D);
+    int64_t units = 0; double llc = 0.0;
+    for (int64_t d = 0; d < D; d++) {
+        const int64_t len = doc_ptr[d + 1] - doc_ptr[d];
+        c->doc_len[(size_t)d] = len;
+        if (units > 0xffffffffll) return fail(SABER_ERANGE, "rows of A exceed 2^32 * 128 bytes");
+        h_rec[(size_t)d] = make_uint2((uint32_t)units, 0u);
+        units += (std::min<int64_t>(len, K) + 31) / 32;
+        (len > c->opt.long_doc_tokens ? h_long : h_short).push_back((int32_t)d);
+        if (len > 0) llc += (double)len * std::log((double)len + (double)K * (double)c->alpha);
+    }
+    c->ll_const = llc; c->cd_cap = units * 32;
+    c->n_short = (int64_t)h_short.size(); c->n_long = (int64_t)h_long.size();
+
+    // ---- device memory ----
+    const size_t vk = (size_t)V * (size_t)c->Kpad;
+    if (c->z16) SABER_TRY(dev_alloc((uint16_t **)&c->z, (size_t)T)); else SABER_TRY(dev_alloc((int32_t **)&c->z, (size_t)T));
+    SABER_TRY(dev_alloc(&c->tok_doc, (size_t)T)); SABER_TRY(dev_alloc(&c->tok_t, (size_t)T));
+    SABER_TRY(dev_alloc(&c->tiles, h_tiles.size())); SABER_TRY(dev_alloc(&c->docrec, (size_t)D));
+    SABER_TRY(dev_alloc(&c->cd_ent, (size_t)c->cd_cap)); SABER_TRY(dev_alloc(&c->doc_ptr, (size_t)D + 1));
+    SABER_TRY(dev_alloc(&c->short_docs, h_short.size())); SABER_TRY(dev_alloc(&c->long_docs, h_long.size()));
+    SABER_TRY(dev_alloc(&c->cwk, vk)); SABER_TRY(dev_alloc(&c->ck, (size_t)K));
+    SABER_TRY(dev_alloc(&c->phi, vk)); SABER_TRY(dev_alloc(&c->prefix, vk));
+    SABER_TRY(dev_alloc(&c->l3, (size_t)V * (size_t)c->n3pad)); SABER_TRY(dev_alloc(&c->sumphi, (size_t)V));
+    SABER_TRY(dev_alloc(&c->counters, (size_t)kMaxTimedIters * 3));
+    SABER_TRY(dev_alloc(&c->ll_partial, (size_t)std::max<int64_t>(c->max_chunk_tiles, 1)));
+    if (T) {
+        HIP_TRY(hipMemcpy(c->tok_doc, h_tok_doc.data(), sizeof(int32_t) * (size_t)T, hipMemcpyHostToDevice));
+        HIP_TRY(hipMemcpy(c->tok_t, h_tok_t.data(), sizeof(uint32_t) * (size_t)T, hipMemcpyHostToDevice));
+    }
+    if (!h_tiles.empty()) HIP_TRY(hipMemcpy(c->tiles, h_tiles.data(), sizeof(Tile) * h_tiles.size(), hipMemcpyHostToDevice));
+    if (D) HIP_TRY(hipMemcpy(c->docrec, h_rec.data(), sizeof(uint2) * (size_t)D, hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(c->doc_ptr, doc_ptr, sizeof(int64_t) * ((size_t)D + 1), hipMemcpyHostToDevice));
+    if (!h_short.empty()) HIP_TRY(hipMemcpy(c->short_docs, h_short.data(), sizeof(int32_t) * h_short.size(), hipMemcpyHostToDevice));
+    if (!h_long.empty()) HIP_TRY(hipMemcpy(c->long_docs, h_long.data(), sizeof(int32_t) * h_long.size(), hipMemcpyHostToDevice));
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for((int64_t)vk, 256, 8192)), dim3(256), 0, c->stream, (uint32_t *)c->cwk, 0u, vk);
+    HIP_TRY(hipGetLastError());
+
+    // ---- iteration 0: Philox assignment, then the M-step ----
+    if (T) {
+        if (c->z16)
+            hipLaunchKernelGGL((init_z_kernel<uint16_t>), dim3(grid_for(T, 256, 8192)), dim3(256), 0, c->stream,
+                               (uint16_t *)c->z, T, (uint32_t)K, (uint32_t)c->seed, (uint32_t)(c->seed >> 32));
+        else
+            hipLaunchKernelGGL((init_z_kernel<int32_t>), dim3(grid_for(T, 256, 8192)), dim3(256), 0, c->stream,
+                               (int32_t *)c->z, T, (uint32_t)K, (uint32_t)c->seed, (uint32_t)(c->seed >> 32));
+        HIP_TRY(hipGetLastError());
+    }
+    SABER_TRY(full_mstep(c));
+    SABER_TRY(refresh_workload_stats(c));
+    c->stats.tokens = T; c->stats.tiles = c->total_tiles;
+    c->stats.words_present = 0;
+    for (const Chunk &ch : c->chunks) c->stats.words_present += ch.words_present;
+    return SABER_OK;
+}
+
+extern "C" int saber_init_ex(saber_ctx **out, const int64_t *doc_ptr, const int32_t *word_ids, int64_t D, int32_t V,
+                             int32_t K, float alpha, float beta, uint64_t seed, const saber_options *opt_in) {
+    if (out) *out = nullptr;
+    if (!out || !doc_ptr) return fail(SABER_EINVAL, "saber_init: null argument");
+    if (D < 0 || V < 1 || K < 1) return fail(SABER_EINVAL, "saber_init: need D >= 0, V >= 1, K >= 1");
+    if (!(alpha > 0.f) || !(beta > 0.f) || !std::isfinite(alpha) || !std::isfinite(beta))
+        return fail(SABER_EINVAL, "saber_init: alpha and beta must be positive and finite");
+    if (K > 262144) return fail(SABER_ERANGE, "saber_init: K = %d exceeds 262144 (three tree levels of width 64)", K);
+    if (D > 0x7fffffffll) return fail(SABER_ERANGE, "saber_init: D exceeds 2^31 - 1");
+    if (doc_ptr[0] != 0) return fail(SABER_EINVAL, "saber_init: doc_ptr[0] must be 0");
+    int64_t maxlen = 0;
+    for (int64_t d = 0; d < D; d++) {
+        if (doc_ptr[d + 1] < doc_ptr[d]) return fail(SABER_EINVAL, "saber_init: doc_ptr decreases at document %lld", (long long)d);
+        maxlen = std::max(maxlen, doc_ptr[d + 1] - doc_ptr[d]);
+    }
+    const int64_t T = doc_ptr[D];
+    if (T >= (1ll << 31)) return fail(SABER_ERANGE, "saber_init: T = %lld tokens; this build handles T < 2^31", (long long)T);
+    if (T > 0 && !word_ids) return fail(SABER_EINVAL, "saber_init: word_ids is null");
+    for (int64_t t = 0; t < T; t++)
+        if (word_ids[t] < 0 || word_ids[t] >= V)
+            return fail(SABER_EINVAL, "saber_init: word id %d at token %lld is outside [0,%d)", word_ids[t], (long long)t, V);
+    uint32_t bits = 1; while ((1u << bits) < (uint32_t)K) bits++;
+    if (maxlen >= (1ll << (32 - bits)))
+        return fail(SABER_ERANGE, "saber_init: longest document (%lld tokens) does not fit the %u count bits left by K = %d",
+                    (long long)maxlen, 32 - bits, K);
+
+    saber_options opt; saber_options_default(&opt);
+    if (opt_in) {
+        if (opt_in->n_chunks > 0) opt.n_chunks = opt_in->n_chunks;
+        if (opt_in->block_threads > 0) opt.block_threads = opt_in->block_threads;
+        if (opt_in->tile_tokens > 0) opt.tile_tokens = opt_in->tile_tokens;
+        if (opt_in->long_doc_tokens > 0) opt.long_doc_tokens = opt_in->long_doc_tokens;
+        if (opt_in->dz_lds_entries > 0) opt.dz_lds_entries = opt_in->dz_lds_entries;
+        opt.stage_phi = opt_in->stage_phi; opt.profile = opt_in->profile;
+        if (opt_in->stage_phi < 0) opt.stage_phi = 1;
+    }
+    if (opt.block_threads % 64 || opt.block_threads < 64 || opt.block_threads > 1024)
+        return fail(SABER_EINVAL, "saber_init: block_threads must be a multiple of 64 in [64,1024]");
+    if (opt.n_chunks > 65536) return fail(SABER_EINVAL, "saber_init: n_chunks too large");
+    if (opt.dz_lds_entries > 12288) return fail(SABER_EINVAL, "saber_init: dz_lds_entries must not exceed 12288");
+    if ((int64_t)opt.n_chunks > std::max<int64_t>(D, 1)) opt.n_chunks = (int32_t)std::max<int64_t>(D, 1);
+
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return fail(SABER_EDEVICE, "saber_init: no HIP device available");
+
+    saber_ctx *c = new (std::nothrow) saber_ctx();
+    if (!c) return fail(SABER_ENOMEM, "saber_init: out of host memory");
+    c->D = D; c->T = T; c->V = V; c->K = K; c->alpha = alpha; c->beta = beta; c->seed = seed; c->opt = opt;
+    c->Kpad = (K + 63) / 64 * 64;
+    c->n3pad = ((c->Kpad / 64) + 63) / 64 * 64;
+    c->nwords = (K + 31) / 32;
+    c->topic_bits = bits; c->topic_mask = (1u << bits) - 1u;
+    c->z16 = K <= 65536;
+    c->staged = opt.stage_phi && (size_t)c->Kpad * sizeof(float) <= 60 * 1024;
+    c->vbeta = (float)V * beta;
+    c->max_doc_len = maxlen;
+    int rc;
+    try { rc = build(c, doc_ptr, word_ids); }
+    catch (const std::bad_alloc &) { rc = fail(SABER_ENOMEM, "saber_init: out of host memory"); }
+    if (rc != SABER_OK) { saber_free(c); return rc; }
+    *out = c;
+    return SABER_OK;
+}
+
+extern "C" int saber_init(saber_ctx **out, const int64_t *doc_ptr, const int32_t *word_ids, int64_t D, int32_t V,
+                          int32_t K, float alpha, float beta, uint64_t seed) {
+    return saber_init_ex(out, doc_ptr, word_ids, D, V, K, alpha, beta, seed, nullptr);
+}
+
+// ------------------------------------------------------------------------------------------------
+// saber_iterate
+// ------------------------------------------------------------------------------------------------
+extern "C" int saber_iterate(saber_ctx *c, int32_t n) {
+    if (!c) return fail(SABER_EINVAL, "saber_iterate: null context");
+    if (n < 0) return fail(SABER_EINVAL, "saber_iterate: n must be >= 0");
+    const bool prof = c->opt.profile != 0;
+    int32_t done = 0;
+    while (done < n) {
+        const int batch = std::min<int32_t>(n - done, kMaxTimedIters);
+        // per-iteration device counters: {dense-branch tokens, nnz(A), sum_d K_d L_d}
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, c->stream, (uint32_t *)c->counters, 0u,
+                           (size_t)kMaxTimedIters * 6);
+        HIP_TRY(hipGetLastError());
+        for (int b = 0; b < batch; b++) {
+            hipEvent_t *ev = c->ev + (size_t)b * EV_PER_ITER;
+            c->iter++;
+            if (prof) HIP_TRY(hipEventRecord(ev[EV_BEGIN], c->stream));
+            // E-step: z <- Sample(A_d, Bhat_v, Q_v, T_v) for every token; B accumulates as a by-product
+            for (const Chunk &ch : c->chunks) {
+                EStepParams p = make_params(c, ch);
+                p.n_dense = c->counters + 3 * b;
+                SABER_TRY(launch_estep<MODE_SAMPLE>(c, ch, p));
+            }
+            if (prof) HIP_TRY(hipEventRecord(ev[EV_SAMPLE], c->stream));
+            // M-step
+            SABER_TRY(launch_count_dz(c));
+            if (prof) HIP_TRY(hipEventRecord(ev[EV_DZ], c->stream));
+            SABER_TRY(launch_topic_totals(c));
+            if (prof) HIP_TRY(hipEventRecord(ev[EV_CK], c->stream));
+            SABER_TRY(launch_phi(c));
+            if (prof) HIP_TRY(hipEventRecord(ev[EV_PHI], c->stream));
+            SABER_TRY(launch_row_stats(c, c->counters + 3 * b + 1));
+        }
+        HIP_TRY(hipStreamSynchronize(c->stream));
+        unsigned long long h[kMaxTimedIters * 3];
+        HIP_TRY(hipMemcpy(h, c->counters, sizeof(h), hipMemcpyDeviceToHost));
+        for (int b = 0; b < batch; b++) {
+            // the E-step of this iteration read the rows counted at the end of the previous one
+            c->stats.sum_tokens += c->T;
+            c->stats.sum_tokens_dense += (int64_t)h[3 * b];
+            c->stats.sum_row_entries += c->stats.next_row_entries;
+            c->stats.nnz_cd = (int64_t)h[3 * b + 1];
+            c->stats.next_row_entries = (int64_t)h[3 * b + 2];
+            if (prof) {
+                hipEvent_t *ev = c->ev + (size_t)b * EV_PER_ITER;
+                float ms[4], tot;
+                for (int s = 0; s < 4; s++) HIP_TRY(hipEventElapsedTime(&ms[s], ev[s], ev[s + 1]));
+                HIP_TRY(hipEventElapsedTime(&tot, ev[EV_BEGIN], ev[EV_PHI]));
+                c->stats.ms_sample += ms[0]; c->stats.ms_count_dz += ms[1]; c->stats.ms_ck += ms[2];
+                c->stats.ms_phi += ms[3]; c->stats.ms_total += tot;
+                c->stats.sample_launches += (int64_t)c->chunks.size();
+            }
+            c->stats.iterations++;
+        }
+        done += batch;
+    }
+    return SABER_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// outputs
+// ------------------------------------------------------------------------------------------------
+extern "C" int saber_counts_nnz(saber_ctx *c, int64_t *nnz) {
+    if (!c || !nnz) return fail(SABER_EINVAL, "saber_counts_nnz: null argument");
+    std::vector<uint2> rec((size_t)c->D);
+    if (c->D) HIP_TRY(hipMemcpy(rec.data(), c->docrec, sizeof(uint2) * (size_t)c->D, hipMemcpyDeviceToHost));
+    int64_t s = 0; for (auto &r : rec) s += r.y;
+    *nnz = s;
+    return SABER_OK;
+}
+
+extern "C" int saber_counts(saber_ctx *c, int64_t *cd_row_ptr, int32_t *cd_topic, int32_t *cd_count, int32_t *cwk,
+                            int64_t *ck) {
+    if (!c) return fail(SABER_EINVAL, "saber_counts: null context");
+    if ((cd_topic || cd_count) && !cd_row_ptr) return fail(SABER_EINVAL, "saber_counts: cd_topic/cd_count need cd_row_ptr");
+    try {
+        if (cd_row_ptr) {
+            std::vector<uint2> rec((size_t)c->D);
+            if (c->D) HIP_TRY(hipMemcpy(rec.data(), c->docrec, sizeof(uint2) * (size_t)c->D, hipMemcpyDeviceToHost));
+            cd_row_ptr[0] = 0;
+            for (int64_t d = 0; d < c->D; d++) cd_row_ptr[d + 1] = cd_row_ptr[d] + rec[(size_t)d].y;
+            if (cd_topic || cd_count) {
+                // unpack the device rows slab by slab (format conversion only)
+                const int64_t slab_docs = 65536;
+                std::vector<uint32_t> buf;
+                for (int64_t d0 = 0; d0 < c->D; d0 += slab_docs) {
+                    const int64_t d1 = std::min(c->D, d0 + slab_docs);
+                    const int64_t e0 = (int64_t)rec[(size_t)d0].x * 32;
+                    const int64_t e1 = d1 < c->D ? (int64_t)rec[(size_t)d1].x * 32 : c->cd_cap;
+                    buf.resize((size_t)std::max<int64_t>(e1 - e0, 1));
+                    if (e1 > e0) HIP_TRY(hipMemcpy(buf.data(), c->cd_ent + e0, sizeof(uint32_t) * (size_t)(e1 - e0), hipMemcpyDeviceToHost));
+                    for (int64_t d = d0; d < d1; d++) {
+                        const uint32_t *row = buf.data() + ((int64_t)rec[(size_t)d].x * 32 - e0);
+                        int64_t o = cd_row_ptr[d];
+                        for (uint32_t j = 0; j < rec[(size_t)d].y; j++, o++) {
+                            if (cd_topic) cd_topic[o] = (int32_t)(row[j] & c->topic_mask);
+                            if (cd_count) cd_count[o] = (int32_t)(row[j] >> c->topic_bits);
+                        }
+                    }
+                }
+            }
+        }
+        if (cwk) {
+            // B is consumed (and cleared) by the Bhat kernel; rebuild it from z for export
+            SABER_TRY(launch_count_vz(c));
+            HIP_TRY(hipStreamSynchronize(c->stream));
+            HIP_TRY(hipMemcpy2D(cwk, sizeof(int32_t) * (size_t)c->K, c->cwk, sizeof(int32_t) * (size_t)c->Kpad,
+                                sizeof(int32_t) * (size_t)c->K, (size_t)c->V, hipMemcpyDeviceToHost));
+            const size_t vk = (size_t)c->V * (size_t)c->Kpad;
+            hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for((int64_t)vk, 256, 8192)), dim3(256), 0, c->stream,
+                               (uint32_t *)c->cwk, 0u, vk);
+            HIP_TRY(hipGetLastError());
+            HIP_TRY(hipStreamSynchronize(c->stream));
+        }
+        if (ck) {
+            std::vector<uint32_t> h((size_t)c->K);
+            HIP_TRY(hipMemcpy(h.data(), c->ck, sizeof(uint32_t) * (size_t)c->K, hipMemcpyDeviceToHost));
+            for (int32_t k = 0; k < c->K; k++) ck[k] = (int64_t)h[(size_t)k];
+        }
+    } catch (const std::bad_alloc &) { return fail(SABER_ENOMEM, "saber_counts: out of host memory"); }
+    return SABER_OK;
+}
+
+extern "C" int saber_loglik(saber_ctx *c, double *out) {
+    if (!c || !out) return fail(SABER_EINVAL, "saber_loglik: null argument");
+    if (c->T == 0) { *out = 0.0; return SABER_OK; }
+    double total = 0.0;
+    try {
+        std::vector<double> part;
+        for (const Chunk &ch : c->chunks) {
+            if (ch.ntiles == 0) continue;
+            EStepParams p = make_params(c, ch);
+            p.out_ll = c->ll_partial;
+            SABER_TRY(launch_estep<MODE_LOGLIK>(c, ch, p));
+            HIP_TRY(hipStreamSynchronize(c->stream));
+            part.resize((size_t)ch.ntiles);
+            HIP_TRY(hipMemcpy(part.data(), c->ll_partial, sizeof(double) * (size_t)ch.ntiles, hipMemcpyDeviceToHost));
+            for (double v : part) total += v;   // fixed order: the result is reproducible
+        }
+    } catch (const std::bad_alloc &) { return fail(SABER_ENOMEM, "saber_loglik: out of host memory"); }
+    *out = (total - c->ll_const) / (double)c->T;
+    return SABER_OK;
+}
+
+extern "C" int saber_get_z(saber_ctx *c, int32_t *z) {
+    if (!c || !z) return fail(SABER_EINVAL, "saber_get_z: null argument");
+    if (c->T == 0) return SABER_OK;
+    if (!c->z16) { HIP_TRY(hipMemcpy(z, c->z, sizeof(int32_t) * (size_t)c->T, hipMemcpyDeviceToHost)); return SABER_OK; }
+    int32_t *tmp = nullptr;
+    SABER_TRY(dev_alloc(&tmp, (size_t)c->T));
+    hipLaunchKernelGGL((z_to_i32_kernel<uint16_t>), dim3(grid_for(c->T, 256, 8192)), dim3(256), 0, c->stream,
+                       (const uint16_t *)c->z, tmp, c->T);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e == hipSuccess) e = hipMemcpy(z, tmp, sizeof(int32_t) * (size_t)c->T, hipMemcpyDeviceToHost);
+    dev_free(tmp);
+    if (e != hipSuccess) return fail(SABER_EDEVICE, "saber_get_z: %s", hipGetErrorString(e));
+    return SABER_OK;
+}
+
+extern "C" int saber_set_z(saber_ctx *c, const int32_t *z, uint32_t iter) {
+    if (!c || (!z && c->T)) return fail(SABER_EINVAL, "saber_set_z: null argument");
+    for (int64_t t = 0; t < c->T; t++)
+        if (z[t] < 0 || z[t] >= c->K) return fail(SABER_EINVAL, "saber_set_z: topic %d at token %lld is outside [0,%d)", z[t], (long long)t, c->K);
+    if (c->T) {
+        int32_t *tmp = nullptr;
+        SABER_TRY(dev_alloc(&tmp, (size_t)c->T));
+        hipError_t e = hipMemcpy(tmp, z, sizeof(int32_t) * (size_t)c->T, hipMemcpyHostToDevice);
+        if (e == hipSuccess) {
+            if (c->z16)
+                hipLaunchKernelGGL((z_from_i32_kernel<uint16_t>), dim3(grid_for(c->T, 256, 8192)), dim3(256), 0, c->stream, (uint16_t *)c->z, tmp, c->T);
+            else
+                hipLaunchKernelGGL((z_from_i32_kernel<int32_t>), dim3(grid_for(c->T, 256, 8192)), dim3(256), 0, c->stream, (int32_t *)c->z, tmp, c->T);
+            e = hipGetLastError();
+        }
+        if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+        dev_free(tmp);
+        if (e != hipSuccess) return fail(SABER_EDEVICE, "saber_set_z: %s", hipGetErrorString(e));
+    }
+    c->iter = iter;
+    SABER_TRY(full_mstep(c));
+    SABER_TRY(refresh_workload_stats(c));
+    return SABER_OK;
+}
+
+extern "C" int saber_get_iteration(saber_ctx *c, uint32_t *iter) {
+    if (!c || !iter) return fail(SABER_EINVAL, "saber_get_iteration: null argument");
+    *iter = c->iter;
+    return SABER_OK;
+}
+
+extern "C" int saber_token_probs(saber_ctx *c, const int64_t *tok, int64_t m, float *S, float *Q, float *p_sparse) {
+    if (!c || (m > 0 && !tok) || m < 0) return fail(SABER_EINVAL, "saber_token_probs: bad argument");
+    for (int64_t i = 0; i < m; i++)
+        if (tok[i] < 0 || tok[i] >= c->T) return fail(SABER_EINVAL, "saber_token_probs: token index %lld is outside [0,%lld)", (long long)tok[i], (long long)c->T);
+    if (m == 0) return SABER_OK;
+    float *dS = nullptr, *dQ = nullptr, *gS = nullptr, *gQ = nullptr; int64_t *dtok = nullptr;
+    int rc = SABER_OK;
+    auto cleanup = [&]() { dev_free(dS); dev_free(dQ); dev_free(gS); dev_free(gQ); dev_free(dtok); };
+    if ((rc = dev_alloc(&dS, (size_t)c->T)) || (rc = dev_alloc(&dQ, (size_t)c->T)) || (rc = dev_alloc(&gS, (size_t)m)) ||
+        (rc = dev_alloc(&gQ, (size_t)m)) || (rc = dev_alloc(&dtok, (size_t)m))) { cleanup(); return rc; }
+    for (const Chunk &ch : c->chunks) {
+        EStepParams p = make_params(c, ch);
+        p.out_S = dS; p.out_Q = dQ;
+        if ((rc = launch_estep<MODE_PROBS>(c, ch, p))) { cleanup(); return rc; }
+    }
+    std::vector<float> hS((size_t)m), hQ((size_t)m);
+    hipError_t e = hipMemcpyAsync(dtok, tok, sizeof(int64_t) * (size_t)m, hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(gather_f32_kernel, dim3(grid_for(m, 256)), dim3(256), 0, c->stream, dS, dtok, m, gS);
+        hipLaunchKernelGGL(gather_f32_kernel, dim3(grid_for(m, 256)), dim3(256), 0, c->stream, dQ, dtok, m, gQ);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e == hipSuccess) e = hipMemcpy(hS.data(), gS, sizeof(float) * (size_t)m, hipMemcpyDeviceToHost);
+    if (e == hipSuccess) e = hipMemcpy(hQ.data(), gQ, sizeof(float) * (size_t)m, hipMemcpyDeviceToHost);
+    cleanup();
+    if (e != hipSuccess) return fail(SABER_EDEVICE, "saber_token_probs: %s", hipGetErrorString(e));
+    for (int64_t i = 0; i < m; i++) {
+        if (S) S[i] = hS[(size_t)i];
+        if (Q) Q[i] = hQ[(size_t)i];
+        if (p_sparse) p_sparse[i] = hS[(size_t)i] / (hS[(size_t)i] + hQ[(size_t)i]);
+    }
+    return SABER_OK;
+}
+
+extern "C" int saber_get_phi(saber_ctx *c, const int32_t *words, int32_t m, float *phi, float *prefix) {
+    if (!c || (m > 0 && !words) || m < 0) return fail(SABER_EINVAL, "saber_get_phi: bad argument");
+    for (int32_t i = 0; i < m; i++) {
+        if (words[i] < 0 || words[i] >= c->V) return fail(SABER_EINVAL, "saber_get_phi: word %d is outside [0,%d)", words[i], c->V);
+        const size_t off = (size_t)words[i] * (size_t)c->Kpad;
+        if (phi) HIP_TRY(hipMemcpy(phi + (size_t)i * (size_t)c->K, c->phi + off, sizeof(float) * (size_t)c->K, hipMemcpyDeviceToHost));
+        if (prefix) HIP_TRY(hipMemcpy(prefix + (size_t)i * (size_t)c->K, c->prefix + off, sizeof(float) * (size_t)c->K, hipMemcpyDeviceToHost));
+    }
+    return SABER_OK;
+}
+
+extern "C" int saber_get_stats(saber_ctx *c, saber_stats *out) {
+    if (!c || !out) return fail(SABER_EINVAL, "saber_get_stats: null argument");
+    *out = c->stats;
+    return SABER_OK;
+}
+
+extern "C" int saber_reset_stats(saber_ctx *c) {
+    if (!c) return fail(SABER_EINVAL, "saber_reset_stats: null context");
+    c->stats.iterations = 0; c->stats.ms_sample = c->stats.ms_count_dz = c->stats.ms_ck = c->stats.ms_phi = c->stats.ms_total = 0.0;
+    c->stats.sample_launches = 0; c->stats.sum_tokens = c->stats.sum_tokens_dense = c->stats.sum_row_entries = 0;
+    return SABER_OK;
+}
+
+extern "C" int saber_get_stream(saber_ctx *c, void **s) {
+    if (!c || !s) return fail(SABER_EINVAL, "saber_get_stream: null argument");
+    *s = (void *)c->stream;
+    return SABER_OK;
+}

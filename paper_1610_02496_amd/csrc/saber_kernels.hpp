@@ -1,0 +1,472 @@
+// Device code of the sparsity-aware LDA sampler for gfx950 (wave64).
+// Included once by saber.hip.  Citations refer to the SaberLDA paper.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace saber {
+
+constexpr int kWave = 64;
+
+// ---------------------------------------------------------------------------------------------
+// Wavefront primitives (the wave64 counterparts of warp_sum / warp_prefix_sum / warp_vote /
+// warp_copy in Sec. 3.2.3): DPP row shifts + row broadcasts for scans, a 64-bit ballot + count
+// trailing zeros for the vote, readlane for the copy.
+// ---------------------------------------------------------------------------------------------
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_f32(float v) {
+    // lanes without a valid source (or masked rows) receive 0, the identity of the sums below
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_f64(double v) {
+    long long b = __double_as_longlong(v);
+    int lo = __builtin_amdgcn_update_dpp(0, (int)(b & 0xffffffffll), CTRL, ROW_MASK, 0xf, false);
+    int hi = __builtin_amdgcn_update_dpp(0, (int)(b >> 32), CTRL, ROW_MASK, 0xf, false);
+    return __longlong_as_double(((long long)hi << 32) | (long long)(uint32_t)lo);
+}
+
+// inclusive scan over the 64 lanes: 4 shifts inside each row of 16, then two row broadcasts
+#define SABER_SCAN_BODY(T, DPP)                                                            \
+    v += DPP<0x111, 0xf>(v); /* row_shr:1 */                                               \
+    v += DPP<0x112, 0xf>(v); /* row_shr:2 */                                               \
+    v += DPP<0x114, 0xf>(v); /* row_shr:4 */                                               \
+    v += DPP<0x118, 0xf>(v); /* row_shr:8 */                                               \
+    v += DPP<0x142, 0xa>(v); /* row_bcast:15 into rows 1 and 3 */                          \
+    v += DPP<0x143, 0xc>(v); /* row_bcast:31 into rows 2 and 3 */                          \
+    return v;
+__device__ __forceinline__ float wave_incl_scan(float v) { SABER_SCAN_BODY(float, dpp_f32) }
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) { SABER_SCAN_BODY(uint32_t, dpp_u32) }
+__device__ __forceinline__ double wave_incl_scan(double v) { SABER_SCAN_BODY(double, dpp_f64) }
+#undef SABER_SCAN_BODY
+
+__device__ __forceinline__ float readlane_f32(float v, int lane) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+__device__ __forceinline__ uint32_t readlane_u32(uint32_t v, int lane) {
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, lane);
+}
+__device__ __forceinline__ double readlane_f64(double v, int lane) {
+    long long b = __double_as_longlong(v);
+    int lo = __builtin_amdgcn_readlane((int)(b & 0xffffffffll), lane);
+    int hi = __builtin_amdgcn_readlane((int)(b >> 32), lane);
+    return __longlong_as_double(((long long)hi << 32) | (long long)(uint32_t)lo);
+}
+__device__ __forceinline__ float wave_sum(float v) { return readlane_f32(wave_incl_scan(v), 63); }
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) { return readlane_u32(wave_incl_scan(v), 63); }
+
+// index of the first lane whose predicate holds, or -1
+__device__ __forceinline__ int wave_vote_first(bool pred) {
+    unsigned long long m = __builtin_amdgcn_ballot_w64(pred);
+    return m ? (int)__builtin_ctzll(m) : -1;
+}
+
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & (kWave - 1)); }
+
+// ---------------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11), written for the device; the CPU checker has its own.
+// counter = (token lo, token hi, iteration, 0), key = (seed lo, seed hi).
+// ---------------------------------------------------------------------------------------------
+struct Rand2 { uint32_t r0, r1; };
+__device__ __forceinline__ Rand2 philox_token(uint32_t seed_lo, uint32_t seed_hi, uint64_t t, uint32_t iter) {
+    uint32_t c0 = (uint32_t)t, c1 = (uint32_t)(t >> 32), c2 = iter, c3 = 0u;
+    uint32_t k0 = seed_lo, k1 = seed_hi;
+#pragma unroll
+    for (int r = 0; r < 10; r++) {
+        const uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u;
+        uint32_t hi0 = __umulhi(M0, c0), lo0 = M0 * c0;
+        uint32_t hi1 = __umulhi(M1, c2), lo1 = M1 * c2;
+        uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+        c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+        k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+    }
+    return Rand2{c0, c1};
+}
+__device__ __forceinline__ float unit24(uint32_t r) { return (float)(r >> 8) * (1.0f / 16777216.0f); }
+
+// ---------------------------------------------------------------------------------------------
+// Small utility kernels
+// ---------------------------------------------------------------------------------------------
+__global__ void fill_u32_kernel(uint32_t *p, uint32_t value, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = value;
+}
+
+template <typename ZT>
+__global__ void init_z_kernel(ZT *z, int64_t T, uint32_t K, uint32_t seed_lo, uint32_t seed_hi) {
+    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (int64_t)gridDim.x * blockDim.x;
+    for (; t < T; t += stride) {
+        Rand2 r = philox_token(seed_lo, seed_hi, (uint64_t)t, 0u);
+        z[t] = (ZT)__umulhi(r.r0, K);   // floor(word0 * K / 2^32)
+    }
+}
+
+template <typename ZT>
+__global__ void z_from_i32_kernel(ZT *z, const int32_t *src, int64_t T) {
+    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (int64_t)gridDim.x * blockDim.x;
+    for (; t < T; t += stride) z[t] = (ZT)src[t];
+}
+template <typename ZT>
+__global__ void z_to_i32_kernel(const ZT *z, int32_t *dst, int64_t T) {
+    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (int64_t)gridDim.x * blockDim.x;
+    for (; t < T; t += stride) dst[t] = (int32_t)z[t];
+}
+
+__global__ void gather_f32_kernel(const float *src, const int64_t *idx, int64_t m, float *dst) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < m) dst[i] = src[idx[i]];
+}
+
+// ---------------------------------------------------------------------------------------------
+// Work description of the E-step: one tile = up to tile_tokens tokens of one word inside one chunk.
+// Tokens of a chunk are stored word-major (partition-by-document, order-by-word, Sec. 3.1.4).
+// ---------------------------------------------------------------------------------------------
+struct Tile { int32_t word; int32_t begin; int32_t count; int32_t pad; };
+
+struct EStepParams {
+    const Tile *tiles;
+    const int32_t *tok_doc;     // [chunk tokens] document of the token (global document id)
+    const uint32_t *tok_t;      // [chunk tokens] canonical token index relative to t_base
+    const uint2 *docrec;        // [D] {row start in units of 32 entries, K_d}
+    const uint32_t *cd_ent;     // packed rows of A: topic | count << topic_bits, ascending topic
+    const float *phi;           // [V][Kpad]  Bhat
+    const float *prefix;        // [V][Kpad]  inclusive prefix sums of the Bhat row, padded with the total
+    const float *l3;            // [V][n3pad] every 64th prefix entry, padded with the total
+    const float *sumphi;        // [V]        prefix[K-1]
+    void *z;                    // [T] assignments, canonical order (uint16 or int32)
+    int32_t *cwk;               // [V][Kpad] accumulator of B for the next M-step
+    float *out_S;               // probs mode: S per canonical token
+    float *out_Q;               // probs mode: Q per canonical token
+    double *out_ll;             // loglik mode: one partial sum per tile
+    unsigned long long *n_dense;// sample mode: dense-branch token counter
+    int64_t t_base;             // canonical index of the chunk's first token
+    int32_t K, Kpad, n3pad;
+    uint32_t topic_bits, topic_mask;
+    float alpha;
+    uint32_t seed_lo, seed_hi, iter;
+};
+
+enum { MODE_SAMPLE = 0, MODE_PROBS = 1, MODE_LOGLIK = 2 };
+
+// Dense branch (problem 2, Sec. 2.3): position of x in the word's prefix table by a W-ary descent with
+// W = 64 (Sec. 3.2.4).  Level 2 is every 64th entry of level 3 and is read in place.
+__device__ __forceinline__ int tree_query(const float *__restrict__ c, const float *__restrict__ l3,
+                                          int n3pad, int K, float x, int lane) {
+    int off3 = 0;
+    if (n3pad > kWave) {
+        int n2 = n3pad / kWave;
+        float v2 = (lane < n2) ? l3[(lane + 1) * kWave - 1] : __builtin_inff();
+        int i2 = wave_vote_first(v2 >= x);
+        off3 = (i2 < 0 ? n2 - 1 : i2) * kWave;
+    }
+    float v3 = l3[off3 + lane];
+    int i3 = wave_vote_first(v3 >= x);
+    int off4 = (off3 + (i3 < 0 ? kWave - 1 : i3)) * kWave;
+    const int Kpad = (K + kWave - 1) / kWave * kWave;
+    if (off4 > Kpad - kWave) off4 = Kpad - kWave;   // cannot happen for finite tables; keeps the read in bounds
+    float v4 = c[off4 + lane];
+    int i4 = wave_vote_first(v4 >= x);
+    int k = off4 + (i4 < 0 ? kWave - 1 : i4);
+    return k < K ? k : K - 1;
+}
+
+// ---------------------------------------------------------------------------------------------
+// E-step (Alg. 2): one workgroup per tile; the word's Bhat row is staged in LDS (STAGED) or gathered
+// from global memory; each wavefront takes 64 tokens at a time: the per-token scalars (document,
+// row descriptor, Philox draws) are produced one token per lane, then the wavefront walks the tokens
+// one after another, all 64 lanes striding over the non-zeros of the document's row of A.
+// ---------------------------------------------------------------------------------------------
+template <int MODE, bool STAGED, typename ZT>
+__global__ void __launch_bounds__(1024) estep_kernel(EStepParams p) {
+    extern __shared__ float lds_phi[];
+    __shared__ double ll_wave[16];
+    const Tile tile = p.tiles[blockIdx.x];
+    const int K = p.K;
+    const float *__restrict__ phi_row = p.phi + (size_t)tile.word * (size_t)p.Kpad;
+    if (STAGED) {
+        const float4 *src = reinterpret_cast<const float4 *>(phi_row);
+        float4 *dst = reinterpret_cast<float4 *>(lds_phi);
+        for (int i = threadIdx.x; i < p.Kpad / 4; i += blockDim.x) dst[i] = src[i];
+        __syncthreads();
+    }
+    const float sum_w = p.sumphi[tile.word];
+    const float Q = p.alpha * sum_w;
+    const int lane = lane_id(), wave = threadIdx.x / kWave, nwaves = blockDim.x / kWave;
+    const uint32_t bits = p.topic_bits, tmask = p.topic_mask;
+    double ll_acc = 0.0;
+    uint32_t dense_count = 0;
+
+    for (int batch = wave * kWave; batch < tile.count; batch += nwaves * kWave) {
+        const int n = min(kWave, tile.count - batch);
+        const bool act = lane < n;
+        const int i = tile.begin + batch + lane;
+        const int d = act ? p.tok_doc[i] : 0;
+        const uint32_t t = act ? p.tok_t[i] : 0u;
+        uint2 rec = make_uint2(0u, 0u);
+        if (act) rec = p.docrec[d];
+        float u0 = 0.f, u1 = 0.f;
+        if (MODE == MODE_SAMPLE) {
+            Rand2 r = philox_token(p.seed_lo, p.seed_hi, (uint64_t)(p.t_base + (int64_t)t), p.iter);
+            u0 = unit24(r.r0); u1 = unit24(r.r1);
+        }
+        uint32_t my_z = 0; float my_S = 0.f;
+
+        for (int s = 0; s < n; s++) {
+            const uint32_t start32 = readlane_u32(rec.x, s);
+            const int kd = (int)readlane_u32(rec.y, s);
+            const uint32_t *__restrict__ row = p.cd_ent + (size_t)start32 * 32u;
+            // element-wise product A_d (.) Bhat_v and its sum S (Alg. 2, product loop)
+            float acc = 0.f;
+            for (int j0 = 0; j0 < kd; j0 += kWave) {
+                const int j = j0 + lane;
+                const uint32_t e = (j < kd) ? row[j] : 0u;
+                const float ph = STAGED ? lds_phi[e & tmask] : phi_row[e & tmask];
+                acc += (float)(e >> bits) * ph;
+            }
+            const float S = wave_sum(acc);
+            if (MODE == MODE_SAMPLE) {
+                const float u0s = readlane_f32(u0, s), u1s = readlane_f32(u1, s);
+                uint32_t topic;
+                if (u0s * (S + Q) < S) {
+                    // problem 1: position of x in the prefix sums of P, 64 entries per step
+                    const float x = u1s * S;
+                    float carry = 0.f;
+                    int found = -1; uint32_t efound = 0u;
+                    for (int j0 = 0; j0 < kd; j0 += kWave) {
+                        const int j = j0 + lane;
+                        const uint32_t e = (j < kd) ? row[j] : 0u;
+                        const float ph = STAGED ? lds_phi[e & tmask] : phi_row[e & tmask];
+                        const float ps = wave_incl_scan((float)(e >> bits) * ph) + carry;
+                        const int hit = wave_vote_first((j < kd) && (ps >= x));
+                        if (hit >= 0) { found = j0 + hit; efound = readlane_u32(e, hit); break; }
+                        carry = readlane_f32(ps, 63);
+                    }
+                    if (found < 0) efound = row[kd - 1];   // rounding left no entry: take the last
+                    topic = efound & tmask;
+                } else {
+                    const float x = u1s * sum_w;
+                    topic = (uint32_t)tree_query(p.prefix + (size_t)tile.word * (size_t)p.Kpad,
+                                                 p.l3 + (size_t)tile.word * (size_t)p.n3pad, p.n3pad, K, x, lane);
+                    dense_count++;
+                }
+                if (lane == s) my_z = topic;
+            } else {
+                if (lane == s) my_S = S;
+            }
+        }
+
+        if (act) {
+            const int64_t tc = p.t_base + (int64_t)t;
+            if (MODE == MODE_SAMPLE) {
+                reinterpret_cast<ZT *>(p.z)[tc] = (ZT)my_z;
+                atomicAdd(&p.cwk[(size_t)tile.word * (size_t)p.Kpad + my_z], 1);
+            } else if (MODE == MODE_PROBS) {
+                p.out_S[tc] = my_S; p.out_Q[tc] = Q;
+            } else {
+                ll_acc += log((double)(my_S + Q));
+            }
+        }
+    }
+
+    if (MODE == MODE_SAMPLE) {
+        if (lane == 0 && dense_count) atomicAdd(p.n_dense, (unsigned long long)dense_count);
+    }
+    if (MODE == MODE_LOGLIK) {
+        double tot = readlane_f64(wave_incl_scan(ll_acc), 63);
+        if (lane == 0) ll_wave[wave] = tot;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double sum = 0.0;
+            for (int w = 0; w < nwaves; w++) sum += ll_wave[w];
+            p.out_ll[blockIdx.x] = sum;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// CountByVZ from scratch (used after init / set_z; during iterations B is accumulated by the E-step)
+// ---------------------------------------------------------------------------------------------
+template <typename ZT>
+__global__ void count_vz_kernel(const Tile *tiles, const uint32_t *tok_t, const ZT *z, int64_t t_base,
+                                int32_t *cwk, int Kpad) {
+    const Tile tile = tiles[blockIdx.x];
+    for (int i = threadIdx.x; i < tile.count; i += blockDim.x) {
+        const uint32_t t = tok_t[tile.begin + i];
+        const uint32_t k = (uint32_t)z[t_base + (int64_t)t];
+        atomicAdd(&cwk[(size_t)tile.word * (size_t)Kpad + k], 1);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Block-wide exclusive scan of one uint32 per thread; returns the exclusive prefix, *total = block sum.
+// scratch must hold blockDim.x/64 + 1 values.  Contains two __syncthreads().
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *scratch, uint32_t *total) {
+    const int lane = lane_id(), wave = threadIdx.x / kWave, nwaves = (blockDim.x + kWave - 1) / kWave;
+    const uint32_t incl = wave_incl_scan(v);
+    if (lane == kWave - 1) scratch[wave] = incl;
+    __syncthreads();
+    uint32_t off = 0, tot = 0;
+    for (int w = 0; w < nwaves; w++) { const uint32_t s = scratch[w]; if (w < wave) off += s; tot += s; }
+    __syncthreads();
+    *total = tot;
+    return off + incl - v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// CountByDZ (Alg. 1; the "segmented count" of Sec. 3.3), one workgroup per document.
+// The document's assignments are contiguous (z is kept in document order, so the "shuffle" of Sec. 3.3
+// is the E-step's scattered store).  Instead of sorting, the workgroup marks the topics present in a
+// K-bit LDS bitmap; popcount prefix sums over the bitmap give every present topic its rank, i.e. its
+// slot in the ascending row; counts are accumulated per slot with LDS atomics.
+// Rows whose K_d exceeds lds_entries are accumulated directly in the global row.
+// ---------------------------------------------------------------------------------------------
+template <typename ZT>
+__global__ void __launch_bounds__(1024) count_dz_kernel(const int32_t *doc_list, const int64_t *doc_ptr,
+                                                        const ZT *z, uint2 *docrec, uint32_t *cd_ent, int K,
+                                                        uint32_t topic_bits, int nwords, int lds_entries) {
+    extern __shared__ uint32_t lds_u32[];
+    __shared__ uint32_t scan_scratch[20];
+    uint32_t *bitmap = lds_u32;            // [nwords]
+    uint32_t *wpre = lds_u32 + nwords;     // [nwords] exclusive popcount prefix
+    uint32_t *ent_lds = wpre + nwords;     // [lds_entries]
+    const int d = doc_list[blockIdx.x];
+    const int64_t begin = doc_ptr[d];
+    const int len = (int)(doc_ptr[d + 1] - begin);
+    if (len == 0) { if (threadIdx.x == 0) docrec[d].y = 0u; return; }
+    const ZT *__restrict__ zd = z + begin;
+
+    for (int w = threadIdx.x; w < nwords; w += blockDim.x) bitmap[w] = 0u;
+    __syncthreads();
+    for (int i = threadIdx.x; i < len; i += blockDim.x) {
+        const uint32_t k = (uint32_t)zd[i];
+        atomicOr(&bitmap[k >> 5], 1u << (k & 31u));
+    }
+    __syncthreads();
+    // ranks: exclusive prefix of popcounts over the bitmap words
+    uint32_t carry = 0;
+    for (int w0 = 0; w0 < nwords; w0 += blockDim.x) {
+        const int w = w0 + threadIdx.x;
+        const uint32_t pc = (w < nwords) ? (uint32_t)__popc(bitmap[w]) : 0u;
+        uint32_t total;
+        const uint32_t ex = block_excl_scan(pc, scan_scratch, &total);
+        if (w < nwords) wpre[w] = carry + ex;
+        carry += total;
+    }
+    const int kd = (int)carry;
+    uint32_t *row = cd_ent + (size_t)docrec[d].x * 32u;
+    const bool in_lds = kd <= lds_entries;
+    uint32_t *ent = in_lds ? ent_lds : row;
+    __syncthreads();
+    // slot r of the row starts as (topic, count 0): enumerate the set bits of every bitmap word
+    for (int w = threadIdx.x; w < nwords; w += blockDim.x) {
+        uint32_t m = bitmap[w]; uint32_t r = wpre[w];
+        while (m) { const int b = __ffs((int)m) - 1; m &= m - 1u; ent[r++] = (uint32_t)(w * 32 + b); }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < len; i += blockDim.x) {
+        const uint32_t k = (uint32_t)zd[i];
+        const uint32_t wd = bitmap[k >> 5];
+        const uint32_t r = wpre[k >> 5] + (uint32_t)__popc(wd & ((1u << (k & 31u)) - 1u));
+        atomicAdd(&ent[r], 1u << topic_bits);
+    }
+    __syncthreads();
+    if (in_lds)
+        for (int r = threadIdx.x; r < kd; r += blockDim.x) row[r] = ent_lds[r];
+    if (threadIdx.x == 0) docrec[d].y = (uint32_t)kd;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Topic totals C_k = sum_v B_vk, computed as the histogram of z (same numbers, 20x fewer bytes than
+// column sums of B at K = 10^4).  LDS histogram when K fits, else global atomics.
+// ---------------------------------------------------------------------------------------------
+template <typename ZT>
+__global__ void topic_totals_kernel(const ZT *z, int64_t T, int64_t per_block, uint32_t *ck, int K, int use_lds) {
+    extern __shared__ uint32_t hist[];
+    const int64_t b = (int64_t)blockIdx.x * per_block;
+    int64_t e = b + per_block; if (e > T) e = T;
+    if (use_lds) {
+        for (int k = threadIdx.x; k < K; k += blockDim.x) hist[k] = 0u;
+        __syncthreads();
+        for (int64_t t = b + threadIdx.x; t < e; t += blockDim.x) atomicAdd(&hist[(uint32_t)z[t]], 1u);
+        __syncthreads();
+        for (int k = threadIdx.x; k < K; k += blockDim.x) { const uint32_t h = hist[k]; if (h) atomicAdd(&ck[k], h); }
+    } else {
+        for (int64_t t = b + threadIdx.x; t < e; t += blockDim.x) atomicAdd(&ck[(uint32_t)z[t]], 1u);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Preprocess + BuildTree (Alg. 1; Eq. 2; Sec. 3.2.4), one workgroup of 256 threads per word row.
+//   Bhat_vk = (float(B_vk) + beta) / (float(C_k) + float(V) * beta)      -- three single-rounded fp32 ops
+//   prefix  = round32( running sum of Bhat_v accumulated in fp64 )       -- bottom tree level
+//   l3[i]   = prefix[(i+1)*64 - 1]                                        -- next level, W = 64
+// Pad columns k in [K, Kpad) get Bhat = 0, so the padded prefix entries repeat the row total.
+// The row of B is cleared after it has been read, ready to accumulate the next E-step.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) phi_prefix_kernel(int32_t *cwk, const uint32_t *ck, float *phi, float *prefix,
+                                                         float *l3, float *sumphi, int K, int Kpad, int n3pad,
+                                                         float beta, float vbeta, int clear_cwk) {
+    __shared__ double wave_tot[4];
+    __shared__ float row_total;   // the stored prefix entry of the last real topic, K-1
+    const int v = blockIdx.x;
+    const int lane = lane_id(), wave = threadIdx.x / kWave;
+    const size_t rbase = (size_t)v * (size_t)Kpad;
+    double carry = 0.0;
+    for (int base = 0; base < Kpad; base += 1024) {
+        const int k0 = base + (int)threadIdx.x * 4;
+        float f[4] = {0.f, 0.f, 0.f, 0.f};
+        if (k0 < Kpad) {   // Kpad is a multiple of 64, so k0..k0+3 are all inside the padded row
+            const int4 c = *reinterpret_cast<const int4 *>(cwk + rbase + k0);
+            const int cc[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                const int k = k0 + q;
+                if (k < K) {
+                    const float num = (float)cc[q] + beta;
+                    const float den = (float)ck[k] + vbeta;
+                    f[q] = num / den;
+                }
+            }
+            *reinterpret_cast<float4 *>(phi + rbase + k0) = make_float4(f[0], f[1], f[2], f[3]);
+            if (clear_cwk) *reinterpret_cast<int4 *>(cwk + rbase + k0) = make_int4(0, 0, 0, 0);
+        }
+        const double s0 = (double)f[0], s1 = s0 + (double)f[1], s2 = s1 + (double)f[2], s3 = s2 + (double)f[3];
+        const double incl = wave_incl_scan(s3);
+        if (lane == kWave - 1) wave_tot[wave] = incl;
+        __syncthreads();
+        double woff = 0.0, btot = 0.0;
+#pragma unroll
+        for (int w = 0; w < 4; w++) { const double tw = wave_tot[w]; if (w < wave) woff += tw; btot += tw; }
+        const double off = carry + woff + (incl - s3);
+        if (k0 < Kpad) {
+            *reinterpret_cast<float4 *>(prefix + rbase + k0) =
+                make_float4((float)(off + s0), (float)(off + s1), (float)(off + s2), (float)(off + s3));
+            if (((k0 + 3) & (kWave - 1)) == kWave - 1) l3[(size_t)v * (size_t)n3pad + (size_t)((k0 + 3) / kWave)] = (float)(off + s3);
+            const int q = K - 1 - k0;
+            if (q >= 0 && q < 4) row_total = (float)(off + (q == 0 ? s0 : q == 1 ? s1 : q == 2 ? s2 : s3));
+        }
+        carry += btot;
+        __syncthreads();
+    }
+    const float total = row_total;   // written before the loop's last barrier
+    for (int i = Kpad / kWave + (int)threadIdx.x; i < n3pad; i += blockDim.x) l3[(size_t)v * (size_t)n3pad + i] = total;
+    if (threadIdx.x == 0) sumphi[v] = total;
+}
+
+// nnz(A) and sum_d K_d * L_d (statistics for the bandwidth model; exact in fp64 below 2^53)
+__global__ void row_stats_kernel(const uint2 *docrec, const int64_t *doc_ptr, int64_t D, unsigned long long *out2) {
+    double nnz = 0.0, reads = 0.0;
+    for (int64_t d = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; d < D; d += (int64_t)gridDim.x * blockDim.x) {
+        const double kd = (double)docrec[d].y;
+        nnz += kd; reads += kd * (double)(doc_ptr[d + 1] - doc_ptr[d]);
+    }
+    nnz = readlane_f64(wave_incl_scan(nnz), 63); reads = readlane_f64(wave_incl_scan(reads), 63);
+    if (lane_id() == 0) { atomicAdd(&out2[0], (unsigned long long)nnz); atomicAdd(&out2[1], (unsigned long long)reads); }
+}
+
+}  // namespace saber

@@ -1,0 +1,56 @@
+"""The C-ABI library loads without a GPU and exports every symbol include/saber.h declares."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_1610_02496_amd as pk
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "saber.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(saber_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert len(names) >= 15
+    lib = pk.load_library()
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(pk.EXPORTS) == names
+
+
+def test_struct_layouts_match_header():
+    import ctypes
+    assert ctypes.sizeof(pk.Options) == 16 * 4
+    assert ctypes.sizeof(pk.Stats) == 23 * 8
+    o = pk.options_default()
+    assert (o.n_chunks, o.block_threads, o.tile_tokens, o.stage_phi, o.profile) == (1, 256, 2048, 1, 0)
+
+
+def test_validation_happens_before_any_device_work():
+    """Bad arguments are rejected on the host, GPU or not."""
+    dp = np.array([0, 2], dtype=np.int64)
+    with pytest.raises(pk.SaberError) as e:
+        pk.Saber(dp, np.array([0, 7], dtype=np.int32), 2, 3, 0.1, 0.01, 1)
+    assert e.value.code == pk.binding.SABER_EINVAL and "word id" in str(e.value)
+    with pytest.raises(pk.SaberError) as e:
+        pk.Saber(np.array([0, 2, 1], dtype=np.int64), np.array([0, 1], dtype=np.int32), 2, 3, 0.1, 0.01, 1)
+    assert e.value.code == pk.binding.SABER_EINVAL
+    with pytest.raises(pk.SaberError) as e:
+        pk.Saber(dp, np.array([0, 1], dtype=np.int32), 2, 1 << 20, 0.1, 0.01, 1)
+    assert e.value.code == pk.binding.SABER_ERANGE
+
+
+def test_no_gpu_fails_loudly():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(pk.SaberError) as e:
+        pk.Saber(np.array([0, 2], dtype=np.int64), np.array([0, 1], dtype=np.int32), 2, 3, 0.1, 0.01, 1)
+    assert e.value.code == pk.binding.SABER_EDEVICE
