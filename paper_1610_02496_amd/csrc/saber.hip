@@ -134,7 +134,7 @@ template <int MODE>
 static int launch_estep(saber_ctx *c, const Chunk &ch, EStepParams &p) {
     if (ch.ntiles == 0) return SABER_OK;
     const dim3 grid((unsigned)ch.ntiles), block((unsigned)c->opt.block_threads);
-    const size_t lds = c->staged ? (size_t)c->Kpad * sizeof(float) : 0;
+    const size_t lds = c->staged ? ((size_t)c->Kpad + (size_t)c->n3pad) * sizeof(float) : 0;
     if (c->staged) {
         if (c->z16) hipLaunchKernelGGL((estep_kernel<MODE, true, uint16_t>), grid, block, lds, c->stream, p);
         else hipLaunchKernelGGL((estep_kernel<MODE, true, int32_t>), grid, block, lds, c->stream, p);
@@ -414,7 +414,7 @@ extern "C" int saber_init_ex(saber_ctx **out, const int64_t *doc_ptr, const int3
     c->nwords = (K + 31) / 32;
     c->topic_bits = bits; c->topic_mask = (1u << bits) - 1u;
     c->z16 = K <= 65536;
-    c->staged = opt.stage_phi && (size_t)c->Kpad * sizeof(float) <= 60 * 1024;
+    c->staged = opt.stage_phi && ((size_t)c->Kpad + (size_t)c->n3pad) * sizeof(float) <= 60 * 1024;
     c->vbeta = (float)V * beta;
     c->max_doc_len = maxlen;
     int rc;

@@ -154,7 +154,7 @@ enum { MODE_SAMPLE = 0, MODE_PROBS = 1, MODE_LOGLIK = 2 };
 
 // Dense branch (problem 2, Sec. 2.3): position of x in the word's prefix table by a W-ary descent with
 // W = 64 (Sec. 3.2.4).  Level 2 is every 64th entry of level 3 and is read in place.
-__device__ __forceinline__ int tree_query(const float *__restrict__ c, const float *__restrict__ l3,
+__device__ __forceinline__ int tree_query(const float *__restrict__ c, const float *l3,
                                           int n3pad, int K, float x, int lane) {
     int off3 = 0;
     if (n3pad > kWave) {
@@ -175,22 +175,68 @@ __device__ __forceinline__ int tree_query(const float *__restrict__ c, const flo
 }
 
 // ---------------------------------------------------------------------------------------------
-// E-step (Alg. 2): one workgroup per tile; the word's Bhat row is staged in LDS (STAGED) or gathered
-// from global memory; each wavefront takes 64 tokens at a time: the per-token scalars (document,
-// row descriptor, Philox draws) are produced one token per lane, then the wavefront walks the tokens
-// one after another, all 64 lanes striding over the non-zeros of the document's row of A.
+// E-step (Alg. 2).  One workgroup per tile; the word's Bhat row and the second tree level are staged in
+// LDS (STAGED) or read from global memory.  Each wavefront takes a batch of up to 64 tokens: the
+// per-token scalars (document, row descriptor, Philox draws) are produced one token per lane, then the
+// wavefront walks the tokens one after another.  A row of A is consumed in blocks of 256 entries, lane l
+// holding entries 4l..4l+3 (one 16-byte load per lane, 1 KB per wavefront): the lane forms its four
+// running partial products, one DPP scan over the lane sums yields both S and every prefix sum, and the
+// draw is located with one ballot plus a four-way compare inside the winning lane.  The first block of
+// the next token is fetched while the current token is processed.
 // ---------------------------------------------------------------------------------------------
+struct RowBlock { float a0, a1, a2, a3, incl; };   // running sums inside the lane; inclusive scan of lane sums
+
+__device__ __forceinline__ uint4 load_block(const uint32_t *__restrict__ row, int rel_kd, int lane) {
+    // rows are 128-byte aligned and zero-filled up to the next multiple of 4 entries
+    uint4 e = make_uint4(0u, 0u, 0u, 0u);
+    if (4 * lane < rel_kd) e = *reinterpret_cast<const uint4 *>(row + 4 * lane);
+    return e;
+}
+
+template <bool STAGED>
+__device__ __forceinline__ void block_products(const uint4 e, uint32_t bits, uint32_t tmask,
+                                               const float *lds_phi, const float *__restrict__ phi_row, RowBlock &b) {
+    const float f0 = STAGED ? lds_phi[e.x & tmask] : phi_row[e.x & tmask];
+    const float f1 = STAGED ? lds_phi[e.y & tmask] : phi_row[e.y & tmask];
+    const float f2 = STAGED ? lds_phi[e.z & tmask] : phi_row[e.z & tmask];
+    const float f3 = STAGED ? lds_phi[e.w & tmask] : phi_row[e.w & tmask];
+    b.a0 = (float)(e.x >> bits) * f0;
+    b.a1 = b.a0 + (float)(e.y >> bits) * f1;
+    b.a2 = b.a1 + (float)(e.z >> bits) * f2;
+    b.a3 = b.a2 + (float)(e.w >> bits) * f3;
+    b.incl = wave_incl_scan(b.a3);
+}
+
+// first entry of the block whose prefix sum (carry + sums inside the block) reaches x
+__device__ __forceinline__ uint32_t search_block(const uint4 e, const RowBlock &b, float carry, float x, int rel_kd,
+                                                 int lane, uint32_t tmask) {
+    const int nvalid = rel_kd < 4 * kWave ? rel_kd : 4 * kWave;
+    int L = wave_vote_first(carry + b.incl >= x);
+    if (L < 0) L = (nvalid - 1) >> 2;                      // rounding left no entry: the last one
+    const float base = carry + (b.incl - b.a3);
+    int q = (base + b.a0 >= x) ? 0 : (base + b.a1 >= x) ? 1 : (base + b.a2 >= x) ? 2 : 3;
+    const int maxq = nvalid - 1 - 4 * lane;                // never point at the zero fill
+    q = q > maxq ? maxq : q;
+    const uint32_t sel = q <= 0 ? e.x : q == 1 ? e.y : q == 2 ? e.z : e.w;
+    return readlane_u32(sel, L) & tmask;
+}
+
 template <int MODE, bool STAGED, typename ZT>
 __global__ void __launch_bounds__(1024) estep_kernel(EStepParams p) {
-    extern __shared__ float lds_phi[];
+    extern __shared__ float lds_f32[];
     __shared__ double ll_wave[16];
+    float *lds_phi = lds_f32;                 // [Kpad]
+    float *lds_l3 = lds_f32 + p.Kpad;         // [n3pad]
     const Tile tile = p.tiles[blockIdx.x];
     const int K = p.K;
     const float *__restrict__ phi_row = p.phi + (size_t)tile.word * (size_t)p.Kpad;
+    const float *__restrict__ l3_row = p.l3 + (size_t)tile.word * (size_t)p.n3pad;
     if (STAGED) {
         const float4 *src = reinterpret_cast<const float4 *>(phi_row);
         float4 *dst = reinterpret_cast<float4 *>(lds_phi);
         for (int i = threadIdx.x; i < p.Kpad / 4; i += blockDim.x) dst[i] = src[i];
+        if (MODE == MODE_SAMPLE)
+            for (int i = threadIdx.x; i < p.n3pad; i += blockDim.x) lds_l3[i] = l3_row[i];
         __syncthreads();
     }
     const float sum_w = p.sumphi[tile.word];
@@ -199,9 +245,12 @@ __global__ void __launch_bounds__(1024) estep_kernel(EStepParams p) {
     const uint32_t bits = p.topic_bits, tmask = p.topic_mask;
     double ll_acc = 0.0;
     uint32_t dense_count = 0;
+    // batch size: 64 tokens per wavefront, fewer when the tile is too small to keep every wavefront busy
+    int bs = (tile.count + nwaves - 1) / nwaves;
+    bs = bs > kWave ? kWave : bs;
 
-    for (int batch = wave * kWave; batch < tile.count; batch += nwaves * kWave) {
-        const int n = min(kWave, tile.count - batch);
+    for (int batch = wave * bs; batch < tile.count; batch += nwaves * bs) {
+        const int n = min(bs, tile.count - batch);
         const bool act = lane < n;
         const int i = tile.begin + batch + lane;
         const int d = act ? p.tok_doc[i] : 0;
@@ -215,42 +264,57 @@ __global__ void __launch_bounds__(1024) estep_kernel(EStepParams p) {
         }
         uint32_t my_z = 0; float my_S = 0.f;
 
+        uint4 nxt0 = load_block(p.cd_ent + (size_t)readlane_u32(rec.x, 0) * 32u, (int)readlane_u32(rec.y, 0), lane);
         for (int s = 0; s < n; s++) {
-            const uint32_t start32 = readlane_u32(rec.x, s);
             const int kd = (int)readlane_u32(rec.y, s);
-            const uint32_t *__restrict__ row = p.cd_ent + (size_t)start32 * 32u;
-            // element-wise product A_d (.) Bhat_v and its sum S (Alg. 2, product loop)
-            float acc = 0.f;
-            for (int j0 = 0; j0 < kd; j0 += kWave) {
-                const int j = j0 + lane;
-                const uint32_t e = (j < kd) ? row[j] : 0u;
-                const float ph = STAGED ? lds_phi[e & tmask] : phi_row[e & tmask];
-                acc += (float)(e >> bits) * ph;
+            const uint32_t *__restrict__ row = p.cd_ent + (size_t)readlane_u32(rec.x, s) * 32u;
+            const int nblk = (kd + 4 * kWave - 1) / (4 * kWave);
+            const uint4 e0 = nxt0;
+            uint4 e1 = make_uint4(0u, 0u, 0u, 0u);
+            if (nblk > 1) e1 = load_block(row + 4 * kWave, kd - 4 * kWave, lane);
+            if (s + 1 < n)
+                nxt0 = load_block(p.cd_ent + (size_t)readlane_u32(rec.x, s + 1) * 32u, (int)readlane_u32(rec.y, s + 1), lane);
+            // element-wise product A_d (.) Bhat_v, its prefix sums and its sum S (Alg. 2, product loop)
+            RowBlock b0, b1;
+            block_products<STAGED>(e0, bits, tmask, lds_phi, phi_row, b0);
+            const float t0 = readlane_f32(b0.incl, 63);
+            float t1 = 0.f, S = t0;
+            if (nblk > 1) {
+                block_products<STAGED>(e1, bits, tmask, lds_phi, phi_row, b1);
+                t1 = readlane_f32(b1.incl, 63);
+                S = S + t1;
+                for (int blk = 2; blk < nblk; blk++) {
+                    RowBlock bb;
+                    block_products<STAGED>(load_block(row + blk * 4 * kWave, kd - blk * 4 * kWave, lane), bits, tmask,
+                                           lds_phi, phi_row, bb);
+                    S = S + readlane_f32(bb.incl, 63);
+                }
             }
-            const float S = wave_sum(acc);
             if (MODE == MODE_SAMPLE) {
                 const float u0s = readlane_f32(u0, s), u1s = readlane_f32(u1, s);
                 uint32_t topic;
                 if (u0s * (S + Q) < S) {
-                    // problem 1: position of x in the prefix sums of P, 64 entries per step
+                    // problem 1: position of x in the prefix sums of P
                     const float x = u1s * S;
-                    float carry = 0.f;
-                    int found = -1; uint32_t efound = 0u;
-                    for (int j0 = 0; j0 < kd; j0 += kWave) {
-                        const int j = j0 + lane;
-                        const uint32_t e = (j < kd) ? row[j] : 0u;
-                        const float ph = STAGED ? lds_phi[e & tmask] : phi_row[e & tmask];
-                        const float ps = wave_incl_scan((float)(e >> bits) * ph) + carry;
-                        const int hit = wave_vote_first((j < kd) && (ps >= x));
-                        if (hit >= 0) { found = j0 + hit; efound = readlane_u32(e, hit); break; }
-                        carry = readlane_f32(ps, 63);
+                    if (nblk == 1 || t0 >= x) topic = search_block(e0, b0, 0.f, x, kd, lane, tmask);
+                    else if (nblk == 2 || t0 + t1 >= x) topic = search_block(e1, b1, t0, x, kd - 4 * kWave, lane, tmask);
+                    else {
+                        float carry = t0 + t1;
+                        topic = 0u;
+                        for (int blk = 2; blk < nblk; blk++) {
+                            const int rel = kd - blk * 4 * kWave;
+                            const uint4 e = load_block(row + blk * 4 * kWave, rel, lane);
+                            RowBlock bb;
+                            block_products<STAGED>(e, bits, tmask, lds_phi, phi_row, bb);
+                            const float tot = readlane_f32(bb.incl, 63);
+                            if (blk == nblk - 1 || carry + tot >= x) { topic = search_block(e, bb, carry, x, rel, lane, tmask); break; }
+                            carry = carry + tot;
+                        }
                     }
-                    if (found < 0) efound = row[kd - 1];   // rounding left no entry: take the last
-                    topic = efound & tmask;
                 } else {
                     const float x = u1s * sum_w;
                     topic = (uint32_t)tree_query(p.prefix + (size_t)tile.word * (size_t)p.Kpad,
-                                                 p.l3 + (size_t)tile.word * (size_t)p.n3pad, p.n3pad, K, x, lane);
+                                                 STAGED ? lds_l3 : l3_row, p.n3pad, K, x, lane);
                     dense_count++;
                 }
                 if (lane == s) my_z = topic;
@@ -377,6 +441,8 @@ __global__ void __launch_bounds__(1024) count_dz_kernel(const int32_t *doc_list,
     __syncthreads();
     if (in_lds)
         for (int r = threadIdx.x; r < kd; r += blockDim.x) row[r] = ent_lds[r];
+    // zero fill up to the next multiple of 4 entries: the sampler reads rows in 16-byte pieces
+    if (threadIdx.x < 4) { const int r = kd + (int)threadIdx.x; if (r < ((kd + 3) & ~3)) row[r] = 0u; }
     if (threadIdx.x == 0) docrec[d].y = (uint32_t)kd;
 }
 
