@@ -117,6 +117,7 @@ def main():
     ap.add_argument("--block-threads", type=int, default=0)
     ap.add_argument("--tile-tokens", type=int, default=0)
     ap.add_argument("--chunks", type=int, default=0)
+    ap.add_argument("--probe-bytes", type=int, default=1 << 30, help="size of the copy-bandwidth probe (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards by document, "
@@ -139,7 +140,13 @@ def main():
     if args.tile_tokens: opts["tile_tokens"] = args.tile_tokens
     if args.chunks: opts["n_chunks"] = args.chunks
 
+    copy_gbs = None
+    if args.probe_bytes:
+        import paper_1610_02496_amd as pk
+        copy_gbs = pk.bandwidth_probe(args.probe_bytes, 10)
+        log("[bench] plain copy kernel: %.0f GB/s (read+write)" % copy_gbs)
     main_res = run_gpu(corpus, spec.K, args.steps, args.warmup, opts)
+    main_res["roofline"]["copy_kernel_gbs"] = copy_gbs
     log("[bench] K=%d: %s" % (spec.K, json.dumps(main_res)))
     also = None
     if args.workload == "C3" and not args.no_also:

@@ -23,8 +23,8 @@ _lib = None
 
 
 def build(force: bool = False) -> str:
-    """Compile the generator with gcc (takes about a second)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    """Compile the generator with gcc (about a second).  Without ``force`` an existing library is used as it is."""
+    if force or not os.path.exists(_LIB):
         tmp = _LIB + ".tmp%d" % os.getpid()
         subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)

@@ -47,8 +47,9 @@ typedef enum saber_status {
 /* Tunables; none of them changes any result.  Zero / negative means "library default". */
 typedef struct saber_options {
     int32_t n_chunks;       /* document chunks the corpus is cut into (Sec. 3.1.2); default 1 */
-    int32_t block_threads;  /* threads per workgroup of the sampling kernel (multiple of 64); default 256 */
-    int32_t tile_tokens;    /* most tokens of one word handled by one workgroup; default 2048 */
+    int32_t block_threads;  /* threads per workgroup of the sampling kernel (multiple of 64 up to 1024);
+                               default: 512 when the staged Bhat row is 32 KB or more, else 256 */
+    int32_t tile_tokens;    /* most tokens of one word handled by one workgroup; default 4096 */
     int32_t stage_phi;      /* 1: keep the word's Bhat row in LDS when it fits, 0: always gather from global; default 1 */
     int32_t profile;        /* 1: time every kernel group with HIP events (see saber_get_stats); default 0 */
     int32_t long_doc_tokens;/* documents longer than this use a 256-thread workgroup in CountByDZ; default 512 */
@@ -150,6 +151,11 @@ int saber_get_stats(saber_ctx *ctx, saber_stats *out);
 int saber_reset_stats(saber_ctx *ctx);
 /* HIP stream the library launches on (a hipStream_t), for callers that want to order work against it. */
 int saber_get_stream(saber_ctx *ctx, void **hip_stream);
+
+/* Measurement aid, independent of any context: copies `bytes` bytes device-to-device `reps` times with a
+ * plain streaming kernel and reports read+write bandwidth in GB/s (the achievable-HBM yardstick, and the
+ * kernel the profiler's FETCH_SIZE / WRITE_SIZE counters are calibrated against). */
+int saber_bandwidth_probe(int64_t bytes, int32_t reps, double *gb_per_s);
 
 #ifdef __cplusplus
 }

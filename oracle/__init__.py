@@ -22,7 +22,9 @@ c_f32, c_f64, c_int = ctypes.c_float, ctypes.c_double, ctypes.c_int
 
 
 def build(force: bool = False) -> str:
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    """Compile the oracle with gcc.  Without ``force`` an existing library is used as it is: rebuild
+    (``python __graft_entry__.py``) after editing the C source."""
+    if force or not os.path.exists(_LIB):
         tmp = _LIB + ".tmp%d" % os.getpid()
         subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
@@ -60,6 +62,7 @@ def lib():
         "orc_model_set_z": (c_int, [c_void_p, c_void_p, c_u32]),
         "orc_model_iterate": (c_int, [c_void_p, c_i32, c_int]),
         "orc_model_estep_detail": (None, [c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int]),
+        "orc_model_sample_tokens": (None, [c_void_p, c_void_p, c_i64, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
         "orc_model_loglik": (c_f64, [c_void_p]),
         "orc_model_iter": (c_u32, [c_void_p]),
     }
@@ -214,6 +217,13 @@ class Model:
         z = np.empty(T, dtype=np.int32); S = np.empty(T); p = np.empty(T)
         br = np.empty(T, dtype=np.int8); mg = np.empty(T)
         lib().orc_model_estep_detail(self._h, _p(z), _p(S), _p(p), _p(br), _p(mg), nthreads)
+        return z, S, p, br, mg
+
+    def sample_tokens(self, tok):
+        """Alg. 2 for the listed tokens only (iteration iter+1), from the current state."""
+        tok = np.ascontiguousarray(tok, dtype=np.int64); n = tok.size
+        z = np.empty(n, dtype=np.int32); S = np.empty(n); p = np.empty(n); br = np.empty(n, dtype=np.int8); mg = np.empty(n)
+        lib().orc_model_sample_tokens(self._h, _p(tok), n, _p(z), _p(S), _p(p), _p(br), _p(mg))
         return z, S, p, br, mg
 
     def loglik(self):

@@ -375,6 +375,27 @@ void orc_model_estep_detail(orc_model *m, int32_t *z_out, double *out_S, double 
               m->phi, m->c32, m->sum64, m->seed, m->iter + 1, z_out, out_S, out_p, out_branch, out_margin, nthreads);
 }
 
+/* Alg. 2 for a list of tokens (canonical indices), from the model's current state, for iteration m->iter + 1 */
+void orc_model_sample_tokens(orc_model *m, const int64_t *tok, int64_t n, int32_t *z_out, double *out_S,
+                             double *out_p, int8_t *out_branch, double *out_margin) {
+    for (int64_t i = 0; i < n; i++) {
+        int64_t t = tok[i];
+        /* document of token t: last d with doc_ptr[d] <= t */
+        int64_t lo = 0, hi = m->D - 1;
+        while (lo < hi) { int64_t mid = lo + (hi - lo + 1) / 2; if (m->doc_ptr[mid] <= t) lo = mid; else hi = mid - 1; }
+        int64_t d = lo, a = m->cd_ptr[d]; int32_t nnz = (int32_t)(m->cd_ptr[d + 1] - a);
+        int32_t w = m->word_ids[t];
+        double u0, u1; orc_token_uniforms(m->seed, (uint64_t)t, m->iter + 1, &u0, &u1);
+        orc_detail det;
+        z_out[i] = orc_sample(nnz, m->cd_topic + a, m->cd_count + a, m->phi + (size_t)w * (size_t)m->K,
+                              m->c32 + (size_t)w * (size_t)m->K, m->K, (double)m->alpha * m->sum64[w], u0, u1, &det);
+        if (out_S) out_S[i] = det.S;
+        if (out_p) out_p[i] = det.p_sparse;
+        if (out_branch) out_branch[i] = (int8_t)det.branch;
+        if (out_margin) out_margin[i] = det.margin;
+    }
+}
+
 double orc_model_loglik(orc_model *m) {
     return orc_loglik(m->D, m->doc_ptr, m->word_ids, m->K, m->alpha, m->cd_ptr, m->cd_topic, m->cd_count,
                       m->phi, m->sum64);

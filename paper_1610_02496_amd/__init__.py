@@ -3,6 +3,7 @@
 ``Saber`` wraps the ``saber_*`` calls of ``include/saber.h``; the work is done by
 the HIP kernels in ``csrc/``.
 """
-from .binding import (EXPORTS, Options, Saber, SaberError, Stats, library_path, load_library, options_default)
+from .binding import (EXPORTS, Options, Saber, SaberError, Stats, bandwidth_probe, library_path, load_library,
+                      options_default)
 
-__all__ = ["EXPORTS", "Options", "Saber", "SaberError", "Stats", "library_path", "load_library", "options_default"]
+__all__ = ["EXPORTS", "Options", "Saber", "SaberError", "Stats", "bandwidth_probe", "library_path", "load_library", "options_default"]

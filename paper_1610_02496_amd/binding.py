@@ -20,7 +20,7 @@ _STATUS = {0: "SABER_OK", -1: "SABER_EINVAL", -2: "SABER_ENOMEM", -3: "SABER_EDE
 EXPORTS = ["saber_options_default", "saber_init_ex", "saber_init", "saber_iterate", "saber_counts_nnz",
            "saber_counts", "saber_loglik", "saber_free", "saber_last_error", "saber_get_z", "saber_set_z",
            "saber_get_iteration", "saber_token_probs", "saber_get_phi", "saber_get_stats", "saber_reset_stats",
-           "saber_get_stream"]
+           "saber_get_stream", "saber_bandwidth_probe"]
 
 
 class SaberError(RuntimeError):
@@ -82,6 +82,7 @@ def load_library():
         "saber_get_stats": (ctypes.c_int, [vp, vp]),
         "saber_reset_stats": (ctypes.c_int, [vp]),
         "saber_get_stream": (ctypes.c_int, [vp, vp]),
+        "saber_bandwidth_probe": (ctypes.c_int, [i64, i32, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -103,6 +104,13 @@ def options_default() -> Options:
     o = Options()
     load_library().saber_options_default(ctypes.addressof(o))
     return o
+
+
+def bandwidth_probe(nbytes=1 << 30, reps=10) -> float:
+    """Read+write GB/s of a plain device-to-device copy kernel."""
+    v = ctypes.c_double()
+    _check(load_library().saber_bandwidth_probe(int(nbytes), int(reps), ctypes.addressof(v)))
+    return v.value
 
 
 class Saber:

@@ -98,7 +98,7 @@ static inline int grid_for(int64_t n, int block, int cap = 65535 * 16) {
 extern "C" void saber_options_default(saber_options *opt) {
     if (!opt) return;
     memset(opt, 0, sizeof(*opt));
-    opt->n_chunks = 1; opt->block_threads = 256; opt->tile_tokens = 2048; opt->stage_phi = 1; opt->profile = 0;
+    opt->n_chunks = 1; opt->block_threads = 0; opt->tile_tokens = 4096; opt->stage_phi = 1; opt->profile = 0;
     opt->long_doc_tokens = 512; opt->dz_lds_entries = 8192;
 }
 
@@ -397,6 +397,11 @@ extern "C" int saber_init_ex(saber_ctx **out, const int64_t *doc_ptr, const int3
         opt.stage_phi = opt_in->stage_phi; opt.profile = opt_in->profile;
         if (opt_in->stage_phi < 0) opt.stage_phi = 1;
     }
+    if (opt.block_threads <= 0) {
+        // automatic: rows of Bhat above 32 KB leave room for few workgroups per CU, so make them larger
+        const size_t row_bytes = ((size_t)((K + 63) / 64 * 64)) * sizeof(float);
+        opt.block_threads = (opt.stage_phi && row_bytes >= 32 * 1024 && row_bytes <= 60 * 1024) ? 512 : 256;
+    }
     if (opt.block_threads % 64 || opt.block_threads < 64 || opt.block_threads > 1024)
         return fail(SABER_EINVAL, "saber_init: block_threads must be a multiple of 64 in [64,1024]");
     if (opt.n_chunks > 65536) return fail(SABER_EINVAL, "saber_init: n_chunks too large");
@@ -684,5 +689,35 @@ extern "C" int saber_reset_stats(saber_ctx *c) {
 extern "C" int saber_get_stream(saber_ctx *c, void **s) {
     if (!c || !s) return fail(SABER_EINVAL, "saber_get_stream: null argument");
     *s = (void *)c->stream;
+    return SABER_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// bandwidth probe (measurement aid; independent of any context)
+// ------------------------------------------------------------------------------------------------
+extern "C" int saber_bandwidth_probe(int64_t bytes, int32_t reps, double *gb_per_s) {
+    if (bytes < 16 || reps < 1 || !gb_per_s) return fail(SABER_EINVAL, "saber_bandwidth_probe: bad argument");
+    const size_t n16 = (size_t)bytes / 16;
+    uint4 *src = nullptr, *dst = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    int rc = SABER_OK;
+    auto cleanup = [&]() { dev_free(src); dev_free(dst); if (e0) (void)hipEventDestroy(e0); if (e1) (void)hipEventDestroy(e1); };
+    if ((rc = dev_alloc(&src, n16)) || (rc = dev_alloc(&dst, n16))) { cleanup(); return rc; }
+    hipError_t e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(8192), dim3(256), 0, 0, (uint32_t *)src, 1u, n16 * 4);
+        hipLaunchKernelGGL(copy_probe_kernel, dim3(8192), dim3(256), 0, 0, src, dst, n16);   // warm-up
+        e = hipEventRecord(e0, 0);
+        for (int r = 0; r < reps; r++) hipLaunchKernelGGL(copy_probe_kernel, dim3(8192), dim3(256), 0, 0, src, dst, n16);
+        if (e == hipSuccess) e = hipEventRecord(e1, 0);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+        if (e == hipSuccess) e = hipGetLastError();
+    }
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    cleanup();
+    if (e != hipSuccess) return fail(SABER_EDEVICE, "saber_bandwidth_probe: %s", hipGetErrorString(e));
+    *gb_per_s = 2.0 * (double)(n16 * 16) * reps / ((double)ms * 1e-3) / 1e9;   // read + write
     return SABER_OK;
 }

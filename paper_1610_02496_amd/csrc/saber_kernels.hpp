@@ -535,4 +535,11 @@ __global__ void row_stats_kernel(const uint2 *docrec, const int64_t *doc_ptr, in
     if (lane_id() == 0) { atomicAdd(&out2[0], (unsigned long long)nnz); atomicAdd(&out2[1], (unsigned long long)reads); }
 }
 
+// Plain streaming copy (16 bytes per lane per step): the yardstick for achievable HBM bandwidth and the
+// calibration kernel for the profiler's FETCH_SIZE / WRITE_SIZE counters.
+__global__ void copy_probe_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n16) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
 }  // namespace saber

@@ -275,3 +275,14 @@ def test_config1_likelihood_rises():
     m = oracle.Model(c.doc_ptr, c.word_ids, s.V, s.K, s.alpha, s.beta, s.seed)
     ll0 = m.loglik(); m.iterate(10); ll10 = m.loglik()
     assert ll10 > ll0 + 0.05
+
+
+def test_sample_tokens_is_the_estep_restricted_to_a_list():
+    c = small_corpus(seed=13, D=50, V=80, K=10, mean_len=30.0)
+    m = oracle.Model(c.doc_ptr, c.word_ids, c.spec.V, 10, 0.7, 0.01, 3)
+    m.iterate(1)
+    z, S, p, br, mg = m.estep_detail()
+    tok = np.random.default_rng(0).choice(c.T, 200, replace=False)
+    z2, S2, p2, br2, mg2 = m.sample_tokens(tok)
+    assert np.array_equal(z2, z[tok]) and np.array_equal(S2, S[tok]) and np.array_equal(mg2, mg[tok])
+    assert np.array_equal(br2, br[tok]) and np.array_equal(p2, p[tok])
