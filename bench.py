@@ -32,18 +32,19 @@ def log(*a):
 def algorithmic_bytes(st, K, z_bytes, chunks_words_present):
     """HBM bytes the sampling kernel must move for the iterations counted in ``st`` (model stated in the design doc).
 
-    per token : 4 (document id) + 4 (token index) + 8 (row descriptor) + 4*K_d (packed row of A)
-                + z_bytes (assignment written) + 4 (one count added to B)
-    per dense-branch token : 256 B per searched tree level below the top (one 64-float line each)
-    per (word, chunk) with tokens : the Bhat row staged once, 4*Kpad, plus its total, 4
-    Bhat gathers are served from LDS and count as zero.
+    per token : 4 (document id) + 4 (token index) + 8 (row descriptor) + z_bytes (assignment written)
+                + 4 (one count added to B)
+    per run of consecutive tokens of one (word, document) pair : 4*K_d (the packed row of A, fetched once)
+    per (word, chunk) with tokens : the Bhat row, the tree level above it and the block bases, staged once:
+                4*Kpad + 4*n3pad + 8*n3, plus the row total, 4
+    Bhat gathers and the dense branch are served from LDS and count as zero.
     """
     kpad = (K + 63) // 64 * 64
-    levels = 2 if kpad // 64 <= 64 else 3
-    tok = st["sum_tokens"] * (4 + 4 + 8 + z_bytes + 4) + 4 * st["sum_row_entries"]
-    dense = st["sum_tokens_dense"] * 256 * levels
-    stage = st["iterations"] * chunks_words_present * (4 * kpad + 4)
-    return tok + dense + stage
+    n3 = kpad // 64
+    n3pad = (n3 + 63) // 64 * 64
+    tok = st["sum_tokens"] * (4 + 4 + 8 + z_bytes + 4) + 4 * st["sum_row_fetch"]
+    stage = st["iterations"] * chunks_words_present * (4 * kpad + 4 * n3pad + 8 * n3 + 4)
+    return tok + stage
 
 
 def run_gpu(corpus, K, steps, warmup, opts):
@@ -75,6 +76,7 @@ def run_gpu(corpus, K, steps, warmup, opts):
         "ms_sample": ms_sample / steps, "ms_count_dz": st["ms_count_dz"] / steps, "ms_ck": st["ms_ck"] / steps,
         "ms_phi": st["ms_phi"] / steps,
         "mean_Kd_per_token": st["sum_row_entries"] / max(1, st["sum_tokens"]),
+        "row_entries_fetched_per_token": st["sum_row_fetch"] / max(1, st["sum_tokens"]),
         "dense_fraction": st["sum_tokens_dense"] / max(1, st["sum_tokens"]),
         "bytes_per_token_model": bytes_total / max(1, st["sum_tokens"]),
         "nnz_cd": st["nnz_cd"], "loglik": ll, "iterations_run": warmup + steps,

@@ -77,7 +77,10 @@ typedef struct saber_stats {
     int64_t tokens;           /* T */
     int64_t words_present;    /* (word, chunk) pairs with at least one token */
     int64_t tiles;            /* workgroups of one E-step */
-    int64_t reserved[8];
+    int64_t sum_row_fetch;    /* like sum_row_entries, counting a row once per run of consecutive tokens of one
+                                 (word, document) pair: the entries the sampler has to fetch */
+    int64_t next_row_fetch;   /* sum_d K_d * U_d, U_d = distinct words of document d */
+    int64_t reserved[6];
 } saber_stats;
 
 /* Fill *opt with the defaults. */
@@ -143,7 +146,8 @@ int saber_get_iteration(saber_ctx *ctx, uint32_t *iter);
 int saber_token_probs(saber_ctx *ctx, const int64_t *tok, int64_t m, float *S, float *Q, float *p_sparse);
 
 /* Rows of Bhat (Eq. 2) and of the per-word inclusive prefix table (bottom tree level) for m words:
- * phi[m*K], prefix[m*K]; either may be NULL. */
+ * phi[m*K], prefix[m*K]; either may be NULL.  The prefix rows are not kept in memory; they are rebuilt here with
+ * the arithmetic of the sampler's dense branch. */
 int saber_get_phi(saber_ctx *ctx, const int32_t *words, int32_t m, float *phi, float *prefix);
 
 /* ---- measurement ---- */

@@ -41,7 +41,8 @@ class Stats(ctypes.Structure):
                 ("sample_launches", ctypes.c_int64), ("sum_tokens", ctypes.c_int64),
                 ("sum_tokens_dense", ctypes.c_int64), ("sum_row_entries", ctypes.c_int64),
                 ("nnz_cd", ctypes.c_int64), ("next_row_entries", ctypes.c_int64), ("tokens", ctypes.c_int64),
-                ("words_present", ctypes.c_int64), ("tiles", ctypes.c_int64), ("reserved", ctypes.c_int64 * 8)]
+                ("words_present", ctypes.c_int64), ("tiles", ctypes.c_int64), ("sum_row_fetch", ctypes.c_int64),
+                ("next_row_fetch", ctypes.c_int64), ("reserved", ctypes.c_int64 * 6)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_ if n != "reserved"}

@@ -48,11 +48,11 @@ enum { EV_BEGIN = 0, EV_SAMPLE, EV_DZ, EV_CK, EV_PHI, EV_PER_ITER };
 
 struct saber_ctx {
     int64_t D = 0, T = 0;
-    int32_t V = 0, K = 0, Kpad = 0, n3pad = 0, nwords = 0;
+    int32_t V = 0, K = 0, Kpad = 0, n3 = 0, n3pad = 0, nwords = 0;
     float alpha = 0, beta = 0, vbeta = 0;
     uint64_t seed = 0;
     uint32_t iter = 0, topic_bits = 0, topic_mask = 0;
-    bool z16 = false, staged = false;
+    bool z16 = false, staged = false, b16 = false;
     saber_options opt{};
     double ll_const = 0.0;            // sum_d L_d ln(L_d + K alpha)
     int64_t max_doc_len = 0;
@@ -70,8 +70,10 @@ struct saber_ctx {
     int64_t n_short = 0, n_long = 0;
     int32_t *cwk = nullptr;           // [V][Kpad]
     uint32_t *ck = nullptr;           // [K]
-    float *phi = nullptr, *prefix = nullptr, *l3 = nullptr, *sumphi = nullptr;
-    unsigned long long *counters = nullptr; // [kMaxTimedIters] dense-branch counters, one per iteration slot
+    float *phi = nullptr, *l3 = nullptr, *sumphi = nullptr;
+    double *l3_64 = nullptr;          // [V][n3]
+    uint32_t *doc_words = nullptr;    // [D] distinct words of the document
+    unsigned long long *counters = nullptr; // [kMaxTimedIters][4]: dense-branch tokens, nnz(A), sum K_d L_d, sum K_d U_d
     double *ll_partial = nullptr;     // [max tiles per chunk]
     std::vector<Chunk> chunks;
     int64_t total_tiles = 0, max_chunk_tiles = 0;
@@ -107,7 +109,7 @@ extern "C" void saber_free(saber_ctx *c) {
     if (c->stream) (void)hipStreamSynchronize(c->stream);
     dev_free(c->z); dev_free(c->tok_doc); dev_free(c->tok_t); dev_free(c->tiles); dev_free(c->docrec);
     dev_free(c->cd_ent); dev_free(c->doc_ptr); dev_free(c->short_docs); dev_free(c->long_docs); dev_free(c->cwk);
-    dev_free(c->ck); dev_free(c->phi); dev_free(c->prefix); dev_free(c->l3); dev_free(c->sumphi);
+    dev_free(c->ck); dev_free(c->phi); dev_free(c->l3_64); dev_free(c->l3); dev_free(c->sumphi); dev_free(c->doc_words);
     dev_free(c->counters); dev_free(c->ll_partial);
     if (c->have_events) for (auto &e : c->ev) if (e) (void)hipEventDestroy(e);
     if (c->stream) (void)hipStreamDestroy(c->stream);
@@ -122,25 +124,35 @@ static EStepParams make_params(saber_ctx *c, const Chunk &ch) {
     p.tiles = c->tiles + ch.tile0;
     p.tok_doc = c->tok_doc + ch.t0; p.tok_t = c->tok_t + ch.t0;
     p.docrec = c->docrec; p.cd_ent = c->cd_ent;
-    p.phi = c->phi; p.prefix = c->prefix; p.l3 = c->l3; p.sumphi = c->sumphi;
+    p.phi = c->phi; p.l3 = c->l3; p.l3_64 = c->l3_64; p.sumphi = c->sumphi;
     p.z = c->z; p.cwk = c->cwk;
-    p.t_base = ch.t0; p.K = c->K; p.Kpad = c->Kpad; p.n3pad = c->n3pad;
+    p.t_base = ch.t0; p.K = c->K; p.Kpad = c->Kpad; p.n3 = c->n3; p.n3pad = c->n3pad;
     p.topic_bits = c->topic_bits; p.topic_mask = c->topic_mask; p.alpha = c->alpha;
     p.seed_lo = (uint32_t)c->seed; p.seed_hi = (uint32_t)(c->seed >> 32); p.iter = c->iter;
     return p;
+}
+
+static size_t estep_lds_bytes(const saber_ctx *c) {
+    return (size_t)c->n3 * sizeof(double) + ((size_t)c->Kpad + (size_t)c->n3pad) * sizeof(float);
+}
+
+template <int MODE, bool STAGED, typename ZT>
+static void launch_estep_b16(saber_ctx *c, dim3 grid, dim3 block, size_t lds, const EStepParams &p) {
+    if (c->b16) hipLaunchKernelGGL((estep_kernel<MODE, STAGED, ZT, true>), grid, block, lds, c->stream, p);
+    else hipLaunchKernelGGL((estep_kernel<MODE, STAGED, ZT, false>), grid, block, lds, c->stream, p);
 }
 
 template <int MODE>
 static int launch_estep(saber_ctx *c, const Chunk &ch, EStepParams &p) {
     if (ch.ntiles == 0) return SABER_OK;
     const dim3 grid((unsigned)ch.ntiles), block((unsigned)c->opt.block_threads);
-    const size_t lds = c->staged ? ((size_t)c->Kpad + (size_t)c->n3pad) * sizeof(float) : 0;
+    const size_t lds = c->staged ? estep_lds_bytes(c) : 0;
     if (c->staged) {
-        if (c->z16) hipLaunchKernelGGL((estep_kernel<MODE, true, uint16_t>), grid, block, lds, c->stream, p);
-        else hipLaunchKernelGGL((estep_kernel<MODE, true, int32_t>), grid, block, lds, c->stream, p);
+        if (c->z16) launch_estep_b16<MODE, true, uint16_t>(c, grid, block, lds, p);
+        else launch_estep_b16<MODE, true, int32_t>(c, grid, block, lds, p);
     } else {
-        if (c->z16) hipLaunchKernelGGL((estep_kernel<MODE, false, uint16_t>), grid, block, lds, c->stream, p);
-        else hipLaunchKernelGGL((estep_kernel<MODE, false, int32_t>), grid, block, lds, c->stream, p);
+        if (c->z16) launch_estep_b16<MODE, false, uint16_t>(c, grid, block, lds, p);
+        else launch_estep_b16<MODE, false, int32_t>(c, grid, block, lds, p);
     }
     HIP_TRY(hipGetLastError());
     return SABER_OK;
@@ -176,11 +188,11 @@ static int launch_count_dz(saber_ctx *c) {
     return SABER_OK;
 }
 
-// nnz(A) and sum_d K_d * L_d (the row entries the next E-step will read) into two device counters
+// nnz(A), sum_d K_d L_d and sum_d K_d U_d (what the next E-step will read) into three device counters
 static int launch_row_stats(saber_ctx *c, unsigned long long *out2) {
     if (c->D == 0) return SABER_OK;
-    hipLaunchKernelGGL(row_stats_kernel, dim3(grid_for(c->D, 256, 4096)), dim3(256), 0, c->stream, c->docrec,
-                       c->doc_ptr, c->D, out2);
+    hipLaunchKernelGGL(row_stats_kernel, dim3(grid_for(c->D, 256, 1024)), dim3(256), 0, c->stream, c->docrec,
+                       c->doc_ptr, c->doc_words, c->D, out2);
     HIP_TRY(hipGetLastError());
     return SABER_OK;
 }
@@ -204,8 +216,8 @@ static int launch_topic_totals(saber_ctx *c) {
 }
 
 static int launch_phi(saber_ctx *c) {
-    hipLaunchKernelGGL(phi_prefix_kernel, dim3((unsigned)c->V), dim3(256), 0, c->stream, c->cwk, c->ck, c->phi,
-                       c->prefix, c->l3, c->sumphi, c->K, c->Kpad, c->n3pad, c->beta, c->vbeta, 1);
+    hipLaunchKernelGGL(phi_tree_kernel, dim3((unsigned)c->V), dim3(256), 0, c->stream, c->cwk, c->ck, c->phi,
+                       c->l3, c->l3_64, c->sumphi, c->K, c->Kpad, c->n3, c->n3pad, c->beta, c->vbeta, 1);
     HIP_TRY(hipGetLastError());
     return SABER_OK;
 }
@@ -241,9 +253,9 @@ static int refresh_workload_stats(saber_ctx *c) {
     HIP_TRY(hipGetLastError());
     SABER_TRY(launch_row_stats(c, c->counters + 1));
     HIP_TRY(hipStreamSynchronize(c->stream));
-    unsigned long long h[3];
+    unsigned long long h[4];
     HIP_TRY(hipMemcpy(h, c->counters, sizeof(h), hipMemcpyDeviceToHost));
-    c->stats.nnz_cd = (int64_t)h[1]; c->stats.next_row_entries = (int64_t)h[2];
+    c->stats.nnz_cd = (int64_t)h[1]; c->stats.next_row_entries = (int64_t)h[2]; c->stats.next_row_fetch = (int64_t)h[3];
     return SABER_OK;
 }
 
@@ -305,6 +317,16 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     // ---- rows of A: fixed, 128-byte aligned slots of capacity min(L_d, K) (Sec. 3.4 aligns rows likewise) ----
     std::vector<uint2> h_rec((size_t)std::max<int64_t>(D, 1));
     std::vector<int32_t> h_short, h_long;
+    std::vector<uint32_t> h_doc_words((size_t)std::max<int64_t>(D, 1));
+    {   // distinct words per document (layout statistic for the bandwidth model)
+        std::vector<int64_t> last_doc((size_t)V, -1);
+        for (int64_t d = 0; d < D; d++) {
+            uint32_t u = 0;
+            for (int64_t t = doc_ptr[d]; t < doc_ptr[d + 1]; t++)
+                if (last_doc[(size_t)word_ids[t]] != d) { last_doc[(size_t)word_ids[t]] = d; u++; }
+            h_doc_words[(size_t)d] = u;
+        }
+    }
     c->doc_len.resize((size_t)D);
     int64_t units = 0; double llc = 0.0;
     for (int64_t d = 0; d < D; d++) {
@@ -327,9 +349,10 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     SABER_TRY(dev_alloc(&c->cd_ent, (size_t)c->cd_cap)); SABER_TRY(dev_alloc(&c->doc_ptr, (size_t)D + 1));
     SABER_TRY(dev_alloc(&c->short_docs, h_short.size())); SABER_TRY(dev_alloc(&c->long_docs, h_long.size()));
     SABER_TRY(dev_alloc(&c->cwk, vk)); SABER_TRY(dev_alloc(&c->ck, (size_t)K));
-    SABER_TRY(dev_alloc(&c->phi, vk)); SABER_TRY(dev_alloc(&c->prefix, vk));
+    SABER_TRY(dev_alloc(&c->phi, vk)); SABER_TRY(dev_alloc(&c->l3_64, (size_t)V * (size_t)c->n3));
+    SABER_TRY(dev_alloc(&c->doc_words, (size_t)D));
     SABER_TRY(dev_alloc(&c->l3, (size_t)V * (size_t)c->n3pad)); SABER_TRY(dev_alloc(&c->sumphi, (size_t)V));
-    SABER_TRY(dev_alloc(&c->counters, (size_t)kMaxTimedIters * 3));
+    SABER_TRY(dev_alloc(&c->counters, (size_t)kMaxTimedIters * 4));
     SABER_TRY(dev_alloc(&c->ll_partial, (size_t)std::max<int64_t>(c->max_chunk_tiles, 1)));
     if (T) {
         HIP_TRY(hipMemcpy(c->tok_doc, h_tok_doc.data(), sizeof(int32_t) * (size_t)T, hipMemcpyHostToDevice));
@@ -337,6 +360,7 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     }
     if (!h_tiles.empty()) HIP_TRY(hipMemcpy(c->tiles, h_tiles.data(), sizeof(Tile) * h_tiles.size(), hipMemcpyHostToDevice));
     if (D) HIP_TRY(hipMemcpy(c->docrec, h_rec.data(), sizeof(uint2) * (size_t)D, hipMemcpyHostToDevice));
+    if (D) HIP_TRY(hipMemcpy(c->doc_words, h_doc_words.data(), sizeof(uint32_t) * (size_t)D, hipMemcpyHostToDevice));
     HIP_TRY(hipMemcpy(c->doc_ptr, doc_ptr, sizeof(int64_t) * ((size_t)D + 1), hipMemcpyHostToDevice));
     if (!h_short.empty()) HIP_TRY(hipMemcpy(c->short_docs, h_short.data(), sizeof(int32_t) * h_short.size(), hipMemcpyHostToDevice));
     if (!h_long.empty()) HIP_TRY(hipMemcpy(c->long_docs, h_long.data(), sizeof(int32_t) * h_long.size(), hipMemcpyHostToDevice));
@@ -383,6 +407,8 @@ extern "C" int saber_init_ex(saber_ctx **out, const int64_t *doc_ptr, const int3
         if (word_ids[t] < 0 || word_ids[t] >= V)
             return fail(SABER_EINVAL, "saber_init: word id %d at token %lld is outside [0,%d)", word_ids[t], (long long)t, V);
     uint32_t bits = 1; while ((1u << bits) < (uint32_t)K) bits++;
+    const bool b16 = K <= 65536 && maxlen < 65536;   // the common case: topic and count both fit 16 bits
+    if (b16) bits = 16;
     if (maxlen >= (1ll << (32 - bits)))
         return fail(SABER_ERANGE, "saber_init: longest document (%lld tokens) does not fit the %u count bits left by K = %d",
                     (long long)maxlen, 32 - bits, K);
@@ -415,11 +441,13 @@ extern "C" int saber_init_ex(saber_ctx **out, const int64_t *doc_ptr, const int3
     if (!c) return fail(SABER_ENOMEM, "saber_init: out of host memory");
     c->D = D; c->T = T; c->V = V; c->K = K; c->alpha = alpha; c->beta = beta; c->seed = seed; c->opt = opt;
     c->Kpad = (K + 63) / 64 * 64;
-    c->n3pad = ((c->Kpad / 64) + 63) / 64 * 64;
+    c->n3 = c->Kpad / 64;
+    c->n3pad = (c->n3 + 63) / 64 * 64;
+    c->b16 = b16;
     c->nwords = (K + 31) / 32;
     c->topic_bits = bits; c->topic_mask = (1u << bits) - 1u;
     c->z16 = K <= 65536;
-    c->staged = opt.stage_phi && ((size_t)c->Kpad + (size_t)c->n3pad) * sizeof(float) <= 60 * 1024;
+    c->staged = opt.stage_phi && estep_lds_bytes(c) <= 60 * 1024;
     c->vbeta = (float)V * beta;
     c->max_doc_len = maxlen;
     int rc;
@@ -447,7 +475,7 @@ extern "C" int saber_iterate(saber_ctx *c, int32_t n) {
         const int batch = std::min<int32_t>(n - done, kMaxTimedIters);
         // per-iteration device counters: {dense-branch tokens, nnz(A), sum_d K_d L_d}
         hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, c->stream, (uint32_t *)c->counters, 0u,
-                           (size_t)kMaxTimedIters * 6);
+                           (size_t)kMaxTimedIters * 8);
         HIP_TRY(hipGetLastError());
         for (int b = 0; b < batch; b++) {
             hipEvent_t *ev = c->ev + (size_t)b * EV_PER_ITER;
@@ -456,7 +484,7 @@ extern "C" int saber_iterate(saber_ctx *c, int32_t n) {
             // E-step: z <- Sample(A_d, Bhat_v, Q_v, T_v) for every token; B accumulates as a by-product
             for (const Chunk &ch : c->chunks) {
                 EStepParams p = make_params(c, ch);
-                p.n_dense = c->counters + 3 * b;
+                p.n_dense = c->counters + 4 * b;
                 SABER_TRY(launch_estep<MODE_SAMPLE>(c, ch, p));
             }
             if (prof) HIP_TRY(hipEventRecord(ev[EV_SAMPLE], c->stream));
@@ -467,18 +495,20 @@ extern "C" int saber_iterate(saber_ctx *c, int32_t n) {
             if (prof) HIP_TRY(hipEventRecord(ev[EV_CK], c->stream));
             SABER_TRY(launch_phi(c));
             if (prof) HIP_TRY(hipEventRecord(ev[EV_PHI], c->stream));
-            SABER_TRY(launch_row_stats(c, c->counters + 3 * b + 1));
+            SABER_TRY(launch_row_stats(c, c->counters + 4 * b + 1));
         }
         HIP_TRY(hipStreamSynchronize(c->stream));
-        unsigned long long h[kMaxTimedIters * 3];
+        unsigned long long h[kMaxTimedIters * 4];
         HIP_TRY(hipMemcpy(h, c->counters, sizeof(h), hipMemcpyDeviceToHost));
         for (int b = 0; b < batch; b++) {
             // the E-step of this iteration read the rows counted at the end of the previous one
             c->stats.sum_tokens += c->T;
-            c->stats.sum_tokens_dense += (int64_t)h[3 * b];
+            c->stats.sum_tokens_dense += (int64_t)h[4 * b];
             c->stats.sum_row_entries += c->stats.next_row_entries;
-            c->stats.nnz_cd = (int64_t)h[3 * b + 1];
-            c->stats.next_row_entries = (int64_t)h[3 * b + 2];
+            c->stats.sum_row_fetch += c->stats.next_row_fetch;
+            c->stats.nnz_cd = (int64_t)h[4 * b + 1];
+            c->stats.next_row_entries = (int64_t)h[4 * b + 2];
+            c->stats.next_row_fetch = (int64_t)h[4 * b + 3];
             if (prof) {
                 hipEvent_t *ev = c->ev + (size_t)b * EV_PER_ITER;
                 float ms[4], tot;
@@ -664,11 +694,29 @@ extern "C" int saber_token_probs(saber_ctx *c, const int64_t *tok, int64_t m, fl
 
 extern "C" int saber_get_phi(saber_ctx *c, const int32_t *words, int32_t m, float *phi, float *prefix) {
     if (!c || (m > 0 && !words) || m < 0) return fail(SABER_EINVAL, "saber_get_phi: bad argument");
-    for (int32_t i = 0; i < m; i++) {
+    for (int32_t i = 0; i < m; i++)
         if (words[i] < 0 || words[i] >= c->V) return fail(SABER_EINVAL, "saber_get_phi: word %d is outside [0,%d)", words[i], c->V);
-        const size_t off = (size_t)words[i] * (size_t)c->Kpad;
-        if (phi) HIP_TRY(hipMemcpy(phi + (size_t)i * (size_t)c->K, c->phi + off, sizeof(float) * (size_t)c->K, hipMemcpyDeviceToHost));
-        if (prefix) HIP_TRY(hipMemcpy(prefix + (size_t)i * (size_t)c->K, c->prefix + off, sizeof(float) * (size_t)c->K, hipMemcpyDeviceToHost));
+    if (m == 0) return SABER_OK;
+    if (phi)
+        for (int32_t i = 0; i < m; i++)
+            HIP_TRY(hipMemcpy(phi + (size_t)i * (size_t)c->K, c->phi + (size_t)words[i] * (size_t)c->Kpad,
+                              sizeof(float) * (size_t)c->K, hipMemcpyDeviceToHost));
+    if (prefix) {
+        // the bottom tree level is not stored: rebuild the requested rows the way the dense branch does
+        int32_t *dw = nullptr; float *dout = nullptr;
+        int rc;
+        if ((rc = dev_alloc(&dw, (size_t)m)) || (rc = dev_alloc(&dout, (size_t)m * (size_t)c->K))) { dev_free(dw); dev_free(dout); return rc; }
+        hipError_t e = hipMemcpy(dw, words, sizeof(int32_t) * (size_t)m, hipMemcpyHostToDevice);
+        if (e == hipSuccess) {
+            const int64_t items = (int64_t)m * ((c->K + 63) / 64);
+            hipLaunchKernelGGL(prefix_export_kernel, dim3((unsigned)items), dim3(64), 0, c->stream, c->phi, c->l3_64, dw, m,
+                               c->K, c->Kpad, c->n3, dout);
+            e = hipGetLastError();
+        }
+        if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+        if (e == hipSuccess) e = hipMemcpy(prefix, dout, sizeof(float) * (size_t)m * (size_t)c->K, hipMemcpyDeviceToHost);
+        dev_free(dw); dev_free(dout);
+        if (e != hipSuccess) return fail(SABER_EDEVICE, "saber_get_phi: %s", hipGetErrorString(e));
     }
     return SABER_OK;
 }
@@ -682,7 +730,7 @@ extern "C" int saber_get_stats(saber_ctx *c, saber_stats *out) {
 extern "C" int saber_reset_stats(saber_ctx *c) {
     if (!c) return fail(SABER_EINVAL, "saber_reset_stats: null context");
     c->stats.iterations = 0; c->stats.ms_sample = c->stats.ms_count_dz = c->stats.ms_ck = c->stats.ms_phi = c->stats.ms_total = 0.0;
-    c->stats.sample_launches = 0; c->stats.sum_tokens = c->stats.sum_tokens_dense = c->stats.sum_row_entries = 0;
+    c->stats.sample_launches = 0; c->stats.sum_tokens = c->stats.sum_tokens_dense = c->stats.sum_row_entries = c->stats.sum_row_fetch = 0;
     return SABER_OK;
 }
 

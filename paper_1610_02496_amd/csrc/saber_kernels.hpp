@@ -134,9 +134,10 @@ struct EStepParams {
     const uint2 *docrec;        // [D] {row start in units of 32 entries, K_d}
     const uint32_t *cd_ent;     // packed rows of A: topic | count << topic_bits, ascending topic
     const float *phi;           // [V][Kpad]  Bhat
-    const float *prefix;        // [V][Kpad]  inclusive prefix sums of the Bhat row, padded with the total
-    const float *l3;            // [V][n3pad] every 64th prefix entry, padded with the total
-    const float *sumphi;        // [V]        prefix[K-1]
+    const float *l3;            // [V][n3pad] binary32 prefix sum of the Bhat row at the end of every 64-topic block,
+                                //            padded with the row total (tree level above the bottom)
+    const double *l3_64;        // [V][n3]    the same running sums before rounding (base of each bottom block)
+    const float *sumphi;        // [V]        prefix sum at topic K-1 = l3[n3-1]
     void *z;                    // [T] assignments, canonical order (uint16 or int32)
     int32_t *cwk;               // [V][Kpad] accumulator of B for the next M-step
     float *out_S;               // probs mode: S per canonical token
@@ -144,7 +145,7 @@ struct EStepParams {
     double *out_ll;             // loglik mode: one partial sum per tile
     unsigned long long *n_dense;// sample mode: dense-branch token counter
     int64_t t_base;             // canonical index of the chunk's first token
-    int32_t K, Kpad, n3pad;
+    int32_t K, Kpad, n3, n3pad;
     uint32_t topic_bits, topic_mask;
     float alpha;
     uint32_t seed_lo, seed_hi, iter;
@@ -152,97 +153,117 @@ struct EStepParams {
 
 enum { MODE_SAMPLE = 0, MODE_PROBS = 1, MODE_LOGLIK = 2 };
 
-// Dense branch (problem 2, Sec. 2.3): position of x in the word's prefix table by a W-ary descent with
-// W = 64 (Sec. 3.2.4).  Level 2 is every 64th entry of level 3 and is read in place.
-__device__ __forceinline__ int tree_query(const float *__restrict__ c, const float *l3,
-                                          int n3pad, int K, float x, int lane) {
+// Dense branch (problem 2, Sec. 2.3): position of x in the prefix sums of the word's Bhat row, by a W-ary
+// descent with W = 64 (Sec. 3.2.4).  Levels above the bottom hold the binary32 prefix sum at the end of
+// every 64-topic block (level 2 is every 64th entry of level 3, read in place).  The bottom level is not
+// stored: the 64 prefix sums of the chosen block are rebuilt from the Bhat values themselves, as
+// round32(base + running sum in binary64), base being the unrounded running sum at the block's start.
+// That is the same number the table would hold, so the search is exact.
+__device__ __forceinline__ int dense_query(const float *phi_row, const float *l3, const double *l3_64, int n3pad,
+                                           int K, float x, int lane) {
     int off3 = 0;
     if (n3pad > kWave) {
-        int n2 = n3pad / kWave;
-        float v2 = (lane < n2) ? l3[(lane + 1) * kWave - 1] : __builtin_inff();
-        int i2 = wave_vote_first(v2 >= x);
+        const int n2 = n3pad / kWave;
+        const float v2 = (lane < n2) ? l3[(lane + 1) * kWave - 1] : __builtin_inff();
+        const int i2 = wave_vote_first(v2 >= x);
         off3 = (i2 < 0 ? n2 - 1 : i2) * kWave;
     }
-    float v3 = l3[off3 + lane];
-    int i3 = wave_vote_first(v3 >= x);
-    int off4 = (off3 + (i3 < 0 ? kWave - 1 : i3)) * kWave;
-    const int Kpad = (K + kWave - 1) / kWave * kWave;
-    if (off4 > Kpad - kWave) off4 = Kpad - kWave;   // cannot happen for finite tables; keeps the read in bounds
-    float v4 = c[off4 + lane];
-    int i4 = wave_vote_first(v4 >= x);
-    int k = off4 + (i4 < 0 ? kWave - 1 : i4);
+    const float v3 = l3[off3 + lane];
+    const int i3 = wave_vote_first(v3 >= x);
+    int blk = off3 + (i3 < 0 ? kWave - 1 : i3);
+    const int nblk = (K + kWave - 1) / kWave;
+    if (blk > nblk - 1) blk = nblk - 1;                 // cannot happen for finite tables; keeps reads in bounds
+    const double base = blk > 0 ? l3_64[blk - 1] : 0.0;
+    const float v4 = (float)(base + wave_incl_scan((double)phi_row[blk * kWave + lane]));
+    const int i4 = wave_vote_first(v4 >= x);
+    const int k = blk * kWave + (i4 < 0 ? kWave - 1 : i4);
     return k < K ? k : K - 1;
 }
 
 // ---------------------------------------------------------------------------------------------
-// E-step (Alg. 2).  One workgroup per tile; the word's Bhat row and the second tree level are staged in
+// E-step (Alg. 2).  One workgroup per tile; the word's Bhat row and the upper tree level are staged in
 // LDS (STAGED) or read from global memory.  Each wavefront takes a batch of up to 64 tokens: the
 // per-token scalars (document, row descriptor, Philox draws) are produced one token per lane, then the
 // wavefront walks the tokens one after another.  A row of A is consumed in blocks of 256 entries, lane l
 // holding entries 4l..4l+3 (one 16-byte load per lane, 1 KB per wavefront): the lane forms its four
 // running partial products, one DPP scan over the lane sums yields both S and every prefix sum, and the
 // draw is located with one ballot plus a four-way compare inside the winning lane.  The first block of
-// the next token is fetched while the current token is processed.
+// the next row is fetched while the current token is processed.  Tokens are ordered by (word, document),
+// so repeated occurrences of a word in a document are neighbours: they share A_d (.) Bhat_v and S, and only
+// the two draws are repeated.
+// B16: entries are packed topic:16 | count:16 (compile-time shifts); otherwise topic_bits is a run-time value.
 // ---------------------------------------------------------------------------------------------
 struct RowBlock { float a0, a1, a2, a3, incl; };   // running sums inside the lane; inclusive scan of lane sums
 
 __device__ __forceinline__ uint4 load_block(const uint32_t *__restrict__ row, int rel_kd, int lane) {
-    // rows are 128-byte aligned and zero-filled up to the next multiple of 4 entries
+    // rows are 128-byte aligned and padded to a multiple of 4 entries with (last topic, count 0)
     uint4 e = make_uint4(0u, 0u, 0u, 0u);
     if (4 * lane < rel_kd) e = *reinterpret_cast<const uint4 *>(row + 4 * lane);
     return e;
 }
 
-template <bool STAGED>
+// Bhat value of the entry's topic
+template <bool STAGED, bool B16>
+__device__ __forceinline__ float phi_of(uint32_t e, uint32_t tmask, const float *lds_phi, const float *__restrict__ phi_row) {
+    return STAGED ? lds_phi[e & tmask] : phi_row[e & tmask];
+}
+
+template <bool STAGED, bool B16>
 __device__ __forceinline__ void block_products(const uint4 e, uint32_t bits, uint32_t tmask,
                                                const float *lds_phi, const float *__restrict__ phi_row, RowBlock &b) {
-    const float f0 = STAGED ? lds_phi[e.x & tmask] : phi_row[e.x & tmask];
-    const float f1 = STAGED ? lds_phi[e.y & tmask] : phi_row[e.y & tmask];
-    const float f2 = STAGED ? lds_phi[e.z & tmask] : phi_row[e.z & tmask];
-    const float f3 = STAGED ? lds_phi[e.w & tmask] : phi_row[e.w & tmask];
+    const float f0 = phi_of<STAGED, B16>(e.x, tmask, lds_phi, phi_row);
+    const float f1 = phi_of<STAGED, B16>(e.y, tmask, lds_phi, phi_row);
+    const float f2 = phi_of<STAGED, B16>(e.z, tmask, lds_phi, phi_row);
+    const float f3 = phi_of<STAGED, B16>(e.w, tmask, lds_phi, phi_row);
     b.a0 = (float)(e.x >> bits) * f0;
-    b.a1 = b.a0 + (float)(e.y >> bits) * f1;
-    b.a2 = b.a1 + (float)(e.z >> bits) * f2;
-    b.a3 = b.a2 + (float)(e.w >> bits) * f3;
+    b.a1 = __builtin_fmaf((float)(e.y >> bits), f1, b.a0);
+    b.a2 = __builtin_fmaf((float)(e.z >> bits), f2, b.a1);
+    b.a3 = __builtin_fmaf((float)(e.w >> bits), f3, b.a2);
     b.incl = wave_incl_scan(b.a3);
 }
 
-// first entry of the block whose prefix sum (carry + sums inside the block) reaches x
+// First entry of the block whose prefix sum (carry + sums inside the block) reaches x.  The lane is found
+// with one ballot over the lanes' inclusive sums, the entry inside it with three compares.  If rounding
+// leaves no entry, the choice falls on the block's last one (a row's padding repeats its last topic).
 __device__ __forceinline__ uint32_t search_block(const uint4 e, const RowBlock &b, float carry, float x, int rel_kd,
-                                                 int lane, uint32_t tmask) {
-    const int nvalid = rel_kd < 4 * kWave ? rel_kd : 4 * kWave;
-    int L = wave_vote_first(carry + b.incl >= x);
-    if (L < 0) L = (nvalid - 1) >> 2;                      // rounding left no entry: the last one
+                                                 uint32_t tmask) {
     const float base = carry + (b.incl - b.a3);
-    int q = (base + b.a0 >= x) ? 0 : (base + b.a1 >= x) ? 1 : (base + b.a2 >= x) ? 2 : 3;
-    const int maxq = nvalid - 1 - 4 * lane;                // never point at the zero fill
-    q = q > maxq ? maxq : q;
-    const uint32_t sel = q <= 0 ? e.x : q == 1 ? e.y : q == 2 ? e.z : e.w;
+    const unsigned long long m3 = __builtin_amdgcn_ballot_w64(carry + b.incl >= x);
+    const int nvalid = rel_kd < 4 * kWave ? rel_kd : 4 * kWave;
+    const int L = m3 ? (int)__builtin_ctzll(m3) : ((nvalid - 1) >> 2);
+    const uint32_t sel = (base + b.a0 >= x) ? e.x : (base + b.a1 >= x) ? e.y : (base + b.a2 >= x) ? e.z : e.w;
     return readlane_u32(sel, L) & tmask;
 }
 
-template <int MODE, bool STAGED, typename ZT>
+template <int MODE, bool STAGED, typename ZT, bool B16>
 __global__ void __launch_bounds__(1024) estep_kernel(EStepParams p) {
-    extern __shared__ float lds_f32[];
+    extern __shared__ double lds_f64[];
     __shared__ double ll_wave[16];
-    float *lds_phi = lds_f32;                 // [Kpad]
-    float *lds_l3 = lds_f32 + p.Kpad;         // [n3pad]
+    // LDS: [Kpad] floats (Bhat row), [n3pad] floats (tree level), [n3] doubles (block bases); Kpad and n3pad are
+    // multiples of 64, so every part keeps 16-byte alignment
+    float *lds_phi = reinterpret_cast<float *>(lds_f64);
+    float *lds_l3 = lds_phi + p.Kpad;
+    double *lds_l3_64 = reinterpret_cast<double *>(lds_l3 + p.n3pad);
     const Tile tile = p.tiles[blockIdx.x];
     const int K = p.K;
     const float *__restrict__ phi_row = p.phi + (size_t)tile.word * (size_t)p.Kpad;
     const float *__restrict__ l3_row = p.l3 + (size_t)tile.word * (size_t)p.n3pad;
+    const double *__restrict__ l3_64_row = p.l3_64 + (size_t)tile.word * (size_t)p.n3;
     if (STAGED) {
         const float4 *src = reinterpret_cast<const float4 *>(phi_row);
         float4 *dst = reinterpret_cast<float4 *>(lds_phi);
         for (int i = threadIdx.x; i < p.Kpad / 4; i += blockDim.x) dst[i] = src[i];
-        if (MODE == MODE_SAMPLE)
+        if (MODE == MODE_SAMPLE) {
             for (int i = threadIdx.x; i < p.n3pad; i += blockDim.x) lds_l3[i] = l3_row[i];
+            for (int i = threadIdx.x; i < p.n3; i += blockDim.x) lds_l3_64[i] = l3_64_row[i];
+        }
         __syncthreads();
     }
     const float sum_w = p.sumphi[tile.word];
     const float Q = p.alpha * sum_w;
-    const int lane = lane_id(), wave = threadIdx.x / kWave, nwaves = blockDim.x / kWave;
-    const uint32_t bits = p.topic_bits, tmask = p.topic_mask;
+    const int lane = lane_id(), nwaves = blockDim.x / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));   // wave-uniform: keeps loop control scalar
+    const uint32_t bits = B16 ? 16u : p.topic_bits, tmask = B16 ? 0xffffu : p.topic_mask;
     double ll_acc = 0.0;
     uint32_t dense_count = 0;
     // batch size: 64 tokens per wavefront, fewer when the tile is too small to keep every wavefront busy
@@ -253,7 +274,7 @@ __global__ void __launch_bounds__(1024) estep_kernel(EStepParams p) {
         const int n = min(bs, tile.count - batch);
         const bool act = lane < n;
         const int i = tile.begin + batch + lane;
-        const int d = act ? p.tok_doc[i] : 0;
+        const int d = act ? p.tok_doc[i] : -1;
         const uint32_t t = act ? p.tok_t[i] : 0u;
         uint2 rec = make_uint2(0u, 0u);
         if (act) rec = p.docrec[d];
@@ -265,62 +286,71 @@ __global__ void __launch_bounds__(1024) estep_kernel(EStepParams p) {
         uint32_t my_z = 0; float my_S = 0.f;
 
         uint4 nxt0 = load_block(p.cd_ent + (size_t)readlane_u32(rec.x, 0) * 32u, (int)readlane_u32(rec.y, 0), lane);
-        for (int s = 0; s < n; s++) {
+        int s = 0;
+        while (s < n) {
+            // the run [s, s_end) of tokens of this word in one document: they share A_d (.) Bhat_v and S
+            const int ds = __builtin_amdgcn_readlane(d, s);
+            const unsigned long long other = __builtin_amdgcn_ballot_w64(d != ds) & (~0ull << s);
+            int s_end = other ? (int)__builtin_ctzll(other) : kWave;
+            s_end = __builtin_amdgcn_readfirstlane(s_end < n ? s_end : n);   // wave-uniform by construction
             const int kd = (int)readlane_u32(rec.y, s);
             const uint32_t *__restrict__ row = p.cd_ent + (size_t)readlane_u32(rec.x, s) * 32u;
             const int nblk = (kd + 4 * kWave - 1) / (4 * kWave);
             const uint4 e0 = nxt0;
             uint4 e1 = make_uint4(0u, 0u, 0u, 0u);
             if (nblk > 1) e1 = load_block(row + 4 * kWave, kd - 4 * kWave, lane);
-            if (s + 1 < n)
-                nxt0 = load_block(p.cd_ent + (size_t)readlane_u32(rec.x, s + 1) * 32u, (int)readlane_u32(rec.y, s + 1), lane);
+            if (s_end < n)
+                nxt0 = load_block(p.cd_ent + (size_t)readlane_u32(rec.x, s_end) * 32u, (int)readlane_u32(rec.y, s_end), lane);
             // element-wise product A_d (.) Bhat_v, its prefix sums and its sum S (Alg. 2, product loop)
             RowBlock b0, b1;
-            block_products<STAGED>(e0, bits, tmask, lds_phi, phi_row, b0);
+            block_products<STAGED, B16>(e0, bits, tmask, lds_phi, phi_row, b0);
             const float t0 = readlane_f32(b0.incl, 63);
             float t1 = 0.f, S = t0;
             if (nblk > 1) {
-                block_products<STAGED>(e1, bits, tmask, lds_phi, phi_row, b1);
+                block_products<STAGED, B16>(e1, bits, tmask, lds_phi, phi_row, b1);
                 t1 = readlane_f32(b1.incl, 63);
                 S = S + t1;
                 for (int blk = 2; blk < nblk; blk++) {
                     RowBlock bb;
-                    block_products<STAGED>(load_block(row + blk * 4 * kWave, kd - blk * 4 * kWave, lane), bits, tmask,
-                                           lds_phi, phi_row, bb);
+                    block_products<STAGED, B16>(load_block(row + blk * 4 * kWave, kd - blk * 4 * kWave, lane), bits, tmask,
+                                                lds_phi, phi_row, bb);
                     S = S + readlane_f32(bb.incl, 63);
                 }
             }
             if (MODE == MODE_SAMPLE) {
-                const float u0s = readlane_f32(u0, s), u1s = readlane_f32(u1, s);
-                uint32_t topic;
-                if (u0s * (S + Q) < S) {
-                    // problem 1: position of x in the prefix sums of P
-                    const float x = u1s * S;
-                    if (nblk == 1 || t0 >= x) topic = search_block(e0, b0, 0.f, x, kd, lane, tmask);
-                    else if (nblk == 2 || t0 + t1 >= x) topic = search_block(e1, b1, t0, x, kd - 4 * kWave, lane, tmask);
-                    else {
-                        float carry = t0 + t1;
-                        topic = 0u;
-                        for (int blk = 2; blk < nblk; blk++) {
-                            const int rel = kd - blk * 4 * kWave;
-                            const uint4 e = load_block(row + blk * 4 * kWave, rel, lane);
-                            RowBlock bb;
-                            block_products<STAGED>(e, bits, tmask, lds_phi, phi_row, bb);
-                            const float tot = readlane_f32(bb.incl, 63);
-                            if (blk == nblk - 1 || carry + tot >= x) { topic = search_block(e, bb, carry, x, rel, lane, tmask); break; }
-                            carry = carry + tot;
+                for (int r = s; r < s_end; r++) {
+                    const float u0s = readlane_f32(u0, r), u1s = readlane_f32(u1, r);
+                    uint32_t topic;
+                    if (u0s * (S + Q) < S) {
+                        // problem 1: position of x in the prefix sums of P
+                        const float x = u1s * S;
+                        if (nblk == 1 || t0 >= x) topic = search_block(e0, b0, 0.f, x, kd, tmask);
+                        else if (nblk == 2 || t0 + t1 >= x) topic = search_block(e1, b1, t0, x, kd - 4 * kWave, tmask);
+                        else {
+                            float carry = t0 + t1;
+                            topic = 0u;
+                            for (int blk = 2; blk < nblk; blk++) {
+                                const int rel = kd - blk * 4 * kWave;
+                                const uint4 e = load_block(row + blk * 4 * kWave, rel, lane);
+                                RowBlock bb;
+                                block_products<STAGED, B16>(e, bits, tmask, lds_phi, phi_row, bb);
+                                const float tot = readlane_f32(bb.incl, 63);
+                                if (blk == nblk - 1 || carry + tot >= x) { topic = search_block(e, bb, carry, x, rel, tmask); break; }
+                                carry = carry + tot;
+                            }
                         }
+                    } else {
+                        const float x = u1s * sum_w;
+                        topic = (uint32_t)dense_query(STAGED ? lds_phi : phi_row, STAGED ? lds_l3 : l3_row,
+                                                      STAGED ? lds_l3_64 : l3_64_row, p.n3pad, K, x, lane);
+                        dense_count++;
                     }
-                } else {
-                    const float x = u1s * sum_w;
-                    topic = (uint32_t)tree_query(p.prefix + (size_t)tile.word * (size_t)p.Kpad,
-                                                 STAGED ? lds_l3 : l3_row, p.n3pad, K, x, lane);
-                    dense_count++;
+                    if (lane == r) my_z = topic;
                 }
-                if (lane == s) my_z = topic;
             } else {
-                if (lane == s) my_S = S;
+                if (lane >= s && lane < s_end) my_S = S;
             }
+            s = s_end;
         }
 
         if (act) {
@@ -349,6 +379,20 @@ __global__ void __launch_bounds__(1024) estep_kernel(EStepParams p) {
             p.out_ll[blockIdx.x] = sum;
         }
     }
+}
+
+// The bottom tree level (inclusive binary32 prefix sums of one Bhat row), rebuilt exactly as the sampler's
+// dense branch sees it; one wavefront per (word, 64-topic block).  Export / test aid.
+__global__ void prefix_export_kernel(const float *phi, const double *l3_64, const int32_t *words, int m, int K,
+                                     int Kpad, int n3, float *out) {
+    const int nblk = (K + kWave - 1) / kWave;
+    const int item = blockIdx.x, wi = item / nblk, blk = item % nblk, lane = lane_id();
+    if (wi >= m) return;
+    const size_t v = (size_t)words[wi];
+    const double base = blk > 0 ? l3_64[v * (size_t)n3 + (size_t)(blk - 1)] : 0.0;
+    const float c = (float)(base + wave_incl_scan((double)phi[v * (size_t)Kpad + (size_t)(blk * kWave + lane)]));
+    const int k = blk * kWave + lane;
+    if (k < K) out[(size_t)wi * (size_t)K + (size_t)k] = c;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -441,8 +485,12 @@ __global__ void __launch_bounds__(1024) count_dz_kernel(const int32_t *doc_list,
     __syncthreads();
     if (in_lds)
         for (int r = threadIdx.x; r < kd; r += blockDim.x) row[r] = ent_lds[r];
-    // zero fill up to the next multiple of 4 entries: the sampler reads rows in 16-byte pieces
-    if (threadIdx.x < 4) { const int r = kd + (int)threadIdx.x; if (r < ((kd + 3) & ~3)) row[r] = 0u; }
+    // pad to the next multiple of 4 entries with (last topic, count 0): the sampler reads rows in 16-byte pieces,
+    // and a draw that rounding pushes past the end of the row then still lands on the last topic
+    if (threadIdx.x < 4) {
+        const int r = kd + (int)threadIdx.x;
+        if (r < ((kd + 3) & ~3)) row[r] = ent[kd - 1] & ((1u << topic_bits) - 1u);
+    }
     if (threadIdx.x == 0) docrec[d].y = (uint32_t)kd;
 }
 
@@ -468,17 +516,18 @@ __global__ void topic_totals_kernel(const ZT *z, int64_t T, int64_t per_block, u
 
 // ---------------------------------------------------------------------------------------------
 // Preprocess + BuildTree (Alg. 1; Eq. 2; Sec. 3.2.4), one workgroup of 256 threads per word row.
-//   Bhat_vk = (float(B_vk) + beta) / (float(C_k) + float(V) * beta)      -- three single-rounded fp32 ops
-//   prefix  = round32( running sum of Bhat_v accumulated in fp64 )       -- bottom tree level
-//   l3[i]   = prefix[(i+1)*64 - 1]                                        -- next level, W = 64
-// Pad columns k in [K, Kpad) get Bhat = 0, so the padded prefix entries repeat the row total.
+//   Bhat_vk  = (float(B_vk) + beta) / (float(C_k) + float(V) * beta)     -- three single-rounded fp32 ops
+//   l3_64[i] = running sum of Bhat_v through topic (i+1)*64 - 1, accumulated in binary64
+//   l3[i]    = round32(l3_64[i])                                           -- tree level above the bottom, W = 64
+// Pad columns k in [K, Kpad) get Bhat = 0, so the last block's running sum is the row total.
+// The bottom level (one prefix sum per topic) is not stored; the sampler rebuilds the 64 entries it needs.
 // The row of B is cleared after it has been read, ready to accumulate the next E-step.
 // ---------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) phi_prefix_kernel(int32_t *cwk, const uint32_t *ck, float *phi, float *prefix,
-                                                         float *l3, float *sumphi, int K, int Kpad, int n3pad,
-                                                         float beta, float vbeta, int clear_cwk) {
+__global__ void __launch_bounds__(256) phi_tree_kernel(int32_t *cwk, const uint32_t *ck, float *phi, float *l3,
+                                                       double *l3_64, float *sumphi, int K, int Kpad, int n3,
+                                                       int n3pad, float beta, float vbeta, int clear_cwk) {
     __shared__ double wave_tot[4];
-    __shared__ float row_total;   // the stored prefix entry of the last real topic, K-1
+    __shared__ float row_total;
     const int v = blockIdx.x;
     const int lane = lane_id(), wave = threadIdx.x / kWave;
     const size_t rbase = (size_t)v * (size_t)Kpad;
@@ -501,38 +550,49 @@ __global__ void __launch_bounds__(256) phi_prefix_kernel(int32_t *cwk, const uin
             *reinterpret_cast<float4 *>(phi + rbase + k0) = make_float4(f[0], f[1], f[2], f[3]);
             if (clear_cwk) *reinterpret_cast<int4 *>(cwk + rbase + k0) = make_int4(0, 0, 0, 0);
         }
-        const double s0 = (double)f[0], s1 = s0 + (double)f[1], s2 = s1 + (double)f[2], s3 = s2 + (double)f[3];
+        const double s3 = (((double)f[0] + (double)f[1]) + (double)f[2]) + (double)f[3];
         const double incl = wave_incl_scan(s3);
         if (lane == kWave - 1) wave_tot[wave] = incl;
         __syncthreads();
         double woff = 0.0, btot = 0.0;
 #pragma unroll
         for (int w = 0; w < 4; w++) { const double tw = wave_tot[w]; if (w < wave) woff += tw; btot += tw; }
-        const double off = carry + woff + (incl - s3);
-        if (k0 < Kpad) {
-            *reinterpret_cast<float4 *>(prefix + rbase + k0) =
-                make_float4((float)(off + s0), (float)(off + s1), (float)(off + s2), (float)(off + s3));
-            if (((k0 + 3) & (kWave - 1)) == kWave - 1) l3[(size_t)v * (size_t)n3pad + (size_t)((k0 + 3) / kWave)] = (float)(off + s3);
-            const int q = K - 1 - k0;
-            if (q >= 0 && q < 4) row_total = (float)(off + (q == 0 ? s0 : q == 1 ? s1 : q == 2 ? s2 : s3));
+        if (k0 < Kpad && ((k0 + 3) & (kWave - 1)) == kWave - 1) {
+            const double run = carry + woff + incl;       // running sum through topic k0+3, the end of a block
+            const int i = (k0 + 3) / kWave;
+            l3_64[(size_t)v * (size_t)n3 + (size_t)i] = run;
+            l3[(size_t)v * (size_t)n3pad + (size_t)i] = (float)run;
+            if (i == n3 - 1) row_total = (float)run;
         }
         carry += btot;
         __syncthreads();
     }
     const float total = row_total;   // written before the loop's last barrier
-    for (int i = Kpad / kWave + (int)threadIdx.x; i < n3pad; i += blockDim.x) l3[(size_t)v * (size_t)n3pad + i] = total;
+    for (int i = n3 + (int)threadIdx.x; i < n3pad; i += blockDim.x) l3[(size_t)v * (size_t)n3pad + i] = total;
     if (threadIdx.x == 0) sumphi[v] = total;
 }
 
-// nnz(A) and sum_d K_d * L_d (statistics for the bandwidth model; exact in fp64 below 2^53)
-__global__ void row_stats_kernel(const uint2 *docrec, const int64_t *doc_ptr, int64_t D, unsigned long long *out2) {
-    double nnz = 0.0, reads = 0.0;
+// Statistics for the bandwidth model (exact in binary64 below 2^53): nnz(A), sum_d K_d * L_d (row entries
+// touched if every token read its row) and sum_d K_d * U_d, U_d = distinct words of document d inside its
+// chunk (row entries the sampler has to fetch: consecutive tokens of one (word, document) pair share the row).
+__global__ void row_stats_kernel(const uint2 *docrec, const int64_t *doc_ptr, const uint32_t *doc_words, int64_t D,
+                                 unsigned long long *out3) {
+    double nnz = 0.0, reads = 0.0, fetch = 0.0;
     for (int64_t d = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; d < D; d += (int64_t)gridDim.x * blockDim.x) {
         const double kd = (double)docrec[d].y;
-        nnz += kd; reads += kd * (double)(doc_ptr[d + 1] - doc_ptr[d]);
+        nnz += kd; reads += kd * (double)(doc_ptr[d + 1] - doc_ptr[d]); fetch += kd * (double)doc_words[d];
     }
     nnz = readlane_f64(wave_incl_scan(nnz), 63); reads = readlane_f64(wave_incl_scan(reads), 63);
-    if (lane_id() == 0) { atomicAdd(&out2[0], (unsigned long long)nnz); atomicAdd(&out2[1], (unsigned long long)reads); }
+    fetch = readlane_f64(wave_incl_scan(fetch), 63);
+    __shared__ double part[3][16];
+    const int wave = threadIdx.x / kWave, nwaves = blockDim.x / kWave;
+    if (lane_id() == 0) { part[0][wave] = nnz; part[1][wave] = reads; part[2][wave] = fetch; }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        double sum = 0.0;
+        for (int w = 0; w < nwaves; w++) sum += part[threadIdx.x][w];
+        atomicAdd(&out3[threadIdx.x], (unsigned long long)sum);
+    }
 }
 
 // Plain streaming copy (16 bytes per lane per step): the yardstick for achievable HBM bandwidth and the
