@@ -49,7 +49,7 @@ typedef struct saber_options {
     int32_t n_chunks;       /* document chunks the corpus is cut into (Sec. 3.1.2); default 1 */
     int32_t block_threads;  /* threads per workgroup of the sampling kernel (multiple of 64 up to 1024);
                                default: 512 when the staged Bhat row is 32 KB or more, else 256 */
-    int32_t tile_tokens;    /* most tokens of one word handled by one workgroup; default 4096 */
+    int32_t tile_tokens;    /* most tokens of one word handled by one workgroup; default 8192 */
     int32_t stage_phi;      /* 1: keep the word's Bhat row in LDS when it fits, 0: always gather from global; default 1 */
     int32_t profile;        /* 1: time every kernel group with HIP events (see saber_get_stats); default 0 */
     int32_t long_doc_tokens;/* documents longer than this use a 256-thread workgroup in CountByDZ; default 512 */

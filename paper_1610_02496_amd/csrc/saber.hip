@@ -100,7 +100,7 @@ static inline int grid_for(int64_t n, int block, int cap = 65535 * 16) {
 extern "C" void saber_options_default(saber_options *opt) {
     if (!opt) return;
     memset(opt, 0, sizeof(*opt));
-    opt->n_chunks = 1; opt->block_threads = 0; opt->tile_tokens = 4096; opt->stage_phi = 1; opt->profile = 0;
+    opt->n_chunks = 1; opt->block_threads = 0; opt->tile_tokens = 8192; opt->stage_phi = 1; opt->profile = 0;
     opt->long_doc_tokens = 512; opt->dz_lds_entries = 8192;
 }
 

@@ -44,6 +44,23 @@ __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) { SABER_SCAN_BODY
 __device__ __forceinline__ double wave_incl_scan(double v) { SABER_SCAN_BODY(double, dpp_f64) }
 #undef SABER_SCAN_BODY
 
+// binary32 scan used in the sampler's inner loop: the two row-broadcast steps as single fused DPP adds (rows
+// outside the row mask keep their value, which is exactly what the scan wants).  s_nop 1 covers the two wait
+// states a DPP read needs after the VALU write of its source.
+__device__ __forceinline__ float wave_incl_scan_fast(float v) {
+    v += dpp_f32<0x111, 0xf>(v);
+    v += dpp_f32<0x112, 0xf>(v);
+    v += dpp_f32<0x114, 0xf>(v);
+    v += dpp_f32<0x118, 0xf>(v);
+    asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf" : "+v"(v));
+    asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf" : "+v"(v));
+    return v;
+}
+
+// write a wave-uniform value into one lane of a register
+__device__ unsigned int llvm_amdgcn_writelane_u32(unsigned int value, unsigned int lane, unsigned int old)
+    __asm("llvm.amdgcn.writelane.i32");
+
 __device__ __forceinline__ float readlane_f32(float v, int lane) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }
@@ -195,31 +212,34 @@ __device__ __forceinline__ int dense_query(const float *phi_row, const float *l3
 // ---------------------------------------------------------------------------------------------
 struct RowBlock { float a0, a1, a2, a3, incl; };   // running sums inside the lane; inclusive scan of lane sums
 
-__device__ __forceinline__ uint4 load_block(const uint32_t *__restrict__ row, int rel_kd, int lane) {
-    // rows are 128-byte aligned and padded to a multiple of 4 entries with (last topic, count 0)
-    uint4 e = make_uint4(0u, 0u, 0u, 0u);
-    if (4 * lane < rel_kd) e = *reinterpret_cast<const uint4 *>(row + 4 * lane);
-    return e;
+// One 256-entry block of a row: lane l receives entries 4l..4l+3 through a buffer load whose descriptor ends
+// at the row's padded length, so lanes past the end read zeros without any branch.  Rows are 128-byte
+// aligned and padded to a multiple of 4 entries with (last topic, count 0).
+__device__ __forceinline__ uint4 load_block(const uint32_t *row, int rel_kd, int lane) {
+    const int bytes = rel_kd > 0 ? ((rel_kd + 3) & ~3) * 4 : 0;
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)row, (short)0, bytes, 0x00020000);
+    const auto v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane * 16, 0, 0);
+    return make_uint4(v[0], v[1], v[2], v[3]);
 }
 
 // Bhat value of the entry's topic
-template <bool STAGED, bool B16>
+template <bool STAGED>
 __device__ __forceinline__ float phi_of(uint32_t e, uint32_t tmask, const float *lds_phi, const float *__restrict__ phi_row) {
     return STAGED ? lds_phi[e & tmask] : phi_row[e & tmask];
 }
 
-template <bool STAGED, bool B16>
+template <bool STAGED>
 __device__ __forceinline__ void block_products(const uint4 e, uint32_t bits, uint32_t tmask,
                                                const float *lds_phi, const float *__restrict__ phi_row, RowBlock &b) {
-    const float f0 = phi_of<STAGED, B16>(e.x, tmask, lds_phi, phi_row);
-    const float f1 = phi_of<STAGED, B16>(e.y, tmask, lds_phi, phi_row);
-    const float f2 = phi_of<STAGED, B16>(e.z, tmask, lds_phi, phi_row);
-    const float f3 = phi_of<STAGED, B16>(e.w, tmask, lds_phi, phi_row);
+    const float f0 = phi_of<STAGED>(e.x, tmask, lds_phi, phi_row);
+    const float f1 = phi_of<STAGED>(e.y, tmask, lds_phi, phi_row);
+    const float f2 = phi_of<STAGED>(e.z, tmask, lds_phi, phi_row);
+    const float f3 = phi_of<STAGED>(e.w, tmask, lds_phi, phi_row);
     b.a0 = (float)(e.x >> bits) * f0;
     b.a1 = __builtin_fmaf((float)(e.y >> bits), f1, b.a0);
     b.a2 = __builtin_fmaf((float)(e.z >> bits), f2, b.a1);
     b.a3 = __builtin_fmaf((float)(e.w >> bits), f3, b.a2);
-    b.incl = wave_incl_scan(b.a3);
+    b.incl = wave_incl_scan_fast(b.a3);
 }
 
 // First entry of the block whose prefix sum (carry + sums inside the block) reaches x.  The lane is found
@@ -239,6 +259,7 @@ template <int MODE, bool STAGED, typename ZT, bool B16>
 __global__ void __launch_bounds__(1024) estep_kernel(EStepParams p) {
     extern __shared__ double lds_f64[];
     __shared__ double ll_wave[16];
+    __shared__ int next_batch;   // batches of a tile are handed out to wavefronts as they become free
     // LDS: [Kpad] floats (Bhat row), [n3pad] floats (tree level), [n3] doubles (block bases); Kpad and n3pad are
     // multiples of 64, so every part keeps 16-byte alignment
     float *lds_phi = reinterpret_cast<float *>(lds_f64);
@@ -249,6 +270,7 @@ __global__ void __launch_bounds__(1024) estep_kernel(EStepParams p) {
     const float *__restrict__ phi_row = p.phi + (size_t)tile.word * (size_t)p.Kpad;
     const float *__restrict__ l3_row = p.l3 + (size_t)tile.word * (size_t)p.n3pad;
     const double *__restrict__ l3_64_row = p.l3_64 + (size_t)tile.word * (size_t)p.n3;
+    if (threadIdx.x == 0) next_batch = 0;
     if (STAGED) {
         const float4 *src = reinterpret_cast<const float4 *>(phi_row);
         float4 *dst = reinterpret_cast<float4 *>(lds_phi);
@@ -257,12 +279,12 @@ __global__ void __launch_bounds__(1024) estep_kernel(EStepParams p) {
             for (int i = threadIdx.x; i < p.n3pad; i += blockDim.x) lds_l3[i] = l3_row[i];
             for (int i = threadIdx.x; i < p.n3; i += blockDim.x) lds_l3_64[i] = l3_64_row[i];
         }
-        __syncthreads();
     }
+    __syncthreads();
     const float sum_w = p.sumphi[tile.word];
     const float Q = p.alpha * sum_w;
     const int lane = lane_id(), nwaves = blockDim.x / kWave;
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));   // wave-uniform: keeps loop control scalar
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
     const uint32_t bits = B16 ? 16u : p.topic_bits, tmask = B16 ? 0xffffu : p.topic_mask;
     double ll_acc = 0.0;
     uint32_t dense_count = 0;
@@ -270,7 +292,11 @@ __global__ void __launch_bounds__(1024) estep_kernel(EStepParams p) {
     int bs = (tile.count + nwaves - 1) / nwaves;
     bs = bs > kWave ? kWave : bs;
 
-    for (int batch = wave * bs; batch < tile.count; batch += nwaves * bs) {
+    for (;;) {
+        int ticket = 0;
+        if (lane == 0) ticket = atomicAdd(&next_batch, 1);
+        const int batch = __builtin_amdgcn_readfirstlane(ticket) * bs;   // wave-uniform: loop control stays scalar
+        if (batch >= tile.count) break;
         const int n = min(bs, tile.count - batch);
         const bool act = lane < n;
         const int i = tile.begin + batch + lane;
@@ -284,47 +310,49 @@ __global__ void __launch_bounds__(1024) estep_kernel(EStepParams p) {
             u0 = unit24(r.r0); u1 = unit24(r.r1);
         }
         uint32_t my_z = 0; float my_S = 0.f;
-
-        uint4 nxt0 = load_block(p.cd_ent + (size_t)readlane_u32(rec.x, 0) * 32u, (int)readlane_u32(rec.y, 0), lane);
         int s = 0;
-        while (s < n) {
-            // the run [s, s_end) of tokens of this word in one document: they share A_d (.) Bhat_v and S
+
+        // One run [s, s_end) of tokens of this word in one document: they share A_d (.) Bhat_v and S.
+        // `cur` holds the first block of the run's row (fetched during the previous run); the first block of
+        // the next run's row is fetched into `nxt` before this run's arithmetic starts.
+        auto do_run = [&](const uint4 &cur, uint4 &nxt) {
             const int ds = __builtin_amdgcn_readlane(d, s);
             const unsigned long long other = __builtin_amdgcn_ballot_w64(d != ds) & (~0ull << s);
             int s_end = other ? (int)__builtin_ctzll(other) : kWave;
             s_end = __builtin_amdgcn_readfirstlane(s_end < n ? s_end : n);   // wave-uniform by construction
             const int kd = (int)readlane_u32(rec.y, s);
-            const uint32_t *__restrict__ row = p.cd_ent + (size_t)readlane_u32(rec.x, s) * 32u;
+            const uint32_t *row = p.cd_ent + (size_t)readlane_u32(rec.x, s) * 32u;
             const int nblk = (kd + 4 * kWave - 1) / (4 * kWave);
-            const uint4 e0 = nxt0;
             uint4 e1 = make_uint4(0u, 0u, 0u, 0u);
             if (nblk > 1) e1 = load_block(row + 4 * kWave, kd - 4 * kWave, lane);
             if (s_end < n)
-                nxt0 = load_block(p.cd_ent + (size_t)readlane_u32(rec.x, s_end) * 32u, (int)readlane_u32(rec.y, s_end), lane);
+                nxt = load_block(p.cd_ent + (size_t)readlane_u32(rec.x, s_end) * 32u, (int)readlane_u32(rec.y, s_end), lane);
             // element-wise product A_d (.) Bhat_v, its prefix sums and its sum S (Alg. 2, product loop)
-            RowBlock b0, b1;
-            block_products<STAGED, B16>(e0, bits, tmask, lds_phi, phi_row, b0);
+            RowBlock b0, b1 = {0.f, 0.f, 0.f, 0.f, 0.f};
+            block_products<STAGED>(cur, bits, tmask, lds_phi, phi_row, b0);
             const float t0 = readlane_f32(b0.incl, 63);
             float t1 = 0.f, S = t0;
             if (nblk > 1) {
-                block_products<STAGED, B16>(e1, bits, tmask, lds_phi, phi_row, b1);
+                block_products<STAGED>(e1, bits, tmask, lds_phi, phi_row, b1);
                 t1 = readlane_f32(b1.incl, 63);
                 S = S + t1;
                 for (int blk = 2; blk < nblk; blk++) {
                     RowBlock bb;
-                    block_products<STAGED, B16>(load_block(row + blk * 4 * kWave, kd - blk * 4 * kWave, lane), bits, tmask,
-                                                lds_phi, phi_row, bb);
+                    block_products<STAGED>(load_block(row + blk * 4 * kWave, kd - blk * 4 * kWave, lane), bits, tmask,
+                                           lds_phi, phi_row, bb);
                     S = S + readlane_f32(bb.incl, 63);
                 }
             }
             if (MODE == MODE_SAMPLE) {
+                // every lane evaluates the coin and the position for its own token; lanes of this run are used
+                const unsigned long long sparse = __builtin_amdgcn_ballot_w64(u0 * (S + Q) < S);
+                const float xs = u1 * S;
                 for (int r = s; r < s_end; r++) {
-                    const float u0s = readlane_f32(u0, r), u1s = readlane_f32(u1, r);
                     uint32_t topic;
-                    if (u0s * (S + Q) < S) {
+                    if ((sparse >> r) & 1ull) {
                         // problem 1: position of x in the prefix sums of P
-                        const float x = u1s * S;
-                        if (nblk == 1 || t0 >= x) topic = search_block(e0, b0, 0.f, x, kd, tmask);
+                        const float x = readlane_f32(xs, r);
+                        if (nblk == 1 || t0 >= x) topic = search_block(cur, b0, 0.f, x, kd, tmask);
                         else if (nblk == 2 || t0 + t1 >= x) topic = search_block(e1, b1, t0, x, kd - 4 * kWave, tmask);
                         else {
                             float carry = t0 + t1;
@@ -333,24 +361,32 @@ __global__ void __launch_bounds__(1024) estep_kernel(EStepParams p) {
                                 const int rel = kd - blk * 4 * kWave;
                                 const uint4 e = load_block(row + blk * 4 * kWave, rel, lane);
                                 RowBlock bb;
-                                block_products<STAGED, B16>(e, bits, tmask, lds_phi, phi_row, bb);
+                                block_products<STAGED>(e, bits, tmask, lds_phi, phi_row, bb);
                                 const float tot = readlane_f32(bb.incl, 63);
                                 if (blk == nblk - 1 || carry + tot >= x) { topic = search_block(e, bb, carry, x, rel, tmask); break; }
                                 carry = carry + tot;
                             }
                         }
                     } else {
-                        const float x = u1s * sum_w;
+                        const float x = readlane_f32(u1, r) * sum_w;
                         topic = (uint32_t)dense_query(STAGED ? lds_phi : phi_row, STAGED ? lds_l3 : l3_row,
                                                       STAGED ? lds_l3_64 : l3_64_row, p.n3pad, K, x, lane);
                         dense_count++;
                     }
-                    if (lane == r) my_z = topic;
+                    my_z = llvm_amdgcn_writelane_u32(topic, (unsigned)r, my_z);
                 }
             } else {
                 if (lane >= s && lane < s_end) my_S = S;
             }
             s = s_end;
+        };
+
+        uint4 blk_a = load_block(p.cd_ent + (size_t)readlane_u32(rec.x, 0) * 32u, (int)readlane_u32(rec.y, 0), lane);
+        uint4 blk_b = make_uint4(0u, 0u, 0u, 0u);
+        while (s < n) {
+            do_run(blk_a, blk_b);
+            if (s >= n) break;
+            do_run(blk_b, blk_a);
         }
 
         if (act) {
