@@ -47,6 +47,21 @@ def algorithmic_bytes(st, K, z_bytes, chunks_words_present):
     return tok + stage
 
 
+def profiled_traffic(workload, steps, warmup):
+    """HBM bytes per launch of the sampling kernel measured with rocprofv3 --pmc on this same command
+    (summary under profiles/); None for any other command."""
+    if (workload, steps, warmup) != ("C3", 48, 2):
+        return None
+    path = os.path.join(ROOT, "profiles", "estep_kernel_C3_hbm_traffic.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1])
+    except OSError:
+        pass
+    return None
+
+
 def run_gpu(corpus, K, steps, warmup, opts):
     import torch
     import paper_1610_02496_amd as pk
@@ -119,6 +134,8 @@ def main():
     ap.add_argument("--block-threads", type=int, default=0)
     ap.add_argument("--tile-tokens", type=int, default=0)
     ap.add_argument("--chunks", type=int, default=0)
+    ap.add_argument("--stage-min", type=int, default=0)
+    ap.add_argument("--light-block", type=int, default=0)
     ap.add_argument("--probe-bytes", type=int, default=1 << 30, help="size of the copy-bandwidth probe (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -141,6 +158,8 @@ def main():
     if args.block_threads: opts["block_threads"] = args.block_threads
     if args.tile_tokens: opts["tile_tokens"] = args.tile_tokens
     if args.chunks: opts["n_chunks"] = args.chunks
+    if args.stage_min: opts["stage_min_tokens"] = args.stage_min
+    if args.light_block: opts["light_block_threads"] = args.light_block
 
     copy_gbs = None
     if args.probe_bytes:
@@ -149,6 +168,8 @@ def main():
         log("[bench] plain copy kernel: %.0f GB/s (read+write)" % copy_gbs)
     main_res = run_gpu(corpus, spec.K, args.steps, args.warmup, opts)
     main_res["roofline"]["copy_kernel_gbs"] = copy_gbs
+    if not opts and not args.docs:
+        main_res["roofline"]["traffic"] = profiled_traffic(args.workload, args.steps, args.warmup)
     log("[bench] K=%d: %s" % (spec.K, json.dumps(main_res)))
     also = None
     if args.workload == "C3" and not args.no_also:

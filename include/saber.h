@@ -48,14 +48,17 @@ typedef enum saber_status {
 typedef struct saber_options {
     int32_t n_chunks;       /* document chunks the corpus is cut into (Sec. 3.1.2); default 1 */
     int32_t block_threads;  /* threads per workgroup of the sampling kernel (multiple of 64 up to 1024);
-                               default: 512 when the staged Bhat row is 32 KB or more, else 256 */
+                               default: the size that lets a CU hold the most wavefronts given the LDS the Bhat row takes */
     int32_t tile_tokens;    /* most tokens of one word handled by one workgroup; default 8192 */
     int32_t stage_phi;      /* 1: keep the word's Bhat row in LDS when it fits, 0: always gather from global; default 1 */
     int32_t profile;        /* 1: time every kernel group with HIP events (see saber_get_stats); default 0 */
     int32_t long_doc_tokens;/* documents longer than this use a 256-thread workgroup in CountByDZ; default 512 */
     int32_t dz_lds_entries; /* LDS capacity (entries) of one CountByDZ workgroup before it falls back to
                                accumulating in the global row; default 8192 */
-    int32_t reserved[9];
+    int32_t stage_min_tokens;   /* tiles with at least this many tokens are launched with block_threads threads, smaller
+                                   ones with light_block_threads; default 1 (one class) */
+    int32_t light_block_threads;/* workgroup size for the smaller tiles; default: as block_threads */
+    int32_t reserved[7];
 } saber_options;
 
 /* Sums over the iterations run since the last saber_reset_stats.  The ms_* fields need profile=1. */

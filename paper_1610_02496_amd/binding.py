@@ -32,7 +32,8 @@ class SaberError(RuntimeError):
 class Options(ctypes.Structure):
     _fields_ = [("n_chunks", ctypes.c_int32), ("block_threads", ctypes.c_int32), ("tile_tokens", ctypes.c_int32),
                 ("stage_phi", ctypes.c_int32), ("profile", ctypes.c_int32), ("long_doc_tokens", ctypes.c_int32),
-                ("dz_lds_entries", ctypes.c_int32), ("reserved", ctypes.c_int32 * 9)]
+                ("dz_lds_entries", ctypes.c_int32), ("stage_min_tokens", ctypes.c_int32),
+                ("light_block_threads", ctypes.c_int32), ("reserved", ctypes.c_int32 * 7)]
 
 
 class Stats(ctypes.Structure):

@@ -41,6 +41,7 @@ struct Chunk {
     int64_t d0 = 0, d1 = 0;   // document range
     int64_t t0 = 0, ntok = 0; // canonical token range [t0, t0+ntok)
     int64_t tile0 = 0, ntiles = 0, words_present = 0;
+    int64_t n_heavy = 0;              // tiles are sorted by size: [0,n_heavy) form the class of large tiles
 };
 
 constexpr int kMaxTimedIters = 32;
@@ -52,7 +53,7 @@ struct saber_ctx {
     float alpha = 0, beta = 0, vbeta = 0;
     uint64_t seed = 0;
     uint32_t iter = 0, topic_bits = 0, topic_mask = 0;
-    bool z16 = false, staged = false, b16 = false;
+    bool z16 = false, staged = false, b16 = false, lds_hist = false;
     saber_options opt{};
     double ll_const = 0.0;            // sum_d L_d ln(L_d + K alpha)
     int64_t max_doc_len = 0;
@@ -101,7 +102,7 @@ extern "C" void saber_options_default(saber_options *opt) {
     if (!opt) return;
     memset(opt, 0, sizeof(*opt));
     opt->n_chunks = 1; opt->block_threads = 0; opt->tile_tokens = 8192; opt->stage_phi = 1; opt->profile = 0;
-    opt->long_doc_tokens = 512; opt->dz_lds_entries = 8192;
+    opt->long_doc_tokens = 512; opt->dz_lds_entries = 8192; opt->stage_min_tokens = 0; opt->light_block_threads = 0;
 }
 
 extern "C" void saber_free(saber_ctx *c) {
@@ -132,29 +133,52 @@ static EStepParams make_params(saber_ctx *c, const Chunk &ch) {
     return p;
 }
 
-static size_t estep_lds_bytes(const saber_ctx *c) {
-    return (size_t)c->n3 * sizeof(double) + ((size_t)c->Kpad + (size_t)c->n3pad) * sizeof(float);
+// dynamic LDS of a staged sampling workgroup: the Bhat row (K rounded to 4 floats) and the tree level (n3 floats);
+// the optional per-tile histogram of new assignments adds Kpad counters
+static size_t estep_lds_bytes(const saber_ctx *c, bool lhist) {
+    const size_t row = (size_t)((c->K + 3) & ~3) + (size_t)((c->n3 + 3) & ~3);
+    return (row + (lhist ? (size_t)c->Kpad : 0)) * sizeof(float);
 }
 
 template <int MODE, bool STAGED, typename ZT>
-static void launch_estep_b16(saber_ctx *c, dim3 grid, dim3 block, size_t lds, const EStepParams &p) {
-    if (c->b16) hipLaunchKernelGGL((estep_kernel<MODE, STAGED, ZT, true>), grid, block, lds, c->stream, p);
-    else hipLaunchKernelGGL((estep_kernel<MODE, STAGED, ZT, false>), grid, block, lds, c->stream, p);
+static void launch_estep_b16(saber_ctx *c, dim3 grid, dim3 block, size_t lds, const EStepParams &p, bool lhist) {
+    if (lhist) {
+        if (c->b16) hipLaunchKernelGGL((estep_kernel<MODE_SAMPLE, true, uint16_t, true, true>), grid, block, lds, c->stream, p);
+        else hipLaunchKernelGGL((estep_kernel<MODE_SAMPLE, true, uint16_t, false, true>), grid, block, lds, c->stream, p);
+        return;
+    }
+    if (c->b16) hipLaunchKernelGGL((estep_kernel<MODE, STAGED, ZT, true, false>), grid, block, lds, c->stream, p);
+    else hipLaunchKernelGGL((estep_kernel<MODE, STAGED, ZT, false, false>), grid, block, lds, c->stream, p);
 }
 
+// One E-step launch per tile class: tiles with at least stage_min_tokens tokens run with block_threads threads,
+// smaller ones with light_block_threads, so that a word with few tokens does not hold a large workgroup whose
+// wavefronts have nothing to do.  Both classes stage the word's Bhat row in LDS when it fits.
 template <int MODE>
-static int launch_estep(saber_ctx *c, const Chunk &ch, EStepParams &p) {
-    if (ch.ntiles == 0) return SABER_OK;
-    const dim3 grid((unsigned)ch.ntiles), block((unsigned)c->opt.block_threads);
-    const size_t lds = c->staged ? estep_lds_bytes(c) : 0;
-    if (c->staged) {
-        if (c->z16) launch_estep_b16<MODE, true, uint16_t>(c, grid, block, lds, p);
-        else launch_estep_b16<MODE, true, int32_t>(c, grid, block, lds, p);
-    } else {
-        if (c->z16) launch_estep_b16<MODE, false, uint16_t>(c, grid, block, lds, p);
-        else launch_estep_b16<MODE, false, int32_t>(c, grid, block, lds, p);
+static int launch_estep(saber_ctx *c, const Chunk &ch, EStepParams &p0) {
+    struct Class { int64_t first, count; int block; };
+    const Class classes[2] = {
+        {0, ch.n_heavy, c->opt.block_threads},
+        {ch.n_heavy, ch.ntiles - ch.n_heavy, c->opt.light_block_threads},
+    };
+    for (const Class &cl : classes) {
+        if (cl.count == 0) continue;
+        EStepParams p = p0;
+        p.tiles = p0.tiles + cl.first;
+        if (p0.out_ll) p.out_ll = p0.out_ll + cl.first;
+        const dim3 grid((unsigned)cl.count), block((unsigned)cl.block);
+        // small K: accumulate the tile's new assignments in an LDS histogram instead of one global atomic per token
+        const bool lhist = MODE == MODE_SAMPLE && c->staged && c->z16 && c->lds_hist;
+        const size_t lds = c->staged ? estep_lds_bytes(c, lhist) : 0;
+        if (c->staged) {
+            if (c->z16) launch_estep_b16<MODE, true, uint16_t>(c, grid, block, lds, p, lhist);
+            else launch_estep_b16<MODE, true, int32_t>(c, grid, block, lds, p, false);
+        } else {
+            if (c->z16) launch_estep_b16<MODE, false, uint16_t>(c, grid, block, lds, p, false);
+            else launch_estep_b16<MODE, false, int32_t>(c, grid, block, lds, p, false);
+        }
+        HIP_TRY(hipGetLastError());
     }
-    HIP_TRY(hipGetLastError());
     return SABER_OK;
 }
 
@@ -311,6 +335,8 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
         std::stable_sort(h_tiles.begin() + (ptrdiff_t)first_tile, h_tiles.end(),
                          [](const Tile &a, const Tile &b) { return a.count > b.count; });
         ch.tile0 = (int64_t)first_tile; ch.ntiles = (int64_t)(h_tiles.size() - first_tile);
+        for (size_t i = first_tile; i < h_tiles.size(); i++)
+            if (h_tiles[i].count >= c->opt.stage_min_tokens) ch.n_heavy++;
         c->max_chunk_tiles = std::max(c->max_chunk_tiles, ch.ntiles);
     }
     c->total_tiles = (int64_t)h_tiles.size();
@@ -420,16 +446,17 @@ extern "C" int saber_init_ex(saber_ctx **out, const int64_t *doc_ptr, const int3
         if (opt_in->tile_tokens > 0) opt.tile_tokens = opt_in->tile_tokens;
         if (opt_in->long_doc_tokens > 0) opt.long_doc_tokens = opt_in->long_doc_tokens;
         if (opt_in->dz_lds_entries > 0) opt.dz_lds_entries = opt_in->dz_lds_entries;
+        if (opt_in->stage_min_tokens > 0) opt.stage_min_tokens = opt_in->stage_min_tokens;
+        if (opt_in->light_block_threads > 0) opt.light_block_threads = opt_in->light_block_threads;
         opt.stage_phi = opt_in->stage_phi; opt.profile = opt_in->profile;
         if (opt_in->stage_phi < 0) opt.stage_phi = 1;
     }
-    if (opt.block_threads <= 0) {
-        // automatic: rows of Bhat above 32 KB leave room for few workgroups per CU, so make them larger
-        const size_t row_bytes = ((size_t)((K + 63) / 64 * 64)) * sizeof(float);
-        opt.block_threads = (opt.stage_phi && row_bytes >= 32 * 1024 && row_bytes <= 60 * 1024) ? 512 : 256;
-    }
+    if (opt.block_threads <= 0) opt.block_threads = 256;   // replaced below, once the LDS footprint is known
     if (opt.block_threads % 64 || opt.block_threads < 64 || opt.block_threads > 1024)
         return fail(SABER_EINVAL, "saber_init: block_threads must be a multiple of 64 in [64,1024]");
+    if (opt.light_block_threads > 0 && (opt.light_block_threads % 64 || opt.light_block_threads > 1024))
+        return fail(SABER_EINVAL, "saber_init: light_block_threads must be a multiple of 64 in [64,1024]");
+    if (opt.stage_min_tokens <= 0) opt.stage_min_tokens = 1;
     if (opt.n_chunks > 65536) return fail(SABER_EINVAL, "saber_init: n_chunks too large");
     if (opt.dz_lds_entries > 12288) return fail(SABER_EINVAL, "saber_init: dz_lds_entries must not exceed 12288");
     if ((int64_t)opt.n_chunks > std::max<int64_t>(D, 1)) opt.n_chunks = (int32_t)std::max<int64_t>(D, 1);
@@ -447,7 +474,24 @@ extern "C" int saber_init_ex(saber_ctx **out, const int64_t *doc_ptr, const int3
     c->nwords = (K + 31) / 32;
     c->topic_bits = bits; c->topic_mask = (1u << bits) - 1u;
     c->z16 = K <= 65536;
-    c->staged = opt.stage_phi && estep_lds_bytes(c) <= 60 * 1024;
+    c->staged = opt.stage_phi && estep_lds_bytes(c, false) <= 60 * 1024;
+    c->lds_hist = c->staged && K <= 2048;
+    if (opt_in == nullptr || opt_in->block_threads <= 0) {
+        // automatic workgroup size: the one that lets a CU hold the most wavefronts given the LDS footprint
+        // (LDS is handed out in 512-byte pieces; a CU holds at most 32 wavefronts); ties go to the smaller size
+        int lds_cu = 0;
+        if (hipDeviceGetAttribute(&lds_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, 0) != hipSuccess || lds_cu <= 0)
+            lds_cu = 64 * 1024;
+        const size_t need = c->staged ? ((estep_lds_bytes(c, c->lds_hist) + 160 + 511) / 512) * 512 : 512;
+        int best = 256, best_waves = 0;
+        for (int block : {256, 512, 1024}) {
+            const int by_lds = (int)std::min<size_t>(64, (size_t)lds_cu / need), by_waves = 32 / (block / 64);
+            const int waves = std::min(by_lds, by_waves) * (block / 64);
+            if (waves > best_waves) { best_waves = waves; best = block; }
+        }
+        c->opt.block_threads = best;
+    }
+    if (c->opt.light_block_threads <= 0) c->opt.light_block_threads = c->opt.block_threads;
     c->vbeta = (float)V * beta;
     c->max_doc_len = maxlen;
     int rc;

@@ -176,20 +176,21 @@ enum { MODE_SAMPLE = 0, MODE_PROBS = 1, MODE_LOGLIK = 2 };
 // stored: the 64 prefix sums of the chosen block are rebuilt from the Bhat values themselves, as
 // round32(base + running sum in binary64), base being the unrounded running sum at the block's start.
 // That is the same number the table would hold, so the search is exact.
-__device__ __forceinline__ int dense_query(const float *phi_row, const float *l3, const double *l3_64, int n3pad,
-                                           int K, float x, int lane) {
+__device__ __forceinline__ int dense_query(const float *phi_row, const float *l3, const double *__restrict__ l3_64,
+                                           int n3, int K, float x, int lane) {
+    // l3 has n3 real entries; reads past the end are clamped to the last one, the row total (the padding value)
     int off3 = 0;
-    if (n3pad > kWave) {
-        const int n2 = n3pad / kWave;
-        const float v2 = (lane < n2) ? l3[(lane + 1) * kWave - 1] : __builtin_inff();
+    if (n3 > kWave) {
+        const int n2 = (n3 + kWave - 1) / kWave;
+        const int i = min((lane + 1) * kWave - 1, n3 - 1);
+        const float v2 = (lane < n2) ? l3[i] : __builtin_inff();
         const int i2 = wave_vote_first(v2 >= x);
         off3 = (i2 < 0 ? n2 - 1 : i2) * kWave;
     }
-    const float v3 = l3[off3 + lane];
+    const float v3 = l3[min(off3 + lane, n3 - 1)];
     const int i3 = wave_vote_first(v3 >= x);
     int blk = off3 + (i3 < 0 ? kWave - 1 : i3);
-    const int nblk = (K + kWave - 1) / kWave;
-    if (blk > nblk - 1) blk = nblk - 1;                 // cannot happen for finite tables; keeps reads in bounds
+    if (blk > n3 - 1) blk = n3 - 1;                     // cannot happen for finite tables; keeps reads in bounds
     const double base = blk > 0 ? l3_64[blk - 1] : 0.0;
     const float v4 = (float)(base + wave_incl_scan((double)phi_row[blk * kWave + lane]));
     const int i4 = wave_vote_first(v4 >= x);
@@ -255,16 +256,19 @@ __device__ __forceinline__ uint32_t search_block(const uint4 e, const RowBlock &
     return readlane_u32(sel, L) & tmask;
 }
 
-template <int MODE, bool STAGED, typename ZT, bool B16>
-__global__ void __launch_bounds__(1024) estep_kernel(EStepParams p) {
-    extern __shared__ double lds_f64[];
-    __shared__ double ll_wave[16];
+template <int MODE, bool STAGED, typename ZT, bool B16, bool LHIST>
+__global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
+    extern __shared__ float4 lds_f4[];
+    __shared__ double ll_wave[MODE == MODE_LOGLIK ? 16 : 1];
     __shared__ int next_batch;   // batches of a tile are handed out to wavefronts as they become free
-    // LDS: [Kpad] floats (Bhat row), [n3pad] floats (tree level), [n3] doubles (block bases); Kpad and n3pad are
-    // multiples of 64, so every part keeps 16-byte alignment
-    float *lds_phi = reinterpret_cast<float *>(lds_f64);
-    float *lds_l3 = lds_phi + p.Kpad;
-    double *lds_l3_64 = reinterpret_cast<double *>(lds_l3 + p.n3pad);
+    // LDS (STAGED): [K rounded to 4] floats: the word's Bhat row; [n3] floats: the tree level above the bottom;
+    // LHIST adds [Kpad] counters: the tile's histogram of new assignments (small K only).
+    // The footprint is kept minimal because it decides how many wavefronts a CU can hold: at K = 10,000 it is
+    // 40,628 bytes, which lets four 512-thread workgroups (32 wavefronts) share the 160 KB of a CU.
+    const int K4 = (p.K + 3) & ~3;
+    float *lds_phi = reinterpret_cast<float *>(lds_f4);
+    float *lds_l3 = lds_phi + K4;
+    uint32_t *lds_hist = reinterpret_cast<uint32_t *>(lds_l3 + ((p.n3 + 3) & ~3));
     const Tile tile = p.tiles[blockIdx.x];
     const int K = p.K;
     const float *__restrict__ phi_row = p.phi + (size_t)tile.word * (size_t)p.Kpad;
@@ -274,12 +278,12 @@ __global__ void __launch_bounds__(1024) estep_kernel(EStepParams p) {
     if (STAGED) {
         const float4 *src = reinterpret_cast<const float4 *>(phi_row);
         float4 *dst = reinterpret_cast<float4 *>(lds_phi);
-        for (int i = threadIdx.x; i < p.Kpad / 4; i += blockDim.x) dst[i] = src[i];
-        if (MODE == MODE_SAMPLE) {
-            for (int i = threadIdx.x; i < p.n3pad; i += blockDim.x) lds_l3[i] = l3_row[i];
-            for (int i = threadIdx.x; i < p.n3; i += blockDim.x) lds_l3_64[i] = l3_64_row[i];
-        }
+        for (int i = threadIdx.x; i < K4 / 4; i += blockDim.x) dst[i] = src[i];
+        if (MODE == MODE_SAMPLE)
+            for (int i = threadIdx.x; i < p.n3; i += blockDim.x) lds_l3[i] = l3_row[i];
     }
+    if (LHIST)
+        for (int i = threadIdx.x; i < p.Kpad; i += blockDim.x) lds_hist[i] = 0u;
     __syncthreads();
     const float sum_w = p.sumphi[tile.word];
     const float Q = p.alpha * sum_w;
@@ -369,8 +373,8 @@ __global__ void __launch_bounds__(1024) estep_kernel(EStepParams p) {
                         }
                     } else {
                         const float x = readlane_f32(u1, r) * sum_w;
-                        topic = (uint32_t)dense_query(STAGED ? lds_phi : phi_row, STAGED ? lds_l3 : l3_row,
-                                                      STAGED ? lds_l3_64 : l3_64_row, p.n3pad, K, x, lane);
+                        topic = (uint32_t)dense_query(STAGED ? lds_phi : phi_row, STAGED ? lds_l3 : l3_row, l3_64_row,
+                                                      p.n3, K, x, lane);
                         dense_count++;
                     }
                     my_z = llvm_amdgcn_writelane_u32(topic, (unsigned)r, my_z);
@@ -393,7 +397,8 @@ __global__ void __launch_bounds__(1024) estep_kernel(EStepParams p) {
             const int64_t tc = p.t_base + (int64_t)t;
             if (MODE == MODE_SAMPLE) {
                 reinterpret_cast<ZT *>(p.z)[tc] = (ZT)my_z;
-                atomicAdd(&p.cwk[(size_t)tile.word * (size_t)p.Kpad + my_z], 1);
+                if (LHIST) atomicAdd(&lds_hist[my_z], 1u);
+                else atomicAdd(&p.cwk[(size_t)tile.word * (size_t)p.Kpad + my_z], 1);
             } else if (MODE == MODE_PROBS) {
                 p.out_S[tc] = my_S; p.out_Q[tc] = Q;
             } else {
@@ -404,6 +409,14 @@ __global__ void __launch_bounds__(1024) estep_kernel(EStepParams p) {
 
     if (MODE == MODE_SAMPLE) {
         if (lane == 0 && dense_count) atomicAdd(p.n_dense, (unsigned long long)dense_count);
+        if (LHIST) {
+            // the tile's counts go to B in one pass: at most K atomics per tile instead of one per token
+            __syncthreads();
+            for (int k = threadIdx.x; k < K; k += blockDim.x) {
+                const uint32_t h = lds_hist[k];
+                if (h) atomicAdd(&p.cwk[(size_t)tile.word * (size_t)p.Kpad + k], (int)h);
+            }
+        }
     }
     if (MODE == MODE_LOGLIK) {
         double tot = readlane_f64(wave_incl_scan(ll_acc), 63);

@@ -200,7 +200,8 @@ def test_results_do_not_depend_on_layout_options():
     pk = saber()
     ref = None
     for opts in [{}, {"n_chunks": 4}, {"tile_tokens": 64, "block_threads": 128}, {"stage_phi": 0},
-                 {"long_doc_tokens": 16, "dz_lds_entries": 8}]:
+                 {"long_doc_tokens": 16, "dz_lds_entries": 8}, {"stage_min_tokens": 65, "light_block_threads": 128},
+                 {"stage_min_tokens": 100000}]:
         g = pk.Saber(c.doc_ptr, c.word_ids, c.spec.V, 300, 0.2, 0.01, 77, **opts)
         g.iterate(3)
         z = g.get_z()
