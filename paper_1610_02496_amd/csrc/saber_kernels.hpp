@@ -170,32 +170,57 @@ struct EStepParams {
 
 enum { MODE_SAMPLE = 0, MODE_PROBS = 1, MODE_LOGLIK = 2 };
 
-// Dense branch (problem 2, Sec. 2.3): position of x in the prefix sums of the word's Bhat row, by a W-ary
-// descent with W = 64 (Sec. 3.2.4).  Levels above the bottom hold the binary32 prefix sum at the end of
-// every 64-topic block (level 2 is every 64th entry of level 3, read in place).  The bottom level is not
-// stored: the 64 prefix sums of the chosen block are rebuilt from the Bhat values themselves, as
-// round32(base + running sum in binary64), base being the unrounded running sum at the block's start.
-// That is the same number the table would hold, so the search is exact.
-__device__ __forceinline__ int dense_query(const float *phi_row, const float *l3, const double *__restrict__ l3_64,
-                                           int n3, int K, float x, int lane) {
-    // l3 has n3 real entries; reads past the end are clamped to the last one, the row total (the padding value)
-    int off3 = 0;
-    if (n3 > kWave) {
+// Sums and scans inside one DPP row (16 lanes): the dense branch serves four tokens at a time, one per row.
+__device__ __forceinline__ uint32_t row16_allsum(uint32_t v) {
+    v += dpp_u32<0x128, 0xf>(v);   // row_ror:8
+    v += dpp_u32<0x124, 0xf>(v);   // row_ror:4
+    v += dpp_u32<0x122, 0xf>(v);   // row_ror:2
+    v += dpp_u32<0x121, 0xf>(v);   // row_ror:1
+    return v;
+}
+__device__ __forceinline__ double row16_incl_scan(double v) {
+    v += dpp_f64<0x111, 0xf>(v);
+    v += dpp_f64<0x112, 0xf>(v);
+    v += dpp_f64<0x114, 0xf>(v);
+    v += dpp_f64<0x118, 0xf>(v);
+    return v;
+}
+
+// Dense branch (problem 2, Sec. 2.3): position of x in the prefix sums of the word's Bhat row, four tokens per
+// call: the 16 lanes of DPP row g serve the token whose x they hold (all lanes of a row hold the same x).
+// The descent follows Sec. 3.2.4 with the stored level l3 (binary32 prefix sum at the end of every 64-topic
+// block; every 64th entry of it acts as the level above when K is large).  Prefix sums are non-decreasing, so
+// "first entry >= x" is the number of entries below x: every lane counts its share and one row-wide sum gives
+// the position.  The bottom level is not stored: the 64 prefix sums of the chosen block are rebuilt from the
+// Bhat values as round32(base + running sum in binary64), base = unrounded running sum at the block's start -
+// the numbers a stored table would hold, so the search is exact.  Returns the topic in every lane of the row.
+__device__ __forceinline__ uint32_t dense_query4(const float *phi_row, int phi_len, const float *l3,
+                                                 const double *__restrict__ l3_64, int n3, int K, float x, int li) {
+    uint32_t cnt = 0;
+    int blk;
+    if (n3 <= 256) {
+        for (int i = li; i < n3; i += 16) cnt += (l3[i] < x) ? 1u : 0u;
+        blk = (int)row16_allsum(cnt);
+    } else {
         const int n2 = (n3 + kWave - 1) / kWave;
-        const int i = min((lane + 1) * kWave - 1, n3 - 1);
-        const float v2 = (lane < n2) ? l3[i] : __builtin_inff();
-        const int i2 = wave_vote_first(v2 >= x);
-        off3 = (i2 < 0 ? n2 - 1 : i2) * kWave;
+        for (int j = li; j < n2; j += 16) cnt += (l3[min((j + 1) * kWave - 1, n3 - 1)] < x) ? 1u : 0u;
+        const int j2 = min((int)row16_allsum(cnt), n2 - 1);
+        cnt = 0;
+#pragma unroll
+        for (int q = 0; q < 4; q++) { const int i = j2 * kWave + li * 4 + q; cnt += (i < n3 && l3[i] < x) ? 1u : 0u; }
+        blk = j2 * kWave + (int)row16_allsum(cnt);
     }
-    const float v3 = l3[min(off3 + lane, n3 - 1)];
-    const int i3 = wave_vote_first(v3 >= x);
-    int blk = off3 + (i3 < 0 ? kWave - 1 : i3);
-    if (blk > n3 - 1) blk = n3 - 1;                     // cannot happen for finite tables; keeps reads in bounds
+    blk = min(blk, n3 - 1);                                 // rounding left no block: the last one
     const double base = blk > 0 ? l3_64[blk - 1] : 0.0;
-    const float v4 = (float)(base + wave_incl_scan((double)phi_row[blk * kWave + lane]));
-    const int i4 = wave_vote_first(v4 >= x);
-    const int k = blk * kWave + (i4 < 0 ? kWave - 1 : i4);
-    return k < K ? k : K - 1;
+    const int k0 = blk * kWave + li * 4;
+    float4 f = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (k0 < phi_len) f = *reinterpret_cast<const float4 *>(phi_row + k0);   // columns K..phi_len-1 hold zeros
+    const double s0 = (double)f.x, s1 = s0 + (double)f.y, s2 = s1 + (double)f.z, s3 = s2 + (double)f.w;
+    const double b2 = base + (row16_incl_scan(s3) - s3);
+    const uint32_t below = ((float)(b2 + s0) < x ? 1u : 0u) + ((float)(b2 + s1) < x ? 1u : 0u) +
+                           ((float)(b2 + s2) < x ? 1u : 0u) + ((float)(b2 + s3) < x ? 1u : 0u);
+    const int k = blk * kWave + min((int)row16_allsum(below), kWave - 1);
+    return (uint32_t)min(k, K - 1);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -314,6 +339,7 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
             u0 = unit24(r.r0); u1 = unit24(r.r1);
         }
         uint32_t my_z = 0; float my_S = 0.f;
+        unsigned long long dense_mask = 0ull;
         int s = 0;
 
         // One run [s, s_end) of tokens of this word in one document: they share A_d (.) Bhat_v and S.
@@ -351,6 +377,8 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
                 // every lane evaluates the coin and the position for its own token; lanes of this run are used
                 const unsigned long long sparse = __builtin_amdgcn_ballot_w64(u0 * (S + Q) < S);
                 const float xs = u1 * S;
+                const unsigned long long in_run = (~0ull << s) & (s_end < kWave ? ~(~0ull << s_end) : ~0ull);
+                dense_mask |= ~sparse & in_run;           // problem 2 is served after the runs, four tokens at a time
                 for (int r = s; r < s_end; r++) {
                     uint32_t topic;
                     if ((sparse >> r) & 1ull) {
@@ -371,13 +399,8 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
                                 carry = carry + tot;
                             }
                         }
-                    } else {
-                        const float x = readlane_f32(u1, r) * sum_w;
-                        topic = (uint32_t)dense_query(STAGED ? lds_phi : phi_row, STAGED ? lds_l3 : l3_row, l3_64_row,
-                                                      p.n3, K, x, lane);
-                        dense_count++;
+                        my_z = llvm_amdgcn_writelane_u32(topic, (unsigned)r, my_z);
                     }
-                    my_z = llvm_amdgcn_writelane_u32(topic, (unsigned)r, my_z);
                 }
             } else {
                 if (lane >= s && lane < s_end) my_S = S;
@@ -391,6 +414,28 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
             do_run(blk_a, blk_b);
             if (s >= n) break;
             do_run(blk_b, blk_a);
+        }
+
+        if (MODE == MODE_SAMPLE && dense_mask) {
+            // problem 2 for the tokens whose coin chose it: DPP row g (16 lanes) serves the g-th of up to four tokens
+            dense_count += (uint32_t)__builtin_popcountll(dense_mask);
+            const float xd = u1 * sum_w;
+            const int g = lane >> 4, li = lane & 15;
+            while (dense_mask) {
+                int tl[4];
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    tl[q] = dense_mask ? (int)__builtin_ctzll(dense_mask) : -1;
+                    dense_mask &= dense_mask - 1ull;
+                }
+                const int mine = g == 0 ? tl[0] : g == 1 ? tl[1] : g == 2 ? tl[2] : tl[3];
+                const float x = __int_as_float(__builtin_amdgcn_ds_bpermute((mine < 0 ? lane : mine) << 2, __float_as_int(xd)));
+                const uint32_t k = dense_query4(STAGED ? lds_phi : phi_row, STAGED ? K4 : p.Kpad, STAGED ? lds_l3 : l3_row,
+                                                l3_64_row, p.n3, K, x, li);
+#pragma unroll
+                for (int q = 0; q < 4; q++)
+                    if (tl[q] >= 0) my_z = llvm_amdgcn_writelane_u32(readlane_u32(k, 16 * q), (unsigned)tl[q], my_z);
+            }
         }
 
         if (act) {
