@@ -21,8 +21,10 @@
  *     word 0 decides the branch, word 1 the position; u = (word >> 8) * 2^-24.
  *     Results therefore do not depend on the internal token order, tile sizes or
  *     chunk count.
- *   - Limits: 1 <= K <= 262144 (three searched tree levels of width 64),
- *     T < 2^31, and the longest document must be shorter than 2^(32 - ceil(log2 K)).
+ *   - Limits: 1 <= K <= 262144 (three searched tree levels of width 64), D < 2^31, T < 2^40 (the corpus is cut
+ *     into document chunks of fewer than 2^30 tokens when it is larger), and the longest document must be
+ *     shorter than 2^(32 - ceil(log2 K)).  Everything stays resident in device memory: about 10 bytes per
+ *     token plus 8*V*K bytes.
  */
 #ifndef SABER_H
 #define SABER_H

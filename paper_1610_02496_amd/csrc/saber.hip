@@ -70,7 +70,8 @@ struct saber_ctx {
     int32_t *short_docs = nullptr, *long_docs = nullptr;
     int64_t n_short = 0, n_long = 0;
     int32_t *cwk = nullptr;           // [V][Kpad]
-    uint32_t *ck = nullptr;           // [K]
+    unsigned long long *ck = nullptr; // [K] topic totals
+    float *denom = nullptr;           // [K] denominators of Eq. 2
     float *phi = nullptr, *l3 = nullptr, *sumphi = nullptr;
     double *l3_64 = nullptr;          // [V][n3]
     uint32_t *doc_words = nullptr;    // [D] distinct words of the document
@@ -110,7 +111,7 @@ extern "C" void saber_free(saber_ctx *c) {
     if (c->stream) (void)hipStreamSynchronize(c->stream);
     dev_free(c->z); dev_free(c->tok_doc); dev_free(c->tok_t); dev_free(c->tiles); dev_free(c->docrec);
     dev_free(c->cd_ent); dev_free(c->doc_ptr); dev_free(c->short_docs); dev_free(c->long_docs); dev_free(c->cwk);
-    dev_free(c->ck); dev_free(c->phi); dev_free(c->l3_64); dev_free(c->l3); dev_free(c->sumphi); dev_free(c->doc_words);
+    dev_free(c->ck); dev_free(c->denom); dev_free(c->phi); dev_free(c->l3_64); dev_free(c->l3); dev_free(c->sumphi); dev_free(c->doc_words);
     dev_free(c->counters); dev_free(c->ll_partial);
     if (c->have_events) for (auto &e : c->ev) if (e) (void)hipEventDestroy(e);
     if (c->stream) (void)hipStreamDestroy(c->stream);
@@ -222,7 +223,7 @@ static int launch_row_stats(saber_ctx *c, unsigned long long *out2) {
 }
 
 static int launch_topic_totals(saber_ctx *c) {
-    hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for(c->K, 256)), dim3(256), 0, c->stream, c->ck, 0u, (size_t)c->K);
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for(2 * (int64_t)c->K, 256)), dim3(256), 0, c->stream, (uint32_t *)c->ck, 0u, (size_t)c->K * 2);
     HIP_TRY(hipGetLastError());
     if (c->T == 0) return SABER_OK;
     const int use_lds = (size_t)c->K * 4 <= 60 * 1024;
@@ -240,8 +241,10 @@ static int launch_topic_totals(saber_ctx *c) {
 }
 
 static int launch_phi(saber_ctx *c) {
-    hipLaunchKernelGGL(phi_tree_kernel, dim3((unsigned)c->V), dim3(256), 0, c->stream, c->cwk, c->ck, c->phi,
-                       c->l3, c->l3_64, c->sumphi, c->K, c->Kpad, c->n3, c->n3pad, c->beta, c->vbeta, 1);
+    hipLaunchKernelGGL(denominators_kernel, dim3(grid_for(c->K, 256)), dim3(256), 0, c->stream, c->ck, c->denom, c->K, c->vbeta);
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(phi_tree_kernel, dim3((unsigned)c->V), dim3(256), 0, c->stream, c->cwk, c->denom, c->phi,
+                       c->l3, c->l3_64, c->sumphi, c->K, c->Kpad, c->n3, c->n3pad, c->beta, 1);
     HIP_TRY(hipGetLastError());
     return SABER_OK;
 }
@@ -306,6 +309,7 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
                 while (d < D && doc_ptr[d + 1] <= target) d++;
             }
             ch.d1 = d; ch.ntok = doc_ptr[d] - ch.t0;
+            if (ch.ntok >= (1ll << 31)) return fail(SABER_ERANGE, "saber_init: a document chunk holds %lld tokens (limit 2^31)", (long long)ch.ntok);
             if (ch.d1 > ch.d0) c->chunks.push_back(ch);
         }
     }
@@ -374,7 +378,7 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     SABER_TRY(dev_alloc(&c->tiles, h_tiles.size())); SABER_TRY(dev_alloc(&c->docrec, (size_t)D));
     SABER_TRY(dev_alloc(&c->cd_ent, (size_t)c->cd_cap)); SABER_TRY(dev_alloc(&c->doc_ptr, (size_t)D + 1));
     SABER_TRY(dev_alloc(&c->short_docs, h_short.size())); SABER_TRY(dev_alloc(&c->long_docs, h_long.size()));
-    SABER_TRY(dev_alloc(&c->cwk, vk)); SABER_TRY(dev_alloc(&c->ck, (size_t)K));
+    SABER_TRY(dev_alloc(&c->cwk, vk)); SABER_TRY(dev_alloc(&c->ck, (size_t)K)); SABER_TRY(dev_alloc(&c->denom, (size_t)K));
     SABER_TRY(dev_alloc(&c->phi, vk)); SABER_TRY(dev_alloc(&c->l3_64, (size_t)V * (size_t)c->n3));
     SABER_TRY(dev_alloc(&c->doc_words, (size_t)D));
     SABER_TRY(dev_alloc(&c->l3, (size_t)V * (size_t)c->n3pad)); SABER_TRY(dev_alloc(&c->sumphi, (size_t)V));
@@ -427,7 +431,7 @@ extern "C" int saber_init_ex(saber_ctx **out, const int64_t *doc_ptr, const int3
         maxlen = std::max(maxlen, doc_ptr[d + 1] - doc_ptr[d]);
     }
     const int64_t T = doc_ptr[D];
-    if (T >= (1ll << 31)) return fail(SABER_ERANGE, "saber_init: T = %lld tokens; this build handles T < 2^31", (long long)T);
+    if (T >= (1ll << 40)) return fail(SABER_ERANGE, "saber_init: T = %lld tokens exceeds 2^40", (long long)T);
     if (T > 0 && !word_ids) return fail(SABER_EINVAL, "saber_init: word_ids is null");
     for (int64_t t = 0; t < T; t++)
         if (word_ids[t] < 0 || word_ids[t] >= V)
@@ -459,6 +463,8 @@ extern "C" int saber_init_ex(saber_ctx **out, const int64_t *doc_ptr, const int3
     if (opt.stage_min_tokens <= 0) opt.stage_min_tokens = 1;
     if (opt.n_chunks > 65536) return fail(SABER_EINVAL, "saber_init: n_chunks too large");
     if (opt.dz_lds_entries > 12288) return fail(SABER_EINVAL, "saber_init: dz_lds_entries must not exceed 12288");
+    // token positions inside a chunk are 32-bit: keep every chunk below 2^30 tokens (documents are far shorter)
+    opt.n_chunks = (int32_t)std::max<int64_t>(opt.n_chunks, (T >> 30) + 1);
     if ((int64_t)opt.n_chunks > std::max<int64_t>(D, 1)) opt.n_chunks = (int32_t)std::max<int64_t>(D, 1);
 
     int ndev = 0;
@@ -625,8 +631,8 @@ extern "C" int saber_counts(saber_ctx *c, int64_t *cd_row_ptr, int32_t *cd_topic
             HIP_TRY(hipStreamSynchronize(c->stream));
         }
         if (ck) {
-            std::vector<uint32_t> h((size_t)c->K);
-            HIP_TRY(hipMemcpy(h.data(), c->ck, sizeof(uint32_t) * (size_t)c->K, hipMemcpyDeviceToHost));
+            std::vector<unsigned long long> h((size_t)c->K);
+            HIP_TRY(hipMemcpy(h.data(), c->ck, sizeof(unsigned long long) * (size_t)c->K, hipMemcpyDeviceToHost));
             for (int32_t k = 0; k < c->K; k++) ck[k] = (int64_t)h[(size_t)k];
         }
     } catch (const std::bad_alloc &) { return fail(SABER_ENOMEM, "saber_counts: out of host memory"); }

@@ -593,7 +593,7 @@ __global__ void __launch_bounds__(1024) count_dz_kernel(const int32_t *doc_list,
 // column sums of B at K = 10^4).  LDS histogram when K fits, else global atomics.
 // ---------------------------------------------------------------------------------------------
 template <typename ZT>
-__global__ void topic_totals_kernel(const ZT *z, int64_t T, int64_t per_block, uint32_t *ck, int K, int use_lds) {
+__global__ void topic_totals_kernel(const ZT *z, int64_t T, int64_t per_block, unsigned long long *ck, int K, int use_lds) {
     extern __shared__ uint32_t hist[];
     const int64_t b = (int64_t)blockIdx.x * per_block;
     int64_t e = b + per_block; if (e > T) e = T;
@@ -602,24 +602,30 @@ __global__ void topic_totals_kernel(const ZT *z, int64_t T, int64_t per_block, u
         __syncthreads();
         for (int64_t t = b + threadIdx.x; t < e; t += blockDim.x) atomicAdd(&hist[(uint32_t)z[t]], 1u);
         __syncthreads();
-        for (int k = threadIdx.x; k < K; k += blockDim.x) { const uint32_t h = hist[k]; if (h) atomicAdd(&ck[k], h); }
+        for (int k = threadIdx.x; k < K; k += blockDim.x) { const uint32_t h = hist[k]; if (h) atomicAdd(&ck[k], (unsigned long long)h); }
     } else {
-        for (int64_t t = b + threadIdx.x; t < e; t += blockDim.x) atomicAdd(&ck[(uint32_t)z[t]], 1u);
+        for (int64_t t = b + threadIdx.x; t < e; t += blockDim.x) atomicAdd(&ck[(uint32_t)z[t]], 1ull);
     }
 }
 
 // ---------------------------------------------------------------------------------------------
 // Preprocess + BuildTree (Alg. 1; Eq. 2; Sec. 3.2.4), one workgroup of 256 threads per word row.
-//   Bhat_vk  = (float(B_vk) + beta) / (float(C_k) + float(V) * beta)     -- three single-rounded fp32 ops
+//   Bhat_vk  = (float(B_vk) + beta) / denom_k,  denom_k = float(C_k) + float(V) * beta   -- single-rounded fp32 ops
 //   l3_64[i] = running sum of Bhat_v through topic (i+1)*64 - 1, accumulated in binary64
 //   l3[i]    = round32(l3_64[i])                                           -- tree level above the bottom, W = 64
 // Pad columns k in [K, Kpad) get Bhat = 0, so the last block's running sum is the row total.
 // The bottom level (one prefix sum per topic) is not stored; the sampler rebuilds the 64 entries it needs.
 // The row of B is cleared after it has been read, ready to accumulate the next E-step.
 // ---------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) phi_tree_kernel(int32_t *cwk, const uint32_t *ck, float *phi, float *l3,
+// Denominators of Eq. 2, one per topic: float(C_k) + float(V) * beta (the conversion rounds to nearest even).
+__global__ void denominators_kernel(const unsigned long long *ck, float *denom, int K, float vbeta) {
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < K) denom[k] = (float)ck[k] + vbeta;
+}
+
+__global__ void __launch_bounds__(256) phi_tree_kernel(int32_t *cwk, const float *denom, float *phi, float *l3,
                                                        double *l3_64, float *sumphi, int K, int Kpad, int n3,
-                                                       int n3pad, float beta, float vbeta, int clear_cwk) {
+                                                       int n3pad, float beta, int clear_cwk) {
     __shared__ double wave_tot[4];
     __shared__ float row_total;
     const int v = blockIdx.x;
@@ -637,8 +643,7 @@ __global__ void __launch_bounds__(256) phi_tree_kernel(int32_t *cwk, const uint3
                 const int k = k0 + q;
                 if (k < K) {
                     const float num = (float)cc[q] + beta;
-                    const float den = (float)ck[k] + vbeta;
-                    f[q] = num / den;
+                    f[q] = num / denom[k];
                 }
             }
             *reinterpret_cast<float4 *>(phi + rbase + k0) = make_float4(f[0], f[1], f[2], f[3]);

@@ -22,19 +22,28 @@ def say(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-@pytest.fixture(scope="module")
-def corpus():
-    t = time.time()
-    c = corpusgen.generate(corpusgen.SPECS["C3"], with_topics=False)
-    say("[fullsize] corpus T=%d generated in %.1fs" % (c.T, time.time() - t))
-    assert c.T == 100_000_000 and c.spec.D == 300_000 and c.spec.V == 100_000
-    return c
+_CORPORA = {}
 
 
-@pytest.mark.parametrize("K", [1000, 10000])
-def test_full_size_parity(corpus, K):
+def corpus_for(name):
+    """C3: the benchmark corpus (100M tokens).  C4p: the first million documents of the PubMed-shaped
+    workload (short documents, 90M tokens, V=141K), fitted with its K=5,000."""
+    if name not in _CORPORA:
+        _CORPORA.clear()                       # one large corpus in memory at a time
+        t = time.time()
+        spec = corpusgen.SPECS["C3"] if name == "C3" else corpusgen.scaled(corpusgen.SPECS["C4"], 1_000_000)
+        c = corpusgen.generate(spec, with_topics=False)
+        say("[fullsize] corpus %s T=%d generated in %.1fs" % (spec.name, c.T, time.time() - t))
+        if name == "C3":
+            assert c.T == 100_000_000 and c.spec.D == 300_000 and c.spec.V == 100_000
+        _CORPORA[name] = c
+    return _CORPORA[name]
+
+
+@pytest.mark.parametrize("name,K", [("C3", 1000), ("C3", 10000), ("C4p", 5000)])
+def test_full_size_parity(name, K):
     import paper_1610_02496_amd as pk
-    c = corpus
+    c = corpus_for(name)
     s = c.spec
     alpha, beta, seed = 50.0 / K, s.beta, s.seed
     t = time.time()
@@ -99,6 +108,6 @@ def test_full_size_parity(corpus, K):
     st = g.get_stats()
     assert st["sum_tokens"] == c.T and st["nnz_cd"] == o_ptr[-1]
     ll = g.loglik()
-    assert np.isfinite(ll) and -12.0 < ll < -4.0
+    assert np.isfinite(ll) and -12.0 < ll < -3.0
     say("[fullsize] K=%d invariants and A after iteration 1 ok, loglik %.4f (%.1fs)" % (K, ll, time.time() - t))
     g.close(); o.close()
