@@ -29,21 +29,30 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes(st, K, z_bytes, chunks_words_present):
+def algorithmic_bytes(st, K, z_bytes):
     """HBM bytes the sampling kernel must move for the iterations counted in ``st`` (model stated in the design doc).
 
     per token : 4 (document id) + 4 (token index) + 8 (row descriptor) + z_bytes (assignment written)
-                + 4 (one count added to B)
+                + 4 (one count added to the dense row of B) or, for a token of a light word, z_bytes (its
+                assignment written a second time, in word-major order, for that word's CountByVZ)
     per run of consecutive tokens of one (word, document) pair : 4*K_d (the packed row of A, fetched once)
-    per (word, chunk) with tokens : the Bhat row, the tree level above it and the block bases, staged once:
-                4*Kpad + 4*n3pad + 8*n3, plus the row total, 4
+    per (word, chunk) with tokens : the tree level above the bottom and the block bases, 4*n3pad + 8*n3, the
+                row total, 4, and the Bhat row: 4*Kpad for a dense row, or 8 (descriptor) + 8 per non-zero of
+                the sparse row of a light word
+    per iteration : the base vector the light words share, 4*Kpad
     Bhat gathers and the dense branch are served from LDS and count as zero.
     """
     kpad = (K + 63) // 64 * 64
     n3 = kpad // 64
     n3pad = (n3 + 63) // 64 * 64
-    tok = st["sum_tokens"] * (4 + 4 + 8 + z_bytes + 4) + 4 * st["sum_row_fetch"]
-    stage = st["iterations"] * chunks_words_present * (4 * kpad + 4 * n3pad + 8 * n3 + 4)
+    it = st["iterations"]
+    light_share = st["light_tokens"] / max(1, st["tokens"])
+    tok = st["sum_tokens"] * (4 + 4 + 8 + z_bytes + 4 * (1.0 - light_share) + z_bytes * light_share)
+    tok += 4 * st["sum_row_fetch"]
+    tree = 4 * n3pad + 8 * n3 + 4
+    dense_rows = st["words_present"] - st["light_words_present"]
+    stage = it * (dense_rows * (4 * kpad + tree) + st["light_words_present"] * (8 + tree))
+    stage += 8 * st["sum_light_entries"] + (it * 4 * kpad if st["light_words_present"] else 0)
     return tok + stage
 
 
@@ -82,7 +91,7 @@ def run_gpu(corpus, K, steps, warmup, opts):
     T = corpus.T
     z_bytes = 2 if K <= 65536 else 4
     launches = max(1, st["sample_launches"])
-    bytes_total = algorithmic_bytes(st, K, z_bytes, st["words_present"])
+    bytes_total = algorithmic_bytes(st, K, z_bytes)
     ms_sample = st["ms_sample"]
     achieved = bytes_total / (ms_sample * 1e-3) / 1e9 if ms_sample > 0 else 0.0
     res = {

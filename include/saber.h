@@ -60,7 +60,10 @@ typedef struct saber_options {
     int32_t stage_min_tokens;   /* tiles with at least this many tokens are launched with block_threads threads, smaller
                                    ones with light_block_threads; default 1 (one class) */
     int32_t light_block_threads;/* workgroup size for the smaller tiles; default: as block_threads */
-    int32_t reserved[7];
+    int32_t light_word_tokens;  /* words with fewer tokens than this keep their row of B sparse (rebuilt by a segmented
+                                   count, like a row of A) and their Bhat row is formed in LDS from a base vector and
+                                   the non-zeros; default K/2; negative: every word keeps a dense row */
+    int32_t reserved[6];
 } saber_options;
 
 /* Sums over the iterations run since the last saber_reset_stats.  The ms_* fields need profile=1. */
@@ -85,7 +88,12 @@ typedef struct saber_stats {
     int64_t sum_row_fetch;    /* like sum_row_entries, counting a row once per run of consecutive tokens of one
                                  (word, document) pair: the entries the sampler has to fetch */
     int64_t next_row_fetch;   /* sum_d K_d * U_d, U_d = distinct words of document d */
-    int64_t reserved[6];
+    /* words whose row of B is kept sparse (light words): */
+    int64_t light_words_present; /* (light word, chunk) pairs with at least one token (layout constant) */
+    int64_t light_tokens;        /* tokens of light words (layout constant) */
+    int64_t sum_light_entries;   /* non-zeros of the sparse rows the counted E-steps staged, once per word */
+    int64_t next_light_entries;  /* non-zeros of the sparse rows after the last M-step */
+    int64_t reserved[2];
 } saber_stats;
 
 /* Fill *opt with the defaults. */

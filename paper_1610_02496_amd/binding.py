@@ -33,7 +33,8 @@ class Options(ctypes.Structure):
     _fields_ = [("n_chunks", ctypes.c_int32), ("block_threads", ctypes.c_int32), ("tile_tokens", ctypes.c_int32),
                 ("stage_phi", ctypes.c_int32), ("profile", ctypes.c_int32), ("long_doc_tokens", ctypes.c_int32),
                 ("dz_lds_entries", ctypes.c_int32), ("stage_min_tokens", ctypes.c_int32),
-                ("light_block_threads", ctypes.c_int32), ("reserved", ctypes.c_int32 * 7)]
+                ("light_block_threads", ctypes.c_int32), ("light_word_tokens", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 6)]
 
 
 class Stats(ctypes.Structure):
@@ -43,7 +44,9 @@ class Stats(ctypes.Structure):
                 ("sum_tokens_dense", ctypes.c_int64), ("sum_row_entries", ctypes.c_int64),
                 ("nnz_cd", ctypes.c_int64), ("next_row_entries", ctypes.c_int64), ("tokens", ctypes.c_int64),
                 ("words_present", ctypes.c_int64), ("tiles", ctypes.c_int64), ("sum_row_fetch", ctypes.c_int64),
-                ("next_row_fetch", ctypes.c_int64), ("reserved", ctypes.c_int64 * 6)]
+                ("next_row_fetch", ctypes.c_int64), ("light_words_present", ctypes.c_int64),
+                ("light_tokens", ctypes.c_int64), ("sum_light_entries", ctypes.c_int64),
+                ("next_light_entries", ctypes.c_int64), ("reserved", ctypes.c_int64 * 2)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_ if n != "reserved"}

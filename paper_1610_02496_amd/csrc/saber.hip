@@ -41,10 +41,13 @@ struct Chunk {
     int64_t d0 = 0, d1 = 0;   // document range
     int64_t t0 = 0, ntok = 0; // canonical token range [t0, t0+ntok)
     int64_t tile0 = 0, ntiles = 0, words_present = 0;
-    int64_t n_heavy = 0;              // tiles are sorted by size: [0,n_heavy) form the class of large tiles
+    // tiles of the chunk: [0, n_dense) belong to words with dense B rows, sorted by size, the first n_heavy of
+    // them forming the class of large tiles; [n_dense, ntiles) belong to light words (sparse B rows)
+    int64_t n_heavy = 0, n_dense = 0;
 };
 
 constexpr int kMaxTimedIters = 32;
+constexpr int kCtr = 8;   // device counters per timed iteration
 enum { EV_BEGIN = 0, EV_SAMPLE, EV_DZ, EV_CK, EV_PHI, EV_PER_ITER };
 
 struct saber_ctx {
@@ -69,13 +72,28 @@ struct saber_ctx {
     int64_t *doc_ptr = nullptr;       // [D+1]
     int32_t *short_docs = nullptr, *long_docs = nullptr;
     int64_t n_short = 0, n_long = 0;
-    int32_t *cwk = nullptr;           // [V][Kpad]
+    // words: V_dense keep dense rows of B and Bhat (row V_dense is an all-zero row that yields the base vector);
+    // V_light keep B sparse, like the rows of A
+    int32_t V_dense = 0, V_light = 0;
+    int32_t *row_word = nullptr;      // [V_dense+1] word of each dense row (the zero row maps to word index V)
+    int32_t *light_words = nullptr;   // [V_light] word of each light row
+    int32_t *light_short = nullptr, *light_long = nullptr;   // light rows by token count, for the count launches
+    int64_t n_light_short = 0, n_light_long = 0;
+    int64_t *light_tok_ptr = nullptr; // [V_light+1] positions of the light words' tokens in z_wm
+    uint2 *wrec = nullptr;            // [V_light] {row start / 32, non-zeros}
+    uint32_t *lw_ent = nullptr;       // packed rows of B of the light words
+    float *lw_phi = nullptr;          // Bhat of each such entry
+    void *z_wm = nullptr;             // [T_light] word-major assignments of the light words' tokens
+    int64_t T_light = 0, lw_cap = 0;
+    std::vector<int32_t> h_word_row;  // host: word -> dense row (>= 0) or -(light row) - 1
+    int32_t *cwk = nullptr;           // [V_dense+1][Kpad]
     unsigned long long *ck = nullptr; // [K] topic totals
     float *denom = nullptr;           // [K] denominators of Eq. 2
     float *phi = nullptr, *l3 = nullptr, *sumphi = nullptr;
     double *l3_64 = nullptr;          // [V][n3]
     uint32_t *doc_words = nullptr;    // [D] distinct words of the document
-    unsigned long long *counters = nullptr; // [kMaxTimedIters][4]: dense-branch tokens, nnz(A), sum K_d L_d, sum K_d U_d
+    unsigned long long *counters = nullptr; // [kMaxTimedIters][kCtr]: dense-branch tokens, nnz(A), sum K_d L_d, sum K_d U_d,
+                                            // non-zeros of the sparse rows of B
     double *ll_partial = nullptr;     // [max tiles per chunk]
     std::vector<Chunk> chunks;
     int64_t total_tiles = 0, max_chunk_tiles = 0;
@@ -103,7 +121,7 @@ extern "C" void saber_options_default(saber_options *opt) {
     if (!opt) return;
     memset(opt, 0, sizeof(*opt));
     opt->n_chunks = 1; opt->block_threads = 0; opt->tile_tokens = 8192; opt->stage_phi = 1; opt->profile = 0;
-    opt->long_doc_tokens = 512; opt->dz_lds_entries = 8192; opt->stage_min_tokens = 0; opt->light_block_threads = 0;
+    opt->long_doc_tokens = 512; opt->dz_lds_entries = 8192; opt->stage_min_tokens = 0; opt->light_block_threads = 0; opt->light_word_tokens = 0;
 }
 
 extern "C" void saber_free(saber_ctx *c) {
@@ -113,6 +131,8 @@ extern "C" void saber_free(saber_ctx *c) {
     dev_free(c->cd_ent); dev_free(c->doc_ptr); dev_free(c->short_docs); dev_free(c->long_docs); dev_free(c->cwk);
     dev_free(c->ck); dev_free(c->denom); dev_free(c->phi); dev_free(c->l3_64); dev_free(c->l3); dev_free(c->sumphi); dev_free(c->doc_words);
     dev_free(c->counters); dev_free(c->ll_partial);
+    dev_free(c->row_word); dev_free(c->light_words); dev_free(c->light_short); dev_free(c->light_long);
+    dev_free(c->light_tok_ptr); dev_free(c->wrec); dev_free(c->lw_ent); dev_free(c->lw_phi); dev_free(c->z_wm);
     if (c->have_events) for (auto &e : c->ev) if (e) (void)hipEventDestroy(e);
     if (c->stream) (void)hipStreamDestroy(c->stream);
     delete c;
@@ -128,6 +148,8 @@ static EStepParams make_params(saber_ctx *c, const Chunk &ch) {
     p.docrec = c->docrec; p.cd_ent = c->cd_ent;
     p.phi = c->phi; p.l3 = c->l3; p.l3_64 = c->l3_64; p.sumphi = c->sumphi;
     p.z = c->z; p.cwk = c->cwk;
+    p.base = c->phi + (size_t)c->V_dense * (size_t)c->Kpad;
+    p.wrec = c->wrec; p.lw_ent = c->lw_ent; p.lw_phi = c->lw_phi; p.z_wm = c->z_wm;
     p.t_base = ch.t0; p.K = c->K; p.Kpad = c->Kpad; p.n3 = c->n3; p.n3pad = c->n3pad;
     p.topic_bits = c->topic_bits; p.topic_mask = c->topic_mask; p.alpha = c->alpha;
     p.seed_lo = (uint32_t)c->seed; p.seed_hi = (uint32_t)(c->seed >> 32); p.iter = c->iter;
@@ -142,25 +164,32 @@ static size_t estep_lds_bytes(const saber_ctx *c, bool lhist) {
 }
 
 template <int MODE, bool STAGED, typename ZT>
-static void launch_estep_b16(saber_ctx *c, dim3 grid, dim3 block, size_t lds, const EStepParams &p, bool lhist) {
-    if (lhist) {
-        if (c->b16) hipLaunchKernelGGL((estep_kernel<MODE_SAMPLE, true, uint16_t, true, true>), grid, block, lds, c->stream, p);
-        else hipLaunchKernelGGL((estep_kernel<MODE_SAMPLE, true, uint16_t, false, true>), grid, block, lds, c->stream, p);
+static void launch_estep_b16(saber_ctx *c, dim3 grid, dim3 block, size_t lds, const EStepParams &p, bool lhist, bool light) {
+    if (light) {   // light words exist only in the staged, 16-bit-z configuration
+        if (c->b16) hipLaunchKernelGGL((estep_kernel<MODE, true, uint16_t, true, false, true>), grid, block, lds, c->stream, p);
+        else hipLaunchKernelGGL((estep_kernel<MODE, true, uint16_t, false, false, true>), grid, block, lds, c->stream, p);
         return;
     }
-    if (c->b16) hipLaunchKernelGGL((estep_kernel<MODE, STAGED, ZT, true, false>), grid, block, lds, c->stream, p);
-    else hipLaunchKernelGGL((estep_kernel<MODE, STAGED, ZT, false, false>), grid, block, lds, c->stream, p);
+    if (lhist) {
+        if (c->b16) hipLaunchKernelGGL((estep_kernel<MODE_SAMPLE, true, uint16_t, true, true, false>), grid, block, lds, c->stream, p);
+        else hipLaunchKernelGGL((estep_kernel<MODE_SAMPLE, true, uint16_t, false, true, false>), grid, block, lds, c->stream, p);
+        return;
+    }
+    if (c->b16) hipLaunchKernelGGL((estep_kernel<MODE, STAGED, ZT, true, false, false>), grid, block, lds, c->stream, p);
+    else hipLaunchKernelGGL((estep_kernel<MODE, STAGED, ZT, false, false, false>), grid, block, lds, c->stream, p);
 }
 
-// One E-step launch per tile class: tiles with at least stage_min_tokens tokens run with block_threads threads,
-// smaller ones with light_block_threads, so that a word with few tokens does not hold a large workgroup whose
-// wavefronts have nothing to do.  Both classes stage the word's Bhat row in LDS when it fits.
+// One E-step launch per tile class.  Dense-row tiles with at least stage_min_tokens tokens run with block_threads
+// threads, smaller ones with light_block_threads (so that a word with few tokens does not hold a large workgroup
+// whose wavefronts have nothing to do); tiles of light words run the variant that builds the Bhat row from the
+// base vector and the word's non-zeros.  All stage the row in LDS when it fits.
 template <int MODE>
 static int launch_estep(saber_ctx *c, const Chunk &ch, EStepParams &p0) {
-    struct Class { int64_t first, count; int block; };
-    const Class classes[2] = {
-        {0, ch.n_heavy, c->opt.block_threads},
-        {ch.n_heavy, ch.ntiles - ch.n_heavy, c->opt.light_block_threads},
+    struct Class { int64_t first, count; int block; bool light; };
+    const Class classes[3] = {
+        {0, ch.n_heavy, c->opt.block_threads, false},
+        {ch.n_heavy, ch.n_dense - ch.n_heavy, c->opt.light_block_threads, false},
+        {ch.n_dense, ch.ntiles - ch.n_dense, c->opt.light_block_threads, true},
     };
     for (const Class &cl : classes) {
         if (cl.count == 0) continue;
@@ -169,27 +198,31 @@ static int launch_estep(saber_ctx *c, const Chunk &ch, EStepParams &p0) {
         if (p0.out_ll) p.out_ll = p0.out_ll + cl.first;
         const dim3 grid((unsigned)cl.count), block((unsigned)cl.block);
         // small K: accumulate the tile's new assignments in an LDS histogram instead of one global atomic per token
-        const bool lhist = MODE == MODE_SAMPLE && c->staged && c->z16 && c->lds_hist;
+        const bool lhist = MODE == MODE_SAMPLE && c->staged && c->z16 && c->lds_hist && !cl.light;
         const size_t lds = c->staged ? estep_lds_bytes(c, lhist) : 0;
         if (c->staged) {
-            if (c->z16) launch_estep_b16<MODE, true, uint16_t>(c, grid, block, lds, p, lhist);
-            else launch_estep_b16<MODE, true, int32_t>(c, grid, block, lds, p, false);
+            if (c->z16) launch_estep_b16<MODE, true, uint16_t>(c, grid, block, lds, p, lhist, cl.light);
+            else launch_estep_b16<MODE, true, int32_t>(c, grid, block, lds, p, false, false);
         } else {
-            if (c->z16) launch_estep_b16<MODE, false, uint16_t>(c, grid, block, lds, p, false);
-            else launch_estep_b16<MODE, false, int32_t>(c, grid, block, lds, p, false);
+            if (c->z16) launch_estep_b16<MODE, false, uint16_t>(c, grid, block, lds, p, false, false);
+            else launch_estep_b16<MODE, false, int32_t>(c, grid, block, lds, p, false, false);
         }
         HIP_TRY(hipGetLastError());
     }
     return SABER_OK;
 }
 
-static int launch_count_dz(saber_ctx *c) {
+// Segmented count of one grouping of the assignments: documents over z (CountByDZ -> rows of A) or light words
+// over z_wm (CountByVZ -> sparse rows of B).  Two launches: short segments with one wavefront each, long ones
+// with 256 threads.
+static int launch_segmented_count(saber_ctx *c, const int32_t *short_list, int64_t n_short, const int32_t *long_list,
+                                  int64_t n_long, const int64_t *seg_ptr, const void *z, uint2 *rec, uint32_t *ent) {
     for (int pass = 0; pass < 2; pass++) {
-        const int64_t n = pass == 0 ? c->n_short : c->n_long;
-        const int32_t *list = pass == 0 ? c->short_docs : c->long_docs;
+        const int64_t n = pass == 0 ? n_short : n_long;
+        const int32_t *list = pass == 0 ? short_list : long_list;
         const int block = pass == 0 ? 64 : 256;
         if (n == 0) continue;
-        // LDS: bitmap + rank prefix (2 * nwords) + the row under construction; a short document's row has at
+        // LDS: bitmap + rank prefix (2 * nwords) + the row under construction; a short segment's row has at
         // most long_doc_tokens entries, so its workgroup asks for no more than that
         const int budget = std::max(0, (int)((63 * 1024 - 8 * (int64_t)c->nwords) / 4));
         const int want = pass == 0 ? std::min(c->opt.long_doc_tokens, c->K) : c->opt.dz_lds_entries;
@@ -201,24 +234,48 @@ static int launch_count_dz(saber_ctx *c) {
         }
         const dim3 grid((unsigned)n), blk((unsigned)block);
         if (c->z16)
-            hipLaunchKernelGGL((count_dz_kernel<uint16_t>), grid, blk, lds, c->stream, list, c->doc_ptr,
-                               (const uint16_t *)c->z, c->docrec, c->cd_ent, c->K, c->topic_bits, c->nwords,
-                               entries);
+            hipLaunchKernelGGL((count_dz_kernel<uint16_t>), grid, blk, lds, c->stream, list, seg_ptr,
+                               (const uint16_t *)z, rec, ent, c->K, c->topic_bits, c->nwords, entries);
         else
-            hipLaunchKernelGGL((count_dz_kernel<int32_t>), grid, blk, lds, c->stream, list, c->doc_ptr,
-                               (const int32_t *)c->z, c->docrec, c->cd_ent, c->K, c->topic_bits, c->nwords,
-                               entries);
+            hipLaunchKernelGGL((count_dz_kernel<int32_t>), grid, blk, lds, c->stream, list, seg_ptr,
+                               (const int32_t *)z, rec, ent, c->K, c->topic_bits, c->nwords, entries);
         HIP_TRY(hipGetLastError());
     }
     return SABER_OK;
 }
 
-// nnz(A), sum_d K_d L_d and sum_d K_d U_d (what the next E-step will read) into three device counters
+static int launch_count_dz(saber_ctx *c) {
+    return launch_segmented_count(c, c->short_docs, c->n_short, c->long_docs, c->n_long, c->doc_ptr, c->z, c->docrec,
+                                  c->cd_ent);
+}
+
+// CountByVZ + Preprocess + BuildTree for the light words (sparse rows of B); needs the base vector, i.e. runs
+// after launch_phi
+static int launch_light_words(saber_ctx *c) {
+    if (c->V_light == 0) return SABER_OK;
+    SABER_TRY(launch_segmented_count(c, c->light_short, c->n_light_short, c->light_long, c->n_light_long,
+                                     c->light_tok_ptr, c->z_wm, c->wrec, c->lw_ent));
+    const size_t lds = (size_t)c->n3 * (sizeof(double) + sizeof(int));
+    hipLaunchKernelGGL(light_tree_kernel, dim3((unsigned)c->V_light), dim3(64), lds, c->stream, c->light_words, c->wrec,
+                       c->lw_ent, c->lw_phi, c->denom, c->phi + (size_t)c->V_dense * (size_t)c->Kpad,
+                       c->l3_64 + (size_t)c->V * (size_t)c->n3, c->l3, c->l3_64, c->sumphi, c->n3, c->n3pad,
+                       c->topic_bits, c->beta);
+    HIP_TRY(hipGetLastError());
+    return SABER_OK;
+}
+
+// nnz(A), sum_d K_d L_d, sum_d K_d U_d and the non-zeros of the sparse rows of B (what the next E-step will
+// read) into four device counters
 static int launch_row_stats(saber_ctx *c, unsigned long long *out2) {
     if (c->D == 0) return SABER_OK;
     hipLaunchKernelGGL(row_stats_kernel, dim3(grid_for(c->D, 256, 1024)), dim3(256), 0, c->stream, c->docrec,
                        c->doc_ptr, c->doc_words, c->D, out2);
     HIP_TRY(hipGetLastError());
+    if (c->V_light) {
+        hipLaunchKernelGGL(light_stats_kernel, dim3(grid_for(c->V_light, 256, 256)), dim3(256), 0, c->stream, c->wrec,
+                           c->V_light, out2 + 3);
+        HIP_TRY(hipGetLastError());
+    }
     return SABER_OK;
 }
 
@@ -243,23 +300,31 @@ static int launch_topic_totals(saber_ctx *c) {
 static int launch_phi(saber_ctx *c) {
     hipLaunchKernelGGL(denominators_kernel, dim3(grid_for(c->K, 256)), dim3(256), 0, c->stream, c->ck, c->denom, c->K, c->vbeta);
     HIP_TRY(hipGetLastError());
-    hipLaunchKernelGGL(phi_tree_kernel, dim3((unsigned)c->V), dim3(256), 0, c->stream, c->cwk, c->denom, c->phi,
-                       c->l3, c->l3_64, c->sumphi, c->K, c->Kpad, c->n3, c->n3pad, c->beta, 1);
+    hipLaunchKernelGGL(phi_tree_kernel, dim3((unsigned)(c->V_dense + 1)), dim3(256), 0, c->stream, c->cwk, c->denom, c->phi,
+                       c->l3, c->l3_64, c->sumphi, c->row_word, c->K, c->Kpad, c->n3, c->n3pad, c->beta, 1);
     HIP_TRY(hipGetLastError());
     return SABER_OK;
 }
 
-// B from scratch out of z (after init / set_z).  B must be all zero on entry (the Bhat kernel leaves it so).
-static int launch_count_vz(saber_ctx *c) {
+// B from scratch out of z (after init / set_z): dense rows by atomics (they must be all zero on entry, which
+// the Bhat kernel leaves them), light words get their word-major copy of z.
+static int launch_count_vz(saber_ctx *c, bool dense_rows, bool light_copy) {
     for (const Chunk &ch : c->chunks) {
-        if (ch.ntiles == 0) continue;
-        if (c->z16)
-            hipLaunchKernelGGL((count_vz_kernel<uint16_t>), dim3((unsigned)ch.ntiles), dim3(256), 0, c->stream,
-                               c->tiles + ch.tile0, c->tok_t + ch.t0, (const uint16_t *)c->z, ch.t0, c->cwk, c->Kpad);
-        else
-            hipLaunchKernelGGL((count_vz_kernel<int32_t>), dim3((unsigned)ch.ntiles), dim3(256), 0, c->stream,
-                               c->tiles + ch.tile0, c->tok_t + ch.t0, (const int32_t *)c->z, ch.t0, c->cwk, c->Kpad);
-        HIP_TRY(hipGetLastError());
+        if (dense_rows && ch.n_dense > 0) {
+            if (c->z16)
+                hipLaunchKernelGGL((count_vz_kernel<uint16_t>), dim3((unsigned)ch.n_dense), dim3(256), 0, c->stream,
+                                   c->tiles + ch.tile0, c->tok_t + ch.t0, (const uint16_t *)c->z, ch.t0, c->cwk, c->Kpad);
+            else
+                hipLaunchKernelGGL((count_vz_kernel<int32_t>), dim3((unsigned)ch.n_dense), dim3(256), 0, c->stream,
+                                   c->tiles + ch.tile0, c->tok_t + ch.t0, (const int32_t *)c->z, ch.t0, c->cwk, c->Kpad);
+            HIP_TRY(hipGetLastError());
+        }
+        if (light_copy && ch.ntiles > ch.n_dense) {
+            hipLaunchKernelGGL((fill_zwm_kernel<uint16_t>), dim3((unsigned)(ch.ntiles - ch.n_dense)), dim3(256), 0, c->stream,
+                               c->tiles + ch.tile0 + ch.n_dense, c->tok_t + ch.t0, (const uint16_t *)c->z, ch.t0,
+                               (uint16_t *)c->z_wm);
+            HIP_TRY(hipGetLastError());
+        }
     }
     return SABER_OK;
 }
@@ -267,22 +332,24 @@ static int launch_count_vz(saber_ctx *c) {
 // The M-step after the assignments changed outside an E-step: all four rebuilds of Alg. 1.
 static int full_mstep(saber_ctx *c) {
     SABER_TRY(launch_count_dz(c));
-    SABER_TRY(launch_count_vz(c));
+    SABER_TRY(launch_count_vz(c, true, true));
     SABER_TRY(launch_topic_totals(c));
     SABER_TRY(launch_phi(c));
+    SABER_TRY(launch_light_words(c));
     HIP_TRY(hipStreamSynchronize(c->stream));
     return SABER_OK;
 }
 
 // Workload numbers of the E-step that will read the current A: nnz(A) and sum_d K_d * L_d.
 static int refresh_workload_stats(saber_ctx *c) {
-    hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, c->stream, (uint32_t *)c->counters, 0u, (size_t)8);
+    hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, c->stream, (uint32_t *)c->counters, 0u, (size_t)kCtr * 2);
     HIP_TRY(hipGetLastError());
     SABER_TRY(launch_row_stats(c, c->counters + 1));
     HIP_TRY(hipStreamSynchronize(c->stream));
-    unsigned long long h[4];
+    unsigned long long h[kCtr];
     HIP_TRY(hipMemcpy(h, c->counters, sizeof(h), hipMemcpyDeviceToHost));
     c->stats.nnz_cd = (int64_t)h[1]; c->stats.next_row_entries = (int64_t)h[2]; c->stats.next_row_fetch = (int64_t)h[3];
+    c->stats.next_light_entries = (int64_t)h[4];
     return SABER_OK;
 }
 
@@ -313,7 +380,43 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
             if (ch.d1 > ch.d0) c->chunks.push_back(ch);
         }
     }
+    // ---- words: dense rows of B for the frequent ones, sparse rows for the rest ----
+    // A word with n tokens has at most n non-zero counts; below light_word_tokens tokens its sparse row
+    // (8 bytes per non-zero, rebuilt by a segmented count like a row of A) is cheaper than 12*K bytes of dense B / Bhat
+    // traffic per iteration.  Needs the LDS-staged sampler and 16-bit assignments.
+    std::vector<int64_t> n_v((size_t)V, 0);
+    for (int64_t t = 0; t < T; t++) n_v[(size_t)word_ids[t]]++;
+    const bool light_ok = c->staged && c->z16 && c->opt.light_word_tokens > 0;
+    // a packed entry of a sparse row has at least 16 count bits when the assignments are 16-bit
+    c->opt.light_word_tokens = std::min(c->opt.light_word_tokens, 65536);
+    c->h_word_row.assign((size_t)V, 0);
+    std::vector<int32_t> h_row_word, h_light_words, h_light_short, h_light_long;
+    std::vector<int64_t> h_light_tok_ptr(1, 0);
+    std::vector<uint2> h_wrec;
+    {
+        int64_t lunits = 0;
+        for (int32_t v = 0; v < V; v++) {
+            if (light_ok && n_v[(size_t)v] < c->opt.light_word_tokens) {
+                const int32_t li = (int32_t)h_light_words.size();
+                c->h_word_row[(size_t)v] = -li - 1;
+                h_light_words.push_back(v);
+                h_light_tok_ptr.push_back(h_light_tok_ptr.back() + n_v[(size_t)v]);
+                if (lunits > 0xffffffffll) return fail(SABER_ERANGE, "sparse rows of B exceed 2^32 * 128 bytes");
+                h_wrec.push_back(make_uint2((uint32_t)lunits, 0u));
+                lunits += (std::min<int64_t>(n_v[(size_t)v], K) + 31) / 32;
+                (n_v[(size_t)v] > c->opt.long_doc_tokens ? h_light_long : h_light_short).push_back(li);
+            } else {
+                c->h_word_row[(size_t)v] = (int32_t)h_row_word.size();
+                h_row_word.push_back(v);
+            }
+        }
+        c->V_dense = (int32_t)h_row_word.size(); c->V_light = (int32_t)h_light_words.size();
+        h_row_word.push_back(V);   // the all-zero row: its Bhat is the base vector, its tree level the base running sums
+        c->T_light = h_light_tok_ptr.back(); c->lw_cap = lunits * 32;
+        c->n_light_short = (int64_t)h_light_short.size(); c->n_light_long = (int64_t)h_light_long.size();
+    }
     // ---- word-major token arrays and tiles per chunk (host counting sort; layout only) ----
+    std::vector<int64_t> light_seen((size_t)c->V_light, 0);   // tokens of each light word placed so far (chunk by chunk)
     std::vector<int32_t> h_tok_doc((size_t)std::max<int64_t>(T, 1));
     std::vector<uint32_t> h_tok_t((size_t)std::max<int64_t>(T, 1));
     std::vector<Tile> h_tiles;
@@ -326,21 +429,36 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
         const size_t first_tile = h_tiles.size();
         for (int32_t v = 0; v < V; v++) {
             const int64_t b = wcount[(size_t)v], e = wcount[(size_t)v + 1];
-            if (e > b) ch.words_present++;
-            for (int64_t s = b; s < e; s += tile_tokens)
-                h_tiles.push_back(Tile{v, (int32_t)s, (int32_t)std::min<int64_t>(tile_tokens, e - s), 0});
+            const int32_t row = c->h_word_row[(size_t)v];
+            if (e > b) { ch.words_present++; if (row < 0) c->stats.light_words_present++; }
+            for (int64_t s = b; s < e; s += tile_tokens) {
+                const int32_t cnt = (int32_t)std::min<int64_t>(tile_tokens, e - s);
+                Tile tl{v, (int32_t)s, cnt, row >= 0 ? row : -row - 1, 0, 0};
+                if (row < 0) {
+                    tl.wm_begin = h_light_tok_ptr[(size_t)(-row - 1)] + light_seen[(size_t)(-row - 1)];
+                    light_seen[(size_t)(-row - 1)] += cnt;
+                }
+                h_tiles.push_back(tl);
+            }
         }
         for (int64_t d = ch.d0; d < ch.d1; d++)
             for (int64_t t = doc_ptr[d]; t < doc_ptr[d + 1]; t++) {
                 const int64_t pos = ch.t0 + wcount[(size_t)word_ids[t]]++;
                 h_tok_doc[(size_t)pos] = (int32_t)d; h_tok_t[(size_t)pos] = (uint32_t)(t - ch.t0);
             }
-        // heavy tiles first so the tail of the launch is made of small ones (Sec. 3.4)
-        std::stable_sort(h_tiles.begin() + (ptrdiff_t)first_tile, h_tiles.end(),
-                         [](const Tile &a, const Tile &b) { return a.count > b.count; });
+        // tiles of dense-row words first, then those of light words; inside each group heavy tiles first so the
+        // tail of a launch is made of small ones (Sec. 3.4)
+        const std::vector<int32_t> &wr = c->h_word_row;
+        std::stable_sort(h_tiles.begin() + (ptrdiff_t)first_tile, h_tiles.end(), [&wr](const Tile &a, const Tile &b) {
+            const bool la = wr[(size_t)a.word] < 0, lb = wr[(size_t)b.word] < 0;
+            return la != lb ? lb : a.count > b.count;
+        });
         ch.tile0 = (int64_t)first_tile; ch.ntiles = (int64_t)(h_tiles.size() - first_tile);
-        for (size_t i = first_tile; i < h_tiles.size(); i++)
+        for (size_t i = first_tile; i < h_tiles.size(); i++) {
+            if (wr[(size_t)h_tiles[i].word] < 0) continue;
+            ch.n_dense++;
             if (h_tiles[i].count >= c->opt.stage_min_tokens) ch.n_heavy++;
+        }
         c->max_chunk_tiles = std::max(c->max_chunk_tiles, ch.ntiles);
     }
     c->total_tiles = (int64_t)h_tiles.size();
@@ -372,17 +490,30 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     c->n_short = (int64_t)h_short.size(); c->n_long = (int64_t)h_long.size();
 
     // ---- device memory ----
-    const size_t vk = (size_t)V * (size_t)c->Kpad;
+    const size_t vk = ((size_t)c->V_dense + 1) * (size_t)c->Kpad;
     if (c->z16) SABER_TRY(dev_alloc((uint16_t **)&c->z, (size_t)T)); else SABER_TRY(dev_alloc((int32_t **)&c->z, (size_t)T));
     SABER_TRY(dev_alloc(&c->tok_doc, (size_t)T)); SABER_TRY(dev_alloc(&c->tok_t, (size_t)T));
     SABER_TRY(dev_alloc(&c->tiles, h_tiles.size())); SABER_TRY(dev_alloc(&c->docrec, (size_t)D));
     SABER_TRY(dev_alloc(&c->cd_ent, (size_t)c->cd_cap)); SABER_TRY(dev_alloc(&c->doc_ptr, (size_t)D + 1));
     SABER_TRY(dev_alloc(&c->short_docs, h_short.size())); SABER_TRY(dev_alloc(&c->long_docs, h_long.size()));
     SABER_TRY(dev_alloc(&c->cwk, vk)); SABER_TRY(dev_alloc(&c->ck, (size_t)K)); SABER_TRY(dev_alloc(&c->denom, (size_t)K));
-    SABER_TRY(dev_alloc(&c->phi, vk)); SABER_TRY(dev_alloc(&c->l3_64, (size_t)V * (size_t)c->n3));
+    SABER_TRY(dev_alloc(&c->phi, vk)); SABER_TRY(dev_alloc(&c->l3_64, ((size_t)V + 1) * (size_t)c->n3));
+    SABER_TRY(dev_alloc(&c->row_word, h_row_word.size())); SABER_TRY(dev_alloc(&c->light_words, h_light_words.size()));
+    SABER_TRY(dev_alloc(&c->light_short, h_light_short.size())); SABER_TRY(dev_alloc(&c->light_long, h_light_long.size()));
+    SABER_TRY(dev_alloc(&c->light_tok_ptr, h_light_tok_ptr.size())); SABER_TRY(dev_alloc(&c->wrec, h_wrec.size()));
+    SABER_TRY(dev_alloc(&c->lw_ent, (size_t)c->lw_cap)); SABER_TRY(dev_alloc(&c->lw_phi, (size_t)c->lw_cap));
+    SABER_TRY(dev_alloc((uint16_t **)&c->z_wm, (size_t)c->T_light));
+    HIP_TRY(hipMemcpy(c->row_word, h_row_word.data(), sizeof(int32_t) * h_row_word.size(), hipMemcpyHostToDevice));
+    HIP_TRY(hipMemcpy(c->light_tok_ptr, h_light_tok_ptr.data(), sizeof(int64_t) * h_light_tok_ptr.size(), hipMemcpyHostToDevice));
+    if (c->V_light) {
+        HIP_TRY(hipMemcpy(c->light_words, h_light_words.data(), sizeof(int32_t) * h_light_words.size(), hipMemcpyHostToDevice));
+        HIP_TRY(hipMemcpy(c->wrec, h_wrec.data(), sizeof(uint2) * h_wrec.size(), hipMemcpyHostToDevice));
+        if (!h_light_short.empty()) HIP_TRY(hipMemcpy(c->light_short, h_light_short.data(), sizeof(int32_t) * h_light_short.size(), hipMemcpyHostToDevice));
+        if (!h_light_long.empty()) HIP_TRY(hipMemcpy(c->light_long, h_light_long.data(), sizeof(int32_t) * h_light_long.size(), hipMemcpyHostToDevice));
+    }
     SABER_TRY(dev_alloc(&c->doc_words, (size_t)D));
-    SABER_TRY(dev_alloc(&c->l3, (size_t)V * (size_t)c->n3pad)); SABER_TRY(dev_alloc(&c->sumphi, (size_t)V));
-    SABER_TRY(dev_alloc(&c->counters, (size_t)kMaxTimedIters * 4));
+    SABER_TRY(dev_alloc(&c->l3, ((size_t)V + 1) * (size_t)c->n3pad)); SABER_TRY(dev_alloc(&c->sumphi, (size_t)V + 1));
+    SABER_TRY(dev_alloc(&c->counters, (size_t)kMaxTimedIters * kCtr));
     SABER_TRY(dev_alloc(&c->ll_partial, (size_t)std::max<int64_t>(c->max_chunk_tiles, 1)));
     if (T) {
         HIP_TRY(hipMemcpy(c->tok_doc, h_tok_doc.data(), sizeof(int32_t) * (size_t)T, hipMemcpyHostToDevice));
@@ -412,6 +543,7 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     c->stats.tokens = T; c->stats.tiles = c->total_tiles;
     c->stats.words_present = 0;
     for (const Chunk &ch : c->chunks) c->stats.words_present += ch.words_present;
+    c->stats.light_tokens = c->T_light;
     return SABER_OK;
 }
 
@@ -452,6 +584,7 @@ extern "C" int saber_init_ex(saber_ctx **out, const int64_t *doc_ptr, const int3
         if (opt_in->dz_lds_entries > 0) opt.dz_lds_entries = opt_in->dz_lds_entries;
         if (opt_in->stage_min_tokens > 0) opt.stage_min_tokens = opt_in->stage_min_tokens;
         if (opt_in->light_block_threads > 0) opt.light_block_threads = opt_in->light_block_threads;
+        opt.light_word_tokens = opt_in->light_word_tokens;
         opt.stage_phi = opt_in->stage_phi; opt.profile = opt_in->profile;
         if (opt_in->stage_phi < 0) opt.stage_phi = 1;
     }
@@ -461,6 +594,7 @@ extern "C" int saber_init_ex(saber_ctx **out, const int64_t *doc_ptr, const int3
     if (opt.light_block_threads > 0 && (opt.light_block_threads % 64 || opt.light_block_threads > 1024))
         return fail(SABER_EINVAL, "saber_init: light_block_threads must be a multiple of 64 in [64,1024]");
     if (opt.stage_min_tokens <= 0) opt.stage_min_tokens = 1;
+    if (opt.light_word_tokens == 0) opt.light_word_tokens = std::max(1, K / 2);   // < 0 keeps every word dense
     if (opt.n_chunks > 65536) return fail(SABER_EINVAL, "saber_init: n_chunks too large");
     if (opt.dz_lds_entries > 12288) return fail(SABER_EINVAL, "saber_init: dz_lds_entries must not exceed 12288");
     // token positions inside a chunk are 32-bit: keep every chunk below 2^30 tokens (documents are far shorter)
@@ -525,7 +659,7 @@ extern "C" int saber_iterate(saber_ctx *c, int32_t n) {
         const int batch = std::min<int32_t>(n - done, kMaxTimedIters);
         // per-iteration device counters: {dense-branch tokens, nnz(A), sum_d K_d L_d}
         hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, c->stream, (uint32_t *)c->counters, 0u,
-                           (size_t)kMaxTimedIters * 8);
+                           (size_t)kMaxTimedIters * kCtr * 2);
         HIP_TRY(hipGetLastError());
         for (int b = 0; b < batch; b++) {
             hipEvent_t *ev = c->ev + (size_t)b * EV_PER_ITER;
@@ -534,7 +668,7 @@ extern "C" int saber_iterate(saber_ctx *c, int32_t n) {
             // E-step: z <- Sample(A_d, Bhat_v, Q_v, T_v) for every token; B accumulates as a by-product
             for (const Chunk &ch : c->chunks) {
                 EStepParams p = make_params(c, ch);
-                p.n_dense = c->counters + 4 * b;
+                p.n_dense = c->counters + kCtr * b;
                 SABER_TRY(launch_estep<MODE_SAMPLE>(c, ch, p));
             }
             if (prof) HIP_TRY(hipEventRecord(ev[EV_SAMPLE], c->stream));
@@ -544,21 +678,24 @@ extern "C" int saber_iterate(saber_ctx *c, int32_t n) {
             SABER_TRY(launch_topic_totals(c));
             if (prof) HIP_TRY(hipEventRecord(ev[EV_CK], c->stream));
             SABER_TRY(launch_phi(c));
+            SABER_TRY(launch_light_words(c));
             if (prof) HIP_TRY(hipEventRecord(ev[EV_PHI], c->stream));
-            SABER_TRY(launch_row_stats(c, c->counters + 4 * b + 1));
+            SABER_TRY(launch_row_stats(c, c->counters + kCtr * b + 1));
         }
         HIP_TRY(hipStreamSynchronize(c->stream));
-        unsigned long long h[kMaxTimedIters * 4];
+        unsigned long long h[kMaxTimedIters * kCtr];
         HIP_TRY(hipMemcpy(h, c->counters, sizeof(h), hipMemcpyDeviceToHost));
         for (int b = 0; b < batch; b++) {
             // the E-step of this iteration read the rows counted at the end of the previous one
             c->stats.sum_tokens += c->T;
-            c->stats.sum_tokens_dense += (int64_t)h[4 * b];
+            c->stats.sum_tokens_dense += (int64_t)h[kCtr * b];
             c->stats.sum_row_entries += c->stats.next_row_entries;
             c->stats.sum_row_fetch += c->stats.next_row_fetch;
-            c->stats.nnz_cd = (int64_t)h[4 * b + 1];
-            c->stats.next_row_entries = (int64_t)h[4 * b + 2];
-            c->stats.next_row_fetch = (int64_t)h[4 * b + 3];
+            c->stats.sum_light_entries += c->stats.next_light_entries;
+            c->stats.nnz_cd = (int64_t)h[kCtr * b + 1];
+            c->stats.next_row_entries = (int64_t)h[kCtr * b + 2];
+            c->stats.next_row_fetch = (int64_t)h[kCtr * b + 3];
+            c->stats.next_light_entries = (int64_t)h[kCtr * b + 4];
             if (prof) {
                 hipEvent_t *ev = c->ev + (size_t)b * EV_PER_ITER;
                 float ms[4], tot;
@@ -619,16 +756,41 @@ extern "C" int saber_counts(saber_ctx *c, int64_t *cd_row_ptr, int32_t *cd_topic
             }
         }
         if (cwk) {
-            // B is consumed (and cleared) by the Bhat kernel; rebuild it from z for export
-            SABER_TRY(launch_count_vz(c));
+            // dense rows: B is consumed (and cleared) by the Bhat kernel; rebuild it from z for export
+            SABER_TRY(launch_count_vz(c, true, false));
             HIP_TRY(hipStreamSynchronize(c->stream));
-            HIP_TRY(hipMemcpy2D(cwk, sizeof(int32_t) * (size_t)c->K, c->cwk, sizeof(int32_t) * (size_t)c->Kpad,
-                                sizeof(int32_t) * (size_t)c->K, (size_t)c->V, hipMemcpyDeviceToHost));
-            const size_t vk = (size_t)c->V * (size_t)c->Kpad;
+            const int64_t slab = 2048;   // rows per host staging buffer
+            std::vector<int32_t> buf((size_t)slab * (size_t)c->Kpad);
+            std::vector<int32_t> row_word((size_t)c->V_dense + 1);
+            HIP_TRY(hipMemcpy(row_word.data(), c->row_word, sizeof(int32_t) * row_word.size(), hipMemcpyDeviceToHost));
+            for (int64_t r0 = 0; r0 < c->V_dense; r0 += slab) {
+                const int64_t r1 = std::min<int64_t>(c->V_dense, r0 + slab);
+                HIP_TRY(hipMemcpy(buf.data(), c->cwk + (size_t)r0 * (size_t)c->Kpad,
+                                  sizeof(int32_t) * (size_t)(r1 - r0) * (size_t)c->Kpad, hipMemcpyDeviceToHost));
+                for (int64_t r = r0; r < r1; r++)
+                    memcpy(cwk + (size_t)row_word[(size_t)r] * (size_t)c->K, buf.data() + (size_t)(r - r0) * (size_t)c->Kpad,
+                           sizeof(int32_t) * (size_t)c->K);
+            }
+            const size_t vk = (size_t)c->V_dense * (size_t)c->Kpad;
             hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for((int64_t)vk, 256, 8192)), dim3(256), 0, c->stream,
                                (uint32_t *)c->cwk, 0u, vk);
             HIP_TRY(hipGetLastError());
             HIP_TRY(hipStreamSynchronize(c->stream));
+            // light words: unpack the sparse rows (format conversion only)
+            if (c->V_light) {
+                std::vector<uint2> wrec((size_t)c->V_light);
+                std::vector<int32_t> lwords((size_t)c->V_light);
+                HIP_TRY(hipMemcpy(wrec.data(), c->wrec, sizeof(uint2) * wrec.size(), hipMemcpyDeviceToHost));
+                HIP_TRY(hipMemcpy(lwords.data(), c->light_words, sizeof(int32_t) * lwords.size(), hipMemcpyDeviceToHost));
+                std::vector<uint32_t> ent((size_t)std::max<int64_t>(c->lw_cap, 1));
+                if (c->lw_cap) HIP_TRY(hipMemcpy(ent.data(), c->lw_ent, sizeof(uint32_t) * (size_t)c->lw_cap, hipMemcpyDeviceToHost));
+                for (int32_t li = 0; li < c->V_light; li++) {
+                    int32_t *row = cwk + (size_t)lwords[(size_t)li] * (size_t)c->K;
+                    memset(row, 0, sizeof(int32_t) * (size_t)c->K);
+                    const uint32_t *e = ent.data() + (size_t)wrec[(size_t)li].x * 32u;
+                    for (uint32_t j = 0; j < wrec[(size_t)li].y; j++) row[e[j] & c->topic_mask] = (int32_t)(e[j] >> c->topic_bits);
+                }
+            }
         }
         if (ck) {
             std::vector<unsigned long long> h((size_t)c->K);
@@ -747,27 +909,43 @@ extern "C" int saber_get_phi(saber_ctx *c, const int32_t *words, int32_t m, floa
     for (int32_t i = 0; i < m; i++)
         if (words[i] < 0 || words[i] >= c->V) return fail(SABER_EINVAL, "saber_get_phi: word %d is outside [0,%d)", words[i], c->V);
     if (m == 0) return SABER_OK;
-    if (phi)
-        for (int32_t i = 0; i < m; i++)
-            HIP_TRY(hipMemcpy(phi + (size_t)i * (size_t)c->K, c->phi + (size_t)words[i] * (size_t)c->Kpad,
-                              sizeof(float) * (size_t)c->K, hipMemcpyDeviceToHost));
-    if (prefix) {
-        // the bottom tree level is not stored: rebuild the requested rows the way the dense branch does
-        int32_t *dw = nullptr; float *dout = nullptr;
-        int rc;
-        if ((rc = dev_alloc(&dw, (size_t)m)) || (rc = dev_alloc(&dout, (size_t)m * (size_t)c->K))) { dev_free(dw); dev_free(dout); return rc; }
-        hipError_t e = hipMemcpy(dw, words, sizeof(int32_t) * (size_t)m, hipMemcpyHostToDevice);
-        if (e == hipSuccess) {
-            const int64_t items = (int64_t)m * ((c->K + 63) / 64);
-            hipLaunchKernelGGL(prefix_export_kernel, dim3((unsigned)items), dim3(64), 0, c->stream, c->phi, c->l3_64, dw, m,
-                               c->K, c->Kpad, c->n3, dout);
-            e = hipGetLastError();
+    // assemble the requested Bhat rows on the device: dense rows are copied, light rows are the base vector
+    // overwritten at the word's non-zeros; the prefix rows are then rebuilt the way the dense branch does
+    float *drows = nullptr, *dout = nullptr; int32_t *dw = nullptr, *dlight = nullptr;
+    auto cleanup = [&]() { dev_free(drows); dev_free(dout); dev_free(dw); dev_free(dlight); };
+    int rc;
+    if ((rc = dev_alloc(&drows, (size_t)m * (size_t)c->K)) || (rc = dev_alloc(&dout, (size_t)m * (size_t)c->K)) ||
+        (rc = dev_alloc(&dw, (size_t)m)) || (rc = dev_alloc(&dlight, (size_t)m))) { cleanup(); return rc; }
+    hipError_t e = hipMemcpy(dw, words, sizeof(int32_t) * (size_t)m, hipMemcpyHostToDevice);
+    for (int32_t i = 0; i < m && e == hipSuccess; i++) {
+        const int32_t row = c->h_word_row[(size_t)words[i]];
+        if (row >= 0) {
+            e = hipMemcpyAsync(drows + (size_t)i * (size_t)c->K, c->phi + (size_t)row * (size_t)c->Kpad,
+                               sizeof(float) * (size_t)c->K, hipMemcpyDeviceToDevice, c->stream);
+        } else {
+            const int32_t li = -row - 1;
+            e = hipMemcpyAsync(dlight, &li, sizeof(int32_t), hipMemcpyHostToDevice, c->stream);
+            if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+            if (e == hipSuccess) {
+                hipLaunchKernelGGL(light_rows_export_kernel, dim3(1), dim3(256), 0, c->stream, dlight, 1, c->wrec, c->lw_ent,
+                                   c->lw_phi, c->phi + (size_t)c->V_dense * (size_t)c->Kpad, c->K, c->topic_bits,
+                                   drows + (size_t)i * (size_t)c->K, (int32_t *)nullptr);
+                e = hipGetLastError();
+            }
+            if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
         }
-        if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
-        if (e == hipSuccess) e = hipMemcpy(prefix, dout, sizeof(float) * (size_t)m * (size_t)c->K, hipMemcpyDeviceToHost);
-        dev_free(dw); dev_free(dout);
-        if (e != hipSuccess) return fail(SABER_EDEVICE, "saber_get_phi: %s", hipGetErrorString(e));
     }
+    if (e == hipSuccess && prefix) {
+        const int64_t items = (int64_t)m * ((c->K + 63) / 64);
+        hipLaunchKernelGGL(prefix_export_kernel, dim3((unsigned)items), dim3(64), 0, c->stream, drows, c->l3_64, dw, m,
+                           c->K, c->n3, dout);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e == hipSuccess && phi) e = hipMemcpy(phi, drows, sizeof(float) * (size_t)m * (size_t)c->K, hipMemcpyDeviceToHost);
+    if (e == hipSuccess && prefix) e = hipMemcpy(prefix, dout, sizeof(float) * (size_t)m * (size_t)c->K, hipMemcpyDeviceToHost);
+    cleanup();
+    if (e != hipSuccess) return fail(SABER_EDEVICE, "saber_get_phi: %s", hipGetErrorString(e));
     return SABER_OK;
 }
 
@@ -780,7 +958,7 @@ extern "C" int saber_get_stats(saber_ctx *c, saber_stats *out) {
 extern "C" int saber_reset_stats(saber_ctx *c) {
     if (!c) return fail(SABER_EINVAL, "saber_reset_stats: null context");
     c->stats.iterations = 0; c->stats.ms_sample = c->stats.ms_count_dz = c->stats.ms_ck = c->stats.ms_phi = c->stats.ms_total = 0.0;
-    c->stats.sample_launches = 0; c->stats.sum_tokens = c->stats.sum_tokens_dense = c->stats.sum_row_entries = c->stats.sum_row_fetch = 0;
+    c->stats.sample_launches = 0; c->stats.sum_tokens = c->stats.sum_tokens_dense = c->stats.sum_row_entries = c->stats.sum_row_fetch = c->stats.sum_light_entries = 0;
     return SABER_OK;
 }
 

@@ -76,6 +76,18 @@ __device__ __forceinline__ double readlane_f64(double v, int lane) {
 __device__ __forceinline__ float wave_sum(float v) { return readlane_f32(wave_incl_scan(v), 63); }
 __device__ __forceinline__ uint32_t wave_sum(uint32_t v) { return readlane_u32(wave_incl_scan(v), 63); }
 
+// inclusive running maximum over the 64 lanes
+__device__ __forceinline__ int wave_incl_scan_max(int v) {
+    const int lo = -2147483647 - 1;
+    v = max(v, __builtin_amdgcn_update_dpp(lo, v, 0x111, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(lo, v, 0x112, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(lo, v, 0x114, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(lo, v, 0x118, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(lo, v, 0x142, 0xa, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(lo, v, 0x143, 0xc, 0xf, false));
+    return v;
+}
+
 // index of the first lane whose predicate holds, or -1
 __device__ __forceinline__ int wave_vote_first(bool pred) {
     unsigned long long m = __builtin_amdgcn_ballot_w64(pred);
@@ -142,7 +154,9 @@ __global__ void gather_f32_kernel(const float *src, const int64_t *idx, int64_t 
 // Work description of the E-step: one tile = up to tile_tokens tokens of one word inside one chunk.
 // Tokens of a chunk are stored word-major (partition-by-document, order-by-word, Sec. 3.1.4).
 // ---------------------------------------------------------------------------------------------
-struct Tile { int32_t word; int32_t begin; int32_t count; int32_t pad; };
+// row: the word's row in the dense B / Bhat arrays, or its index among the light words (see below)
+// wm_begin: position of the tile's first token in the corpus-wide word-major order
+struct Tile { int32_t word; int32_t begin; int32_t count; int32_t row; int64_t wm_begin; int64_t pad; };
 
 struct EStepParams {
     const Tile *tiles;
@@ -150,13 +164,19 @@ struct EStepParams {
     const uint32_t *tok_t;      // [chunk tokens] canonical token index relative to t_base
     const uint2 *docrec;        // [D] {row start in units of 32 entries, K_d}
     const uint32_t *cd_ent;     // packed rows of A: topic | count << topic_bits, ascending topic
-    const float *phi;           // [V][Kpad]  Bhat
+    const float *phi;           // [dense rows][Kpad]  Bhat
     const float *l3;            // [V][n3pad] binary32 prefix sum of the Bhat row at the end of every 64-topic block,
                                 //            padded with the row total (tree level above the bottom)
     const double *l3_64;        // [V][n3]    the same running sums before rounding (base of each bottom block)
     const float *sumphi;        // [V]        prefix sum at topic K-1 = l3[n3-1]
     void *z;                    // [T] assignments, canonical order (uint16 or int32)
-    int32_t *cwk;               // [V][Kpad] accumulator of B for the next M-step
+    int32_t *cwk;               // [dense rows][Kpad] accumulator of B for the next M-step
+    // light words (few tokens): B is kept sparse, Bhat = base + the word's non-zeros
+    const float *base;          // [Kpad] Bhat of a zero count, beta / denom_k (pad columns 0)
+    const uint2 *wrec;          // [light words] {row start in units of 32 entries, non-zeros}
+    const uint32_t *lw_ent;     // packed (topic, count) rows of B for the light words, ascending topic
+    const float *lw_phi;        // Bhat value of every such entry
+    void *z_wm;                 // [T] new assignments in word-major order (input of the light words' CountByVZ)
     float *out_S;               // probs mode: S per canonical token
     float *out_Q;               // probs mode: Q per canonical token
     double *out_ll;             // loglik mode: one partial sum per tile
@@ -281,7 +301,10 @@ __device__ __forceinline__ uint32_t search_block(const uint4 e, const RowBlock &
     return readlane_u32(sel, L) & tmask;
 }
 
-template <int MODE, bool STAGED, typename ZT, bool B16, bool LHIST>
+// LIGHT: the tile's word keeps B sparse.  Its Bhat row is built in LDS from the base vector and the word's
+// non-zeros, and the new assignments go to z_wm (coalesced) for the word's CountByVZ instead of to the dense
+// accumulator.
+template <int MODE, bool STAGED, typename ZT, bool B16, bool LHIST, bool LIGHT>
 __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
     extern __shared__ float4 lds_f4[];
     __shared__ double ll_wave[MODE == MODE_LOGLIK ? 16 : 1];
@@ -296,7 +319,7 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
     uint32_t *lds_hist = reinterpret_cast<uint32_t *>(lds_l3 + ((p.n3 + 3) & ~3));
     const Tile tile = p.tiles[blockIdx.x];
     const int K = p.K;
-    const float *__restrict__ phi_row = p.phi + (size_t)tile.word * (size_t)p.Kpad;
+    const float *__restrict__ phi_row = LIGHT ? p.base : p.phi + (size_t)tile.row * (size_t)p.Kpad;
     const float *__restrict__ l3_row = p.l3 + (size_t)tile.word * (size_t)p.n3pad;
     const double *__restrict__ l3_64_row = p.l3_64 + (size_t)tile.word * (size_t)p.n3;
     if (threadIdx.x == 0) next_batch = 0;
@@ -310,6 +333,15 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
     if (LHIST)
         for (int i = threadIdx.x; i < p.Kpad; i += blockDim.x) lds_hist[i] = 0u;
     __syncthreads();
+    if (LIGHT) {
+        // the staged row is the base vector so far; overwrite the topics this word has counts for
+        const uint2 wr = p.wrec[tile.row];
+        const uint32_t *__restrict__ ent = p.lw_ent + (size_t)wr.x * 32u;
+        const float *__restrict__ val = p.lw_phi + (size_t)wr.x * 32u;
+        const uint32_t tm = B16 ? 0xffffu : p.topic_mask;
+        for (int j = threadIdx.x; j < (int)wr.y; j += blockDim.x) lds_phi[ent[j] & tm] = val[j];
+        __syncthreads();
+    }
     const float sum_w = p.sumphi[tile.word];
     const float Q = p.alpha * sum_w;
     const int lane = lane_id(), nwaves = blockDim.x / kWave;
@@ -442,8 +474,9 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
             const int64_t tc = p.t_base + (int64_t)t;
             if (MODE == MODE_SAMPLE) {
                 reinterpret_cast<ZT *>(p.z)[tc] = (ZT)my_z;
-                if (LHIST) atomicAdd(&lds_hist[my_z], 1u);
-                else atomicAdd(&p.cwk[(size_t)tile.word * (size_t)p.Kpad + my_z], 1);
+                if (LIGHT) reinterpret_cast<ZT *>(p.z_wm)[tile.wm_begin + (int64_t)(i - tile.begin)] = (ZT)my_z;
+                else if (LHIST) atomicAdd(&lds_hist[my_z], 1u);
+                else atomicAdd(&p.cwk[(size_t)tile.row * (size_t)p.Kpad + my_z], 1);
             } else if (MODE == MODE_PROBS) {
                 p.out_S[tc] = my_S; p.out_Q[tc] = Q;
             } else {
@@ -459,7 +492,7 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
             __syncthreads();
             for (int k = threadIdx.x; k < K; k += blockDim.x) {
                 const uint32_t h = lds_hist[k];
-                if (h) atomicAdd(&p.cwk[(size_t)tile.word * (size_t)p.Kpad + k], (int)h);
+                if (h) atomicAdd(&p.cwk[(size_t)tile.row * (size_t)p.Kpad + k], (int)h);
             }
         }
     }
@@ -475,17 +508,18 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
     }
 }
 
-// The bottom tree level (inclusive binary32 prefix sums of one Bhat row), rebuilt exactly as the sampler's
-// dense branch sees it; one wavefront per (word, 64-topic block).  Export / test aid.
-__global__ void prefix_export_kernel(const float *phi, const double *l3_64, const int32_t *words, int m, int K,
-                                     int Kpad, int n3, float *out) {
+// The bottom tree level (inclusive binary32 prefix sums of one Bhat row), rebuilt as the sampler's dense branch
+// sees it; one wavefront per (row, 64-topic block).  rows[m][K] holds the Bhat rows of words[m].  Export / test aid.
+__global__ void prefix_export_kernel(const float *rows, const double *l3_64, const int32_t *words, int m, int K, int n3,
+                                     float *out) {
     const int nblk = (K + kWave - 1) / kWave;
     const int item = blockIdx.x, wi = item / nblk, blk = item % nblk, lane = lane_id();
     if (wi >= m) return;
     const size_t v = (size_t)words[wi];
-    const double base = blk > 0 ? l3_64[v * (size_t)n3 + (size_t)(blk - 1)] : 0.0;
-    const float c = (float)(base + wave_incl_scan((double)phi[v * (size_t)Kpad + (size_t)(blk * kWave + lane)]));
     const int k = blk * kWave + lane;
+    const double base = blk > 0 ? l3_64[v * (size_t)n3 + (size_t)(blk - 1)] : 0.0;
+    const float f = k < K ? rows[(size_t)wi * (size_t)K + (size_t)k] : 0.f;
+    const float c = (float)(base + wave_incl_scan((double)f));
     if (k < K) out[(size_t)wi * (size_t)K + (size_t)k] = c;
 }
 
@@ -499,8 +533,17 @@ __global__ void count_vz_kernel(const Tile *tiles, const uint32_t *tok_t, const 
     for (int i = threadIdx.x; i < tile.count; i += blockDim.x) {
         const uint32_t t = tok_t[tile.begin + i];
         const uint32_t k = (uint32_t)z[t_base + (int64_t)t];
-        atomicAdd(&cwk[(size_t)tile.word * (size_t)Kpad + k], 1);
+        atomicAdd(&cwk[(size_t)tile.row * (size_t)Kpad + k], 1);
     }
+}
+
+// word-major copy of the assignments of the light words' tokens (after init / set_z; during iterations the
+// E-step writes it)
+template <typename ZT>
+__global__ void fill_zwm_kernel(const Tile *tiles, const uint32_t *tok_t, const ZT *z, int64_t t_base, ZT *z_wm) {
+    const Tile tile = tiles[blockIdx.x];
+    for (int i = threadIdx.x; i < tile.count; i += blockDim.x)
+        z_wm[tile.wm_begin + i] = z[t_base + (int64_t)tok_t[tile.begin + i]];
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -623,14 +666,16 @@ __global__ void denominators_kernel(const unsigned long long *ck, float *denom, 
     if (k < K) denom[k] = (float)ck[k] + vbeta;
 }
 
+// row_word[r] is the word of dense row r (the tree levels are indexed by word); the last row is an all-zero
+// row that yields the base vector (Bhat of a zero count) and its running sums for the light words.
 __global__ void __launch_bounds__(256) phi_tree_kernel(int32_t *cwk, const float *denom, float *phi, float *l3,
-                                                       double *l3_64, float *sumphi, int K, int Kpad, int n3,
-                                                       int n3pad, float beta, int clear_cwk) {
+                                                       double *l3_64, float *sumphi, const int32_t *row_word, int K,
+                                                       int Kpad, int n3, int n3pad, float beta, int clear_cwk) {
     __shared__ double wave_tot[4];
     __shared__ float row_total;
-    const int v = blockIdx.x;
+    const int v = row_word[blockIdx.x];
     const int lane = lane_id(), wave = threadIdx.x / kWave;
-    const size_t rbase = (size_t)v * (size_t)Kpad;
+    const size_t rbase = (size_t)blockIdx.x * (size_t)Kpad;
     double carry = 0.0;
     for (int base = 0; base < Kpad; base += 1024) {
         const int k0 = base + (int)threadIdx.x * 4;
@@ -671,6 +716,87 @@ __global__ void __launch_bounds__(256) phi_tree_kernel(int32_t *cwk, const float
     if (threadIdx.x == 0) sumphi[v] = total;
 }
 
+// ---------------------------------------------------------------------------------------------
+// Preprocess + BuildTree for the light words (one wavefront per word).  Their Bhat row is the base vector
+// except at the word's non-zeros, so only those are evaluated (Eq. 2, same three binary32 operations) and
+// stored next to the entries.  The running sums at the block ends follow from the base vector's running sums
+// plus the cumulative difference (Bhat - base) of the non-zeros up to each block, all in binary64: the same
+// sum of the same binary32 numbers as for a dense row, associated differently.
+// LDS: n3 doubles (cumulative difference at the last non-zero of each block) + n3 flags.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(64) light_tree_kernel(const int32_t *light_words, const uint2 *wrec,
+                                                        const uint32_t *lw_ent, float *lw_phi, const float *denom,
+                                                        const float *base, const double *basecum, float *l3,
+                                                        double *l3_64, float *sumphi, int n3, int n3pad,
+                                                        uint32_t topic_bits, float beta) {
+    extern __shared__ double lds_dcum[];
+    int *written = reinterpret_cast<int *>(lds_dcum + n3);
+    const int v = light_words[blockIdx.x], lane = lane_id();
+    const uint2 wr = wrec[blockIdx.x];
+    const int nnz = (int)wr.y;
+    const uint32_t *__restrict__ ent = lw_ent + (size_t)wr.x * 32u;
+    float *__restrict__ val = lw_phi + (size_t)wr.x * 32u;
+    const uint32_t tmask = (1u << topic_bits) - 1u;
+    for (int i = lane; i < n3; i += kWave) written[i] = 0;
+    __syncthreads();
+    double carry = 0.0;
+    for (int j0 = 0; j0 < nnz; j0 += kWave) {
+        const int j = j0 + lane;
+        const bool valid = j < nnz;
+        const uint32_t e = valid ? ent[j] : 0u;
+        const uint32_t k = e & tmask;
+        double delta = 0.0;
+        if (valid) {
+            const float f = ((float)(e >> topic_bits) + beta) / denom[k];
+            val[j] = f;
+            delta = (double)f - (double)base[k];
+        }
+        const double incl = wave_incl_scan(delta) + carry;
+        const int blk = (int)(k >> 6);
+        const int next_blk = (j + 1 < nnz) ? (int)((ent[j + 1] & tmask) >> 6) : -1;
+        if (valid && blk != next_blk) { lds_dcum[blk] = incl; written[blk] = 1; }
+        carry = readlane_f64(incl, 63);
+    }
+    __syncthreads();
+    int last = -1;   // last block at or before the current one that holds a non-zero
+    float total = 0.f;
+    for (int i0 = 0; i0 < n3; i0 += kWave) {
+        const int i = i0 + lane;
+        const int w = (i < n3 && written[i]) ? i : -1;
+        const int idx = max(wave_incl_scan_max(w), last);
+        if (i < n3) {
+            const double run = basecum[i] + (idx >= 0 ? lds_dcum[idx] : 0.0);
+            l3_64[(size_t)v * (size_t)n3 + (size_t)i] = run;
+            l3[(size_t)v * (size_t)n3pad + (size_t)i] = (float)run;
+            if (i == n3 - 1) total = (float)run;
+        }
+        last = __builtin_amdgcn_readlane(idx, 63);
+    }
+    total = readlane_f32(total, (n3 - 1) & (kWave - 1));
+    for (int i = n3 + lane; i < n3pad; i += kWave) l3[(size_t)v * (size_t)n3pad + i] = total;
+    if (lane == 0) sumphi[v] = total;
+}
+
+// Dense image of light words' rows for export: out[i][k] = base[k] (Bhat) or 0 (counts), then the non-zeros.
+__global__ void light_rows_export_kernel(const int32_t *light_ids, int m, const uint2 *wrec, const uint32_t *lw_ent,
+                                         const float *lw_phi, const float *base, int K, uint32_t topic_bits,
+                                         float *out_phi, int32_t *out_cnt) {
+    const int i = blockIdx.x;
+    if (i >= m) return;
+    const uint2 wr = wrec[light_ids[i]];
+    const uint32_t tmask = (1u << topic_bits) - 1u;
+    for (int k = threadIdx.x; k < K; k += blockDim.x) {
+        if (out_phi) out_phi[(size_t)i * (size_t)K + k] = base[k];
+        if (out_cnt) out_cnt[(size_t)i * (size_t)K + k] = 0;
+    }
+    __syncthreads();
+    for (int j = threadIdx.x; j < (int)wr.y; j += blockDim.x) {
+        const uint32_t e = lw_ent[(size_t)wr.x * 32u + j];
+        if (out_phi) out_phi[(size_t)i * (size_t)K + (e & tmask)] = lw_phi[(size_t)wr.x * 32u + j];
+        if (out_cnt) out_cnt[(size_t)i * (size_t)K + (e & tmask)] = (int32_t)(e >> topic_bits);
+    }
+}
+
 // Statistics for the bandwidth model (exact in binary64 below 2^53): nnz(A), sum_d K_d * L_d (row entries
 // touched if every token read its row) and sum_d K_d * U_d, U_d = distinct words of document d inside its
 // chunk (row entries the sampler has to fetch: consecutive tokens of one (word, document) pair share the row).
@@ -692,6 +818,14 @@ __global__ void row_stats_kernel(const uint2 *docrec, const int64_t *doc_ptr, co
         for (int w = 0; w < nwaves; w++) sum += part[threadIdx.x][w];
         atomicAdd(&out3[threadIdx.x], (unsigned long long)sum);
     }
+}
+
+// Non-zeros of the sparse rows of B (what the next E-step stages for the light words), added to *out.
+__global__ void light_stats_kernel(const uint2 *wrec, int n, unsigned long long *out) {
+    uint32_t nnz = 0;
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) nnz += wrec[i].y;
+    nnz = wave_sum(nnz);
+    if (lane_id() == 0 && nnz) atomicAdd(out, (unsigned long long)nnz);
 }
 
 // Plain streaming copy (16 bytes per lane per step): the yardstick for achievable HBM bandwidth and the

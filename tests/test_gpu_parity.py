@@ -92,6 +92,11 @@ def test_init_state_matches_oracle():
     assert st["nnz_cd"] == o.cd[0][-1] and st["tokens"] == c.T
     lens = np.diff(c.doc_ptr)
     assert st["next_row_entries"] == int((np.diff(o.cd[0]) * lens).sum())
+    # words with fewer than K/2 tokens keep their row of B sparse
+    n_v = np.bincount(c.word_ids, minlength=c.spec.V)
+    light = n_v < 50 // 2
+    assert st["light_tokens"] == int(n_v[light].sum()) and st["light_words_present"] == int((n_v[light] > 0).sum())
+    assert st["next_light_entries"] == int(np.count_nonzero(o.cwk[light]))
 
 
 def test_philox_seed_and_64bit_seed():
@@ -110,6 +115,10 @@ def test_philox_seed_and_64bit_seed():
     (1000, {"stage_phi": 0}),                    # Bhat gathered from global memory instead of LDS
     (5000, {"block_threads": 512}),              # three tree levels (K > 4096)
     (5000, {"block_threads": 64, "tile_tokens": 64}),
+    (1000, {"light_word_tokens": -1}),           # every word keeps a dense row of B
+    (1000, {"light_word_tokens": 1 << 20}),      # every word keeps a sparse row of B
+    (1000, {"light_word_tokens": 40, "n_chunks": 3, "tile_tokens": 16, "long_doc_tokens": 16, "dz_lds_entries": 8}),
+    (130, {"light_word_tokens": 1 << 20}),
 ])
 def test_one_estep_from_random_state(K, opts):
     c = corpusgen.tiny(30 + K % 7, 400, 900, 25, 70.0)
@@ -201,7 +210,8 @@ def test_results_do_not_depend_on_layout_options():
     ref = None
     for opts in [{}, {"n_chunks": 4}, {"tile_tokens": 64, "block_threads": 128}, {"stage_phi": 0},
                  {"long_doc_tokens": 16, "dz_lds_entries": 8}, {"stage_min_tokens": 65, "light_block_threads": 128},
-                 {"stage_min_tokens": 100000}]:
+                 {"stage_min_tokens": 100000}, {"light_word_tokens": -1}, {"light_word_tokens": 1 << 20},
+                 {"light_word_tokens": 30, "n_chunks": 2}]:
         g = pk.Saber(c.doc_ptr, c.word_ids, c.spec.V, 300, 0.2, 0.01, 77, **opts)
         g.iterate(3)
         z = g.get_z()
