@@ -92,6 +92,7 @@ struct saber_ctx {
     float *phi = nullptr, *l3 = nullptr, *sumphi = nullptr;
     double *l3_64 = nullptr;          // [V][n3]
     uint32_t *doc_words = nullptr;    // [D] distinct words of the document
+    unsigned long long *dense_slots = nullptr; // [kMaxTimedIters][kDenseSlots] dense-branch tokens, spread over slots
     unsigned long long *counters = nullptr; // [kMaxTimedIters][kCtr]: dense-branch tokens, nnz(A), sum K_d L_d, sum K_d U_d,
                                             // non-zeros of the sparse rows of B
     double *ll_partial = nullptr;     // [max tiles per chunk]
@@ -130,7 +131,7 @@ extern "C" void saber_free(saber_ctx *c) {
     dev_free(c->z); dev_free(c->tok_doc); dev_free(c->tok_t); dev_free(c->tiles); dev_free(c->docrec);
     dev_free(c->cd_ent); dev_free(c->doc_ptr); dev_free(c->short_docs); dev_free(c->long_docs); dev_free(c->cwk);
     dev_free(c->ck); dev_free(c->denom); dev_free(c->phi); dev_free(c->l3_64); dev_free(c->l3); dev_free(c->sumphi); dev_free(c->doc_words);
-    dev_free(c->counters); dev_free(c->ll_partial);
+    dev_free(c->counters); dev_free(c->dense_slots); dev_free(c->ll_partial);
     dev_free(c->row_word); dev_free(c->light_words); dev_free(c->light_short); dev_free(c->light_long);
     dev_free(c->light_tok_ptr); dev_free(c->wrec); dev_free(c->lw_ent); dev_free(c->lw_phi); dev_free(c->z_wm);
     if (c->have_events) for (auto &e : c->ev) if (e) (void)hipEventDestroy(e);
@@ -514,6 +515,7 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     SABER_TRY(dev_alloc(&c->doc_words, (size_t)D));
     SABER_TRY(dev_alloc(&c->l3, ((size_t)V + 1) * (size_t)c->n3pad)); SABER_TRY(dev_alloc(&c->sumphi, (size_t)V + 1));
     SABER_TRY(dev_alloc(&c->counters, (size_t)kMaxTimedIters * kCtr));
+    SABER_TRY(dev_alloc(&c->dense_slots, (size_t)kMaxTimedIters * kDenseSlots));
     SABER_TRY(dev_alloc(&c->ll_partial, (size_t)std::max<int64_t>(c->max_chunk_tiles, 1)));
     if (T) {
         HIP_TRY(hipMemcpy(c->tok_doc, h_tok_doc.data(), sizeof(int32_t) * (size_t)T, hipMemcpyHostToDevice));
@@ -661,6 +663,9 @@ extern "C" int saber_iterate(saber_ctx *c, int32_t n) {
         hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, c->stream, (uint32_t *)c->counters, 0u,
                            (size_t)kMaxTimedIters * kCtr * 2);
         HIP_TRY(hipGetLastError());
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for((int64_t)batch * kDenseSlots * 2, 256)), dim3(256), 0, c->stream,
+                           (uint32_t *)c->dense_slots, 0u, (size_t)batch * kDenseSlots * 2);
+        HIP_TRY(hipGetLastError());
         for (int b = 0; b < batch; b++) {
             hipEvent_t *ev = c->ev + (size_t)b * EV_PER_ITER;
             c->iter++;
@@ -668,7 +673,7 @@ extern "C" int saber_iterate(saber_ctx *c, int32_t n) {
             // E-step: z <- Sample(A_d, Bhat_v, Q_v, T_v) for every token; B accumulates as a by-product
             for (const Chunk &ch : c->chunks) {
                 EStepParams p = make_params(c, ch);
-                p.n_dense = c->counters + kCtr * b;
+                p.n_dense = c->dense_slots + (size_t)kDenseSlots * b;
                 SABER_TRY(launch_estep<MODE_SAMPLE>(c, ch, p));
             }
             if (prof) HIP_TRY(hipEventRecord(ev[EV_SAMPLE], c->stream));
@@ -680,6 +685,9 @@ extern "C" int saber_iterate(saber_ctx *c, int32_t n) {
             SABER_TRY(launch_phi(c));
             SABER_TRY(launch_light_words(c));
             if (prof) HIP_TRY(hipEventRecord(ev[EV_PHI], c->stream));
+            hipLaunchKernelGGL(sum_slots_kernel, dim3(1), dim3(256), 0, c->stream, c->dense_slots + (size_t)kDenseSlots * b,
+                               kDenseSlots, c->counters + kCtr * b);
+            HIP_TRY(hipGetLastError());
             SABER_TRY(launch_row_stats(c, c->counters + kCtr * b + 1));
         }
         HIP_TRY(hipStreamSynchronize(c->stream));

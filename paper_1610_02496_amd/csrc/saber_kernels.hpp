@@ -180,7 +180,8 @@ struct EStepParams {
     float *out_S;               // probs mode: S per canonical token
     float *out_Q;               // probs mode: Q per canonical token
     double *out_ll;             // loglik mode: one partial sum per tile
-    unsigned long long *n_dense;// sample mode: dense-branch token counter
+    unsigned long long *n_dense;// sample mode: kDenseSlots dense-branch token counters (workgroup b adds to slot b mod
+                                // kDenseSlots: one hot address would serialise the atomics of the whole launch)
     int64_t t_base;             // canonical index of the chunk's first token
     int32_t K, Kpad, n3, n3pad;
     uint32_t topic_bits, topic_mask;
@@ -189,6 +190,7 @@ struct EStepParams {
 };
 
 enum { MODE_SAMPLE = 0, MODE_PROBS = 1, MODE_LOGLIK = 2 };
+constexpr int kDenseSlots = 1024;
 
 // Sums and scans inside one DPP row (16 lanes): the dense branch serves four tokens at a time, one per row.
 __device__ __forceinline__ uint32_t row16_allsum(uint32_t v) {
@@ -309,6 +311,7 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
     extern __shared__ float4 lds_f4[];
     __shared__ double ll_wave[MODE == MODE_LOGLIK ? 16 : 1];
     __shared__ int next_batch;   // batches of a tile are handed out to wavefronts as they become free
+    __shared__ unsigned int wg_dense;   // dense-branch tokens of this workgroup
     // LDS (STAGED): [K rounded to 4] floats: the word's Bhat row; [n3] floats: the tree level above the bottom;
     // LHIST adds [Kpad] counters: the tile's histogram of new assignments (small K only).
     // The footprint is kept minimal because it decides how many wavefronts a CU can hold: at K = 10,000 it is
@@ -322,7 +325,7 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
     const float *__restrict__ phi_row = LIGHT ? p.base : p.phi + (size_t)tile.row * (size_t)p.Kpad;
     const float *__restrict__ l3_row = p.l3 + (size_t)tile.word * (size_t)p.n3pad;
     const double *__restrict__ l3_64_row = p.l3_64 + (size_t)tile.word * (size_t)p.n3;
-    if (threadIdx.x == 0) next_batch = 0;
+    if (threadIdx.x == 0) { next_batch = 0; wg_dense = 0u; }
     if (STAGED) {
         const float4 *src = reinterpret_cast<const float4 *>(phi_row);
         float4 *dst = reinterpret_cast<float4 *>(lds_phi);
@@ -358,7 +361,7 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
         if (lane == 0) ticket = atomicAdd(&next_batch, 1);
         const int batch = __builtin_amdgcn_readfirstlane(ticket) * bs;   // wave-uniform: loop control stays scalar
         if (batch >= tile.count) break;
-        const int n = min(bs, tile.count - batch);
+        const int n = __builtin_amdgcn_readfirstlane(min(bs, tile.count - batch));   // wave-uniform by construction
         const bool act = lane < n;
         const int i = tile.begin + batch + lane;
         const int d = act ? p.tok_doc[i] : -1;
@@ -374,49 +377,78 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
         unsigned long long dense_mask = 0ull;
         int s = 0;
 
+        // Runs: tokens are ordered by (word, document), so the tokens of one document are neighbours.  Bit i of
+        // `rest` marks a lane i > s where a new document starts.
+        const int d_prev = __builtin_amdgcn_update_dpp(-2, d, 0x138, 0xf, 0xf, false);   // wave_shr:1
+        unsigned long long rest = __builtin_amdgcn_ballot_w64(act && d != d_prev) & ~1ull;
+
         // One run [s, s_end) of tokens of this word in one document: they share A_d (.) Bhat_v and S.
-        // `cur` holds the first block of the run's row (fetched during the previous run); the first block of
-        // the next run's row is fetched into `nxt` before this run's arithmetic starts.
-        auto do_run = [&](const uint4 &cur, uint4 &nxt) {
-            const int ds = __builtin_amdgcn_readlane(d, s);
-            const unsigned long long other = __builtin_amdgcn_ballot_w64(d != ds) & (~0ull << s);
-            int s_end = other ? (int)__builtin_ctzll(other) : kWave;
-            s_end = __builtin_amdgcn_readfirstlane(s_end < n ? s_end : n);   // wave-uniform by construction
-            const int kd = (int)readlane_u32(rec.y, s);
-            const uint32_t *row = p.cd_ent + (size_t)readlane_u32(rec.x, s) * 32u;
-            const int nblk = (kd + 4 * kWave - 1) / (4 * kWave);
-            uint4 e1 = make_uint4(0u, 0u, 0u, 0u);
-            if (nblk > 1) e1 = load_block(row + 4 * kWave, kd - 4 * kWave, lane);
-            if (s_end < n)
-                nxt = load_block(p.cd_ent + (size_t)readlane_u32(rec.x, s_end) * 32u, (int)readlane_u32(rec.y, s_end), lane);
+        // `cur` holds the first block of the run's row (fetched during the previous run), kd its length and ru
+        // its position; the first block of the next run's row is fetched into `nxt` before this run's
+        // arithmetic starts.
+        auto do_run = [&](const uint4 &cur, const int kd, const uint32_t ru, uint4 &nxt, int &kd_nxt, uint32_t &ru_nxt) {
+            const int s_end = rest ? (int)__builtin_ctzll(rest) : n;
+            rest &= rest - 1ull;
+            if (s_end < n) {
+                kd_nxt = (int)readlane_u32(rec.y, s_end); ru_nxt = readlane_u32(rec.x, s_end);
+                nxt = load_block(p.cd_ent + (size_t)ru_nxt * 32u, kd_nxt, lane);
+            }
+            const unsigned long long in_run = (~0ull << s) & (s_end < kWave ? ~(~0ull << s_end) : ~0ull);
             // element-wise product A_d (.) Bhat_v, its prefix sums and its sum S (Alg. 2, product loop)
-            RowBlock b0, b1 = {0.f, 0.f, 0.f, 0.f, 0.f};
+            RowBlock b0;
             block_products<STAGED>(cur, bits, tmask, lds_phi, phi_row, b0);
             const float t0 = readlane_f32(b0.incl, 63);
-            float t1 = 0.f, S = t0;
-            if (nblk > 1) {
-                block_products<STAGED>(e1, bits, tmask, lds_phi, phi_row, b1);
-                t1 = readlane_f32(b1.incl, 63);
-                S = S + t1;
-                for (int blk = 2; blk < nblk; blk++) {
-                    RowBlock bb;
-                    block_products<STAGED>(load_block(row + blk * 4 * kWave, kd - blk * 4 * kWave, lane), bits, tmask,
-                                           lds_phi, phi_row, bb);
-                    S = S + readlane_f32(bb.incl, 63);
+            if (kd <= 4 * kWave) {
+                // the whole row sits in this block (the common case): straight-line coin and search
+                if (MODE == MODE_SAMPLE) {
+                    unsigned long long sparse = __builtin_amdgcn_ballot_w64(u0 * (t0 + Q) < t0) & in_run;
+                    dense_mask |= in_run & ~sparse;       // problem 2 is served after the runs, four tokens at a time
+                    const float xs = u1 * t0;
+                    const float base = b0.incl - b0.a3;
+                    const float p0 = base + b0.a0, p1 = base + b0.a1, p2 = base + b0.a2;
+                    const int last_lane = (kd - 1) >> 2;
+                    while (sparse) {
+                        // problem 1: position of x in the prefix sums of P
+                        const int r = (int)__builtin_ctzll(sparse);
+                        sparse &= sparse - 1ull;
+                        const float x = readlane_f32(xs, r);
+                        const unsigned long long m3 = __builtin_amdgcn_ballot_w64(b0.incl >= x);
+                        const int L = m3 ? (int)__builtin_ctzll(m3) : last_lane;
+                        uint32_t sel = cur.w;
+                        sel = p2 >= x ? cur.z : sel;
+                        sel = p1 >= x ? cur.y : sel;
+                        sel = p0 >= x ? cur.x : sel;
+                        my_z = llvm_amdgcn_writelane_u32(readlane_u32(sel, L) & tmask, (unsigned)r, my_z);
+                    }
+                } else {
+                    if (lane >= s && lane < s_end) my_S = t0;
                 }
+                s = s_end;
+                return;
+            }
+            const uint32_t *row = p.cd_ent + (size_t)ru * 32u;
+            const int nblk = (kd + 4 * kWave - 1) / (4 * kWave);
+            const uint4 e1 = load_block(row + 4 * kWave, kd - 4 * kWave, lane);
+            RowBlock b1;
+            block_products<STAGED>(e1, bits, tmask, lds_phi, phi_row, b1);
+            const float t1 = readlane_f32(b1.incl, 63);
+            float S = t0 + t1;
+            for (int blk = 2; blk < nblk; blk++) {
+                RowBlock bb;
+                block_products<STAGED>(load_block(row + blk * 4 * kWave, kd - blk * 4 * kWave, lane), bits, tmask,
+                                       lds_phi, phi_row, bb);
+                S = S + readlane_f32(bb.incl, 63);
             }
             if (MODE == MODE_SAMPLE) {
                 // every lane evaluates the coin and the position for its own token; lanes of this run are used
                 const unsigned long long sparse = __builtin_amdgcn_ballot_w64(u0 * (S + Q) < S);
                 const float xs = u1 * S;
-                const unsigned long long in_run = (~0ull << s) & (s_end < kWave ? ~(~0ull << s_end) : ~0ull);
-                dense_mask |= ~sparse & in_run;           // problem 2 is served after the runs, four tokens at a time
+                dense_mask |= ~sparse & in_run;
                 for (int r = s; r < s_end; r++) {
                     uint32_t topic;
                     if ((sparse >> r) & 1ull) {
-                        // problem 1: position of x in the prefix sums of P
                         const float x = readlane_f32(xs, r);
-                        if (nblk == 1 || t0 >= x) topic = search_block(cur, b0, 0.f, x, kd, tmask);
+                        if (t0 >= x) topic = search_block(cur, b0, 0.f, x, kd, tmask);
                         else if (nblk == 2 || t0 + t1 >= x) topic = search_block(e1, b1, t0, x, kd - 4 * kWave, tmask);
                         else {
                             float carry = t0 + t1;
@@ -440,12 +472,14 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
             s = s_end;
         };
 
-        uint4 blk_a = load_block(p.cd_ent + (size_t)readlane_u32(rec.x, 0) * 32u, (int)readlane_u32(rec.y, 0), lane);
+        int kd_a = (int)readlane_u32(rec.y, 0), kd_b = 0;
+        uint32_t ru_a = readlane_u32(rec.x, 0), ru_b = 0u;
+        uint4 blk_a = load_block(p.cd_ent + (size_t)ru_a * 32u, kd_a, lane);
         uint4 blk_b = make_uint4(0u, 0u, 0u, 0u);
         while (s < n) {
-            do_run(blk_a, blk_b);
+            do_run(blk_a, kd_a, ru_a, blk_b, kd_b, ru_b);
             if (s >= n) break;
-            do_run(blk_b, blk_a);
+            do_run(blk_b, kd_b, ru_b, blk_a, kd_a, ru_a);
         }
 
         if (MODE == MODE_SAMPLE && dense_mask) {
@@ -486,7 +520,9 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
     }
 
     if (MODE == MODE_SAMPLE) {
-        if (lane == 0 && dense_count) atomicAdd(p.n_dense, (unsigned long long)dense_count);
+        if (lane == 0 && dense_count) atomicAdd(&wg_dense, dense_count);
+        __syncthreads();
+        if (threadIdx.x == 0 && wg_dense) atomicAdd(p.n_dense + (blockIdx.x & (kDenseSlots - 1)), (unsigned long long)wg_dense);
         if (LHIST) {
             // the tile's counts go to B in one pass: at most K atomics per tile instead of one per token
             __syncthreads();
@@ -818,6 +854,18 @@ __global__ void row_stats_kernel(const uint2 *docrec, const int64_t *doc_ptr, co
         for (int w = 0; w < nwaves; w++) sum += part[threadIdx.x][w];
         atomicAdd(&out3[threadIdx.x], (unsigned long long)sum);
     }
+}
+
+// Sum of the dense-branch counter slots, added to *out.
+__global__ void sum_slots_kernel(const unsigned long long *slots, int n, unsigned long long *out) {
+    unsigned long long v = 0;
+    for (int i = threadIdx.x; i < n; i += blockDim.x) v += slots[i];
+    __shared__ unsigned long long tot;
+    if (threadIdx.x == 0) tot = 0ull;
+    __syncthreads();
+    if (v) atomicAdd(&tot, v);
+    __syncthreads();
+    if (threadIdx.x == 0 && tot) atomicAdd(out, tot);
 }
 
 // Non-zeros of the sparse rows of B (what the next E-step stages for the light words), added to *out.
