@@ -32,9 +32,8 @@ def log(*a):
 def algorithmic_bytes(st, K, z_bytes):
     """HBM bytes the sampling kernel must move for the iterations counted in ``st`` (model stated in the design doc).
 
-    per token : 4 (document id) + 4 (token index) + 8 (row descriptor) + z_bytes (assignment written)
-                + 4 (one count added to the dense row of B) or, for a token of a light word, z_bytes (its
-                assignment written a second time, in word-major order, for that word's CountByVZ)
+    per token : 4 (document id) + 4 (token index) + 8 (row descriptor) + 2 * z_bytes (the assignment, written in
+                canonical order and again in word-major order for CountByVZ)
     per run of consecutive tokens of one (word, document) pair : 4*K_d (the packed row of A, fetched once)
     per (word, chunk) with tokens : the tree level above the bottom and the block bases, 4*n3pad + 8*n3, the
                 row total, 4, and the Bhat row: 4*Kpad for a dense row, or 8 (descriptor) + 8 per non-zero of
@@ -46,9 +45,7 @@ def algorithmic_bytes(st, K, z_bytes):
     n3 = kpad // 64
     n3pad = (n3 + 63) // 64 * 64
     it = st["iterations"]
-    light_share = st["light_tokens"] / max(1, st["tokens"])
-    tok = st["sum_tokens"] * (4 + 4 + 8 + z_bytes + 4 * (1.0 - light_share) + z_bytes * light_share)
-    tok += 4 * st["sum_row_fetch"]
+    tok = st["sum_tokens"] * (4 + 4 + 8 + 2 * z_bytes) + 4 * st["sum_row_fetch"]
     tree = 4 * n3pad + 8 * n3 + 4
     dense_rows = st["words_present"] - st["light_words_present"]
     stage = it * (dense_rows * (4 * kpad + tree) + st["light_words_present"] * (8 + tree))

@@ -56,7 +56,7 @@ struct saber_ctx {
     float alpha = 0, beta = 0, vbeta = 0;
     uint64_t seed = 0;
     uint32_t iter = 0, topic_bits = 0, topic_mask = 0;
-    bool z16 = false, staged = false, b16 = false, lds_hist = false;
+    bool z16 = false, staged = false, b16 = false;
     saber_options opt{};
     double ll_const = 0.0;            // sum_d L_d ln(L_d + K alpha)
     int64_t max_doc_len = 0;
@@ -83,8 +83,10 @@ struct saber_ctx {
     uint2 *wrec = nullptr;            // [V_light] {row start / 32, non-zeros}
     uint32_t *lw_ent = nullptr;       // packed rows of B of the light words
     float *lw_phi = nullptr;          // Bhat of each such entry
-    void *z_wm = nullptr;             // [T_light] word-major assignments of the light words' tokens
+    void *z_wm = nullptr;             // [T] word-major assignments: the light words' tokens first, then the dense rows' ones
     int64_t T_light = 0, lw_cap = 0;
+    VzItem *vz_items = nullptr;       // slabs of the dense-row words' segments of z_wm
+    int64_t n_vz_items = 0;
     std::vector<int32_t> h_word_row;  // host: word -> dense row (>= 0) or -(light row) - 1
     int32_t *cwk = nullptr;           // [V_dense+1][Kpad]
     unsigned long long *ck = nullptr; // [K] topic totals
@@ -133,7 +135,7 @@ extern "C" void saber_free(saber_ctx *c) {
     dev_free(c->ck); dev_free(c->denom); dev_free(c->phi); dev_free(c->l3_64); dev_free(c->l3); dev_free(c->sumphi); dev_free(c->doc_words);
     dev_free(c->counters); dev_free(c->dense_slots); dev_free(c->ll_partial);
     dev_free(c->row_word); dev_free(c->light_words); dev_free(c->light_short); dev_free(c->light_long);
-    dev_free(c->light_tok_ptr); dev_free(c->wrec); dev_free(c->lw_ent); dev_free(c->lw_phi); dev_free(c->z_wm);
+    dev_free(c->light_tok_ptr); dev_free(c->wrec); dev_free(c->lw_ent); dev_free(c->lw_phi); dev_free(c->z_wm); dev_free(c->vz_items);
     if (c->have_events) for (auto &e : c->ev) if (e) (void)hipEventDestroy(e);
     if (c->stream) (void)hipStreamDestroy(c->stream);
     delete c;
@@ -148,7 +150,7 @@ static EStepParams make_params(saber_ctx *c, const Chunk &ch) {
     p.tok_doc = c->tok_doc + ch.t0; p.tok_t = c->tok_t + ch.t0;
     p.docrec = c->docrec; p.cd_ent = c->cd_ent;
     p.phi = c->phi; p.l3 = c->l3; p.l3_64 = c->l3_64; p.sumphi = c->sumphi;
-    p.z = c->z; p.cwk = c->cwk;
+    p.z = c->z;
     p.base = c->phi + (size_t)c->V_dense * (size_t)c->Kpad;
     p.wrec = c->wrec; p.lw_ent = c->lw_ent; p.lw_phi = c->lw_phi; p.z_wm = c->z_wm;
     p.t_base = ch.t0; p.K = c->K; p.Kpad = c->Kpad; p.n3 = c->n3; p.n3pad = c->n3pad;
@@ -157,27 +159,20 @@ static EStepParams make_params(saber_ctx *c, const Chunk &ch) {
     return p;
 }
 
-// dynamic LDS of a staged sampling workgroup: the Bhat row (K rounded to 4 floats) and the tree level (n3 floats);
-// the optional per-tile histogram of new assignments adds Kpad counters
-static size_t estep_lds_bytes(const saber_ctx *c, bool lhist) {
-    const size_t row = (size_t)((c->K + 3) & ~3) + (size_t)((c->n3 + 3) & ~3);
-    return (row + (lhist ? (size_t)c->Kpad : 0)) * sizeof(float);
+// dynamic LDS of a staged sampling workgroup: the Bhat row (K rounded to 4 floats) and the tree level (n3 floats)
+static size_t estep_lds_bytes(const saber_ctx *c) {
+    return ((size_t)((c->K + 3) & ~3) + (size_t)((c->n3 + 3) & ~3)) * sizeof(float);
 }
 
 template <int MODE, bool STAGED, typename ZT>
-static void launch_estep_b16(saber_ctx *c, dim3 grid, dim3 block, size_t lds, const EStepParams &p, bool lhist, bool light) {
+static void launch_estep_b16(saber_ctx *c, dim3 grid, dim3 block, size_t lds, const EStepParams &p, bool light) {
     if (light) {   // light words exist only in the staged, 16-bit-z configuration
-        if (c->b16) hipLaunchKernelGGL((estep_kernel<MODE, true, uint16_t, true, false, true>), grid, block, lds, c->stream, p);
-        else hipLaunchKernelGGL((estep_kernel<MODE, true, uint16_t, false, false, true>), grid, block, lds, c->stream, p);
+        if (c->b16) hipLaunchKernelGGL((estep_kernel<MODE, true, uint16_t, true, true>), grid, block, lds, c->stream, p);
+        else hipLaunchKernelGGL((estep_kernel<MODE, true, uint16_t, false, true>), grid, block, lds, c->stream, p);
         return;
     }
-    if (lhist) {
-        if (c->b16) hipLaunchKernelGGL((estep_kernel<MODE_SAMPLE, true, uint16_t, true, true, false>), grid, block, lds, c->stream, p);
-        else hipLaunchKernelGGL((estep_kernel<MODE_SAMPLE, true, uint16_t, false, true, false>), grid, block, lds, c->stream, p);
-        return;
-    }
-    if (c->b16) hipLaunchKernelGGL((estep_kernel<MODE, STAGED, ZT, true, false, false>), grid, block, lds, c->stream, p);
-    else hipLaunchKernelGGL((estep_kernel<MODE, STAGED, ZT, false, false, false>), grid, block, lds, c->stream, p);
+    if (c->b16) hipLaunchKernelGGL((estep_kernel<MODE, STAGED, ZT, true, false>), grid, block, lds, c->stream, p);
+    else hipLaunchKernelGGL((estep_kernel<MODE, STAGED, ZT, false, false>), grid, block, lds, c->stream, p);
 }
 
 // One E-step launch per tile class.  Dense-row tiles with at least stage_min_tokens tokens run with block_threads
@@ -198,15 +193,13 @@ static int launch_estep(saber_ctx *c, const Chunk &ch, EStepParams &p0) {
         p.tiles = p0.tiles + cl.first;
         if (p0.out_ll) p.out_ll = p0.out_ll + cl.first;
         const dim3 grid((unsigned)cl.count), block((unsigned)cl.block);
-        // small K: accumulate the tile's new assignments in an LDS histogram instead of one global atomic per token
-        const bool lhist = MODE == MODE_SAMPLE && c->staged && c->z16 && c->lds_hist && !cl.light;
-        const size_t lds = c->staged ? estep_lds_bytes(c, lhist) : 0;
+        const size_t lds = c->staged ? estep_lds_bytes(c) : 0;
         if (c->staged) {
-            if (c->z16) launch_estep_b16<MODE, true, uint16_t>(c, grid, block, lds, p, lhist, cl.light);
-            else launch_estep_b16<MODE, true, int32_t>(c, grid, block, lds, p, false, false);
+            if (c->z16) launch_estep_b16<MODE, true, uint16_t>(c, grid, block, lds, p, cl.light);
+            else launch_estep_b16<MODE, true, int32_t>(c, grid, block, lds, p, false);
         } else {
-            if (c->z16) launch_estep_b16<MODE, false, uint16_t>(c, grid, block, lds, p, false, false);
-            else launch_estep_b16<MODE, false, int32_t>(c, grid, block, lds, p, false, false);
+            if (c->z16) launch_estep_b16<MODE, false, uint16_t>(c, grid, block, lds, p, false);
+            else launch_estep_b16<MODE, false, int32_t>(c, grid, block, lds, p, false);
         }
         HIP_TRY(hipGetLastError());
     }
@@ -307,33 +300,43 @@ static int launch_phi(saber_ctx *c) {
     return SABER_OK;
 }
 
-// B from scratch out of z (after init / set_z): dense rows by atomics (they must be all zero on entry, which
-// the Bhat kernel leaves them), light words get their word-major copy of z.
-static int launch_count_vz(saber_ctx *c, bool dense_rows, bool light_copy) {
+// Word-major copy of z (after init / set_z; an E-step writes it itself).
+static int launch_fill_zwm(saber_ctx *c) {
     for (const Chunk &ch : c->chunks) {
-        if (dense_rows && ch.n_dense > 0) {
-            if (c->z16)
-                hipLaunchKernelGGL((count_vz_kernel<uint16_t>), dim3((unsigned)ch.n_dense), dim3(256), 0, c->stream,
-                                   c->tiles + ch.tile0, c->tok_t + ch.t0, (const uint16_t *)c->z, ch.t0, c->cwk, c->Kpad);
-            else
-                hipLaunchKernelGGL((count_vz_kernel<int32_t>), dim3((unsigned)ch.n_dense), dim3(256), 0, c->stream,
-                                   c->tiles + ch.tile0, c->tok_t + ch.t0, (const int32_t *)c->z, ch.t0, c->cwk, c->Kpad);
-            HIP_TRY(hipGetLastError());
-        }
-        if (light_copy && ch.ntiles > ch.n_dense) {
-            hipLaunchKernelGGL((fill_zwm_kernel<uint16_t>), dim3((unsigned)(ch.ntiles - ch.n_dense)), dim3(256), 0, c->stream,
-                               c->tiles + ch.tile0 + ch.n_dense, c->tok_t + ch.t0, (const uint16_t *)c->z, ch.t0,
-                               (uint16_t *)c->z_wm);
-            HIP_TRY(hipGetLastError());
-        }
+        if (ch.ntiles == 0) continue;
+        if (c->z16)
+            hipLaunchKernelGGL((fill_zwm_kernel<uint16_t>), dim3((unsigned)ch.ntiles), dim3(256), 0, c->stream,
+                               c->tiles + ch.tile0, c->tok_t + ch.t0, (const uint16_t *)c->z, ch.t0, (uint16_t *)c->z_wm);
+        else
+            hipLaunchKernelGGL((fill_zwm_kernel<int32_t>), dim3((unsigned)ch.ntiles), dim3(256), 0, c->stream,
+                               c->tiles + ch.tile0, c->tok_t + ch.t0, (const int32_t *)c->z, ch.t0, (int32_t *)c->z_wm);
+        HIP_TRY(hipGetLastError());
     }
+    return SABER_OK;
+}
+
+// CountByVZ for the dense rows of B out of the word-major assignments; the rows must be all zero on entry
+// (the Bhat kernel leaves them so).
+static int launch_count_vz(saber_ctx *c) {
+    if (c->n_vz_items == 0) return SABER_OK;
+    const int use_lds = (size_t)c->K * 4 <= 60 * 1024;
+    const size_t lds = use_lds ? (size_t)c->K * 4 : 0;
+    const dim3 grid((unsigned)c->n_vz_items), block(use_lds ? 1024u : 256u);
+    if (c->z16)
+        hipLaunchKernelGGL((count_vz_kernel<uint16_t>), grid, block, lds, c->stream, c->vz_items, (const uint16_t *)c->z_wm,
+                           c->cwk, c->K, c->Kpad, use_lds);
+    else
+        hipLaunchKernelGGL((count_vz_kernel<int32_t>), grid, block, lds, c->stream, c->vz_items, (const int32_t *)c->z_wm,
+                           c->cwk, c->K, c->Kpad, use_lds);
+    HIP_TRY(hipGetLastError());
     return SABER_OK;
 }
 
 // The M-step after the assignments changed outside an E-step: all four rebuilds of Alg. 1.
 static int full_mstep(saber_ctx *c) {
     SABER_TRY(launch_count_dz(c));
-    SABER_TRY(launch_count_vz(c, true, true));
+    SABER_TRY(launch_fill_zwm(c));
+    SABER_TRY(launch_count_vz(c));
     SABER_TRY(launch_topic_totals(c));
     SABER_TRY(launch_phi(c));
     SABER_TRY(launch_light_words(c));
@@ -417,7 +420,23 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
         c->n_light_short = (int64_t)h_light_short.size(); c->n_light_long = (int64_t)h_light_long.size();
     }
     // ---- word-major token arrays and tiles per chunk (host counting sort; layout only) ----
-    std::vector<int64_t> light_seen((size_t)c->V_light, 0);   // tokens of each light word placed so far (chunk by chunk)
+    // position of every word's segment in the word-major order (light words first, then dense rows) and the
+    // slabs CountByVZ cuts the dense rows' segments into
+    std::vector<int64_t> wm_ptr((size_t)V, 0), wm_seen((size_t)V, 0);   // wm_seen: tokens placed so far (chunk by chunk)
+    std::vector<VzItem> h_vz_items;
+    {
+        for (int32_t li = 0; li < c->V_light; li++) wm_ptr[(size_t)h_light_words[(size_t)li]] = h_light_tok_ptr[(size_t)li];
+        int64_t pos = c->T_light;
+        const int64_t slab = 32768;
+        for (int32_t r = 0; r < c->V_dense; r++) {
+            const int32_t v = h_row_word[(size_t)r];
+            wm_ptr[(size_t)v] = pos;
+            for (int64_t s = 0; s < n_v[(size_t)v]; s += slab)
+                h_vz_items.push_back(VzItem{r, (int32_t)std::min<int64_t>(slab, n_v[(size_t)v] - s), pos + s});
+            pos += n_v[(size_t)v];
+        }
+        c->n_vz_items = (int64_t)h_vz_items.size();
+    }
     std::vector<int32_t> h_tok_doc((size_t)std::max<int64_t>(T, 1));
     std::vector<uint32_t> h_tok_t((size_t)std::max<int64_t>(T, 1));
     std::vector<Tile> h_tiles;
@@ -434,12 +453,8 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
             if (e > b) { ch.words_present++; if (row < 0) c->stats.light_words_present++; }
             for (int64_t s = b; s < e; s += tile_tokens) {
                 const int32_t cnt = (int32_t)std::min<int64_t>(tile_tokens, e - s);
-                Tile tl{v, (int32_t)s, cnt, row >= 0 ? row : -row - 1, 0, 0};
-                if (row < 0) {
-                    tl.wm_begin = h_light_tok_ptr[(size_t)(-row - 1)] + light_seen[(size_t)(-row - 1)];
-                    light_seen[(size_t)(-row - 1)] += cnt;
-                }
-                h_tiles.push_back(tl);
+                h_tiles.push_back(Tile{v, (int32_t)s, cnt, row >= 0 ? row : -row - 1, wm_ptr[(size_t)v] + wm_seen[(size_t)v], 0});
+                wm_seen[(size_t)v] += cnt;
             }
         }
         for (int64_t d = ch.d0; d < ch.d1; d++)
@@ -503,7 +518,10 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     SABER_TRY(dev_alloc(&c->light_short, h_light_short.size())); SABER_TRY(dev_alloc(&c->light_long, h_light_long.size()));
     SABER_TRY(dev_alloc(&c->light_tok_ptr, h_light_tok_ptr.size())); SABER_TRY(dev_alloc(&c->wrec, h_wrec.size()));
     SABER_TRY(dev_alloc(&c->lw_ent, (size_t)c->lw_cap)); SABER_TRY(dev_alloc(&c->lw_phi, (size_t)c->lw_cap));
-    SABER_TRY(dev_alloc((uint16_t **)&c->z_wm, (size_t)c->T_light));
+    if (c->z16) SABER_TRY(dev_alloc((uint16_t **)&c->z_wm, (size_t)T)); else SABER_TRY(dev_alloc((int32_t **)&c->z_wm, (size_t)T));
+    SABER_TRY(dev_alloc(&c->vz_items, h_vz_items.size()));
+    if (!h_vz_items.empty())
+        HIP_TRY(hipMemcpy(c->vz_items, h_vz_items.data(), sizeof(VzItem) * h_vz_items.size(), hipMemcpyHostToDevice));
     HIP_TRY(hipMemcpy(c->row_word, h_row_word.data(), sizeof(int32_t) * h_row_word.size(), hipMemcpyHostToDevice));
     HIP_TRY(hipMemcpy(c->light_tok_ptr, h_light_tok_ptr.data(), sizeof(int64_t) * h_light_tok_ptr.size(), hipMemcpyHostToDevice));
     if (c->V_light) {
@@ -616,15 +634,14 @@ extern "C" int saber_init_ex(saber_ctx **out, const int64_t *doc_ptr, const int3
     c->nwords = (K + 31) / 32;
     c->topic_bits = bits; c->topic_mask = (1u << bits) - 1u;
     c->z16 = K <= 65536;
-    c->staged = opt.stage_phi && estep_lds_bytes(c, false) <= 60 * 1024;
-    c->lds_hist = c->staged && K <= 2048;
+    c->staged = opt.stage_phi && estep_lds_bytes(c) <= 60 * 1024;
     if (opt_in == nullptr || opt_in->block_threads <= 0) {
         // automatic workgroup size: the one that lets a CU hold the most wavefronts given the LDS footprint
         // (LDS is handed out in 512-byte pieces; a CU holds at most 32 wavefronts); ties go to the smaller size
         int lds_cu = 0;
         if (hipDeviceGetAttribute(&lds_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, 0) != hipSuccess || lds_cu <= 0)
             lds_cu = 64 * 1024;
-        const size_t need = c->staged ? ((estep_lds_bytes(c, c->lds_hist) + 160 + 511) / 512) * 512 : 512;
+        const size_t need = c->staged ? ((estep_lds_bytes(c) + 160 + 511) / 512) * 512 : 512;
         int best = 256, best_waves = 0;
         for (int block : {256, 512, 1024}) {
             const int by_lds = (int)std::min<size_t>(64, (size_t)lds_cu / need), by_waves = 32 / (block / 64);
@@ -682,6 +699,7 @@ extern "C" int saber_iterate(saber_ctx *c, int32_t n) {
             if (prof) HIP_TRY(hipEventRecord(ev[EV_DZ], c->stream));
             SABER_TRY(launch_topic_totals(c));
             if (prof) HIP_TRY(hipEventRecord(ev[EV_CK], c->stream));
+            SABER_TRY(launch_count_vz(c));
             SABER_TRY(launch_phi(c));
             SABER_TRY(launch_light_words(c));
             if (prof) HIP_TRY(hipEventRecord(ev[EV_PHI], c->stream));
@@ -765,7 +783,7 @@ extern "C" int saber_counts(saber_ctx *c, int64_t *cd_row_ptr, int32_t *cd_topic
         }
         if (cwk) {
             // dense rows: B is consumed (and cleared) by the Bhat kernel; rebuild it from z for export
-            SABER_TRY(launch_count_vz(c, true, false));
+            SABER_TRY(launch_count_vz(c));
             HIP_TRY(hipStreamSynchronize(c->stream));
             const int64_t slab = 2048;   // rows per host staging buffer
             std::vector<int32_t> buf((size_t)slab * (size_t)c->Kpad);

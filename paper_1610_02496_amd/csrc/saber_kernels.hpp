@@ -170,13 +170,12 @@ struct EStepParams {
     const double *l3_64;        // [V][n3]    the same running sums before rounding (base of each bottom block)
     const float *sumphi;        // [V]        prefix sum at topic K-1 = l3[n3-1]
     void *z;                    // [T] assignments, canonical order (uint16 or int32)
-    int32_t *cwk;               // [dense rows][Kpad] accumulator of B for the next M-step
     // light words (few tokens): B is kept sparse, Bhat = base + the word's non-zeros
     const float *base;          // [Kpad] Bhat of a zero count, beta / denom_k (pad columns 0)
     const uint2 *wrec;          // [light words] {row start in units of 32 entries, non-zeros}
     const uint32_t *lw_ent;     // packed (topic, count) rows of B for the light words, ascending topic
     const float *lw_phi;        // Bhat value of every such entry
-    void *z_wm;                 // [T] new assignments in word-major order (input of the light words' CountByVZ)
+    void *z_wm;                 // [T] new assignments in word-major order (light words first): input of CountByVZ
     float *out_S;               // probs mode: S per canonical token
     float *out_Q;               // probs mode: Q per canonical token
     double *out_ll;             // loglik mode: one partial sum per tile
@@ -303,23 +302,22 @@ __device__ __forceinline__ uint32_t search_block(const uint4 e, const RowBlock &
     return readlane_u32(sel, L) & tmask;
 }
 
+// New assignments are written twice: to z (canonical order) and to z_wm (word-major, coalesced), from which the
+// M-step counts B; the sampler itself adds nothing to B.
 // LIGHT: the tile's word keeps B sparse.  Its Bhat row is built in LDS from the base vector and the word's
-// non-zeros, and the new assignments go to z_wm (coalesced) for the word's CountByVZ instead of to the dense
-// accumulator.
-template <int MODE, bool STAGED, typename ZT, bool B16, bool LHIST, bool LIGHT>
+// non-zeros.
+template <int MODE, bool STAGED, typename ZT, bool B16, bool LIGHT>
 __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
     extern __shared__ float4 lds_f4[];
     __shared__ double ll_wave[MODE == MODE_LOGLIK ? 16 : 1];
     __shared__ int next_batch;   // batches of a tile are handed out to wavefronts as they become free
     __shared__ unsigned int wg_dense;   // dense-branch tokens of this workgroup
     // LDS (STAGED): [K rounded to 4] floats: the word's Bhat row; [n3] floats: the tree level above the bottom;
-    // LHIST adds [Kpad] counters: the tile's histogram of new assignments (small K only).
     // The footprint is kept minimal because it decides how many wavefronts a CU can hold: at K = 10,000 it is
     // 40,628 bytes, which lets four 512-thread workgroups (32 wavefronts) share the 160 KB of a CU.
     const int K4 = (p.K + 3) & ~3;
     float *lds_phi = reinterpret_cast<float *>(lds_f4);
     float *lds_l3 = lds_phi + K4;
-    uint32_t *lds_hist = reinterpret_cast<uint32_t *>(lds_l3 + ((p.n3 + 3) & ~3));
     const Tile tile = p.tiles[blockIdx.x];
     const int K = p.K;
     const float *__restrict__ phi_row = LIGHT ? p.base : p.phi + (size_t)tile.row * (size_t)p.Kpad;
@@ -333,8 +331,6 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
         if (MODE == MODE_SAMPLE)
             for (int i = threadIdx.x; i < p.n3; i += blockDim.x) lds_l3[i] = l3_row[i];
     }
-    if (LHIST)
-        for (int i = threadIdx.x; i < p.Kpad; i += blockDim.x) lds_hist[i] = 0u;
     __syncthreads();
     if (LIGHT) {
         // the staged row is the base vector so far; overwrite the topics this word has counts for
@@ -508,9 +504,8 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
             const int64_t tc = p.t_base + (int64_t)t;
             if (MODE == MODE_SAMPLE) {
                 reinterpret_cast<ZT *>(p.z)[tc] = (ZT)my_z;
-                if (LIGHT) reinterpret_cast<ZT *>(p.z_wm)[tile.wm_begin + (int64_t)(i - tile.begin)] = (ZT)my_z;
-                else if (LHIST) atomicAdd(&lds_hist[my_z], 1u);
-                else atomicAdd(&p.cwk[(size_t)tile.row * (size_t)p.Kpad + my_z], 1);
+                // the second copy, in word-major order, is what CountByVZ reads (coalesced here and there)
+                reinterpret_cast<ZT *>(p.z_wm)[tile.wm_begin + (int64_t)(i - tile.begin)] = (ZT)my_z;
             } else if (MODE == MODE_PROBS) {
                 p.out_S[tc] = my_S; p.out_Q[tc] = Q;
             } else {
@@ -523,14 +518,6 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
         if (lane == 0 && dense_count) atomicAdd(&wg_dense, dense_count);
         __syncthreads();
         if (threadIdx.x == 0 && wg_dense) atomicAdd(p.n_dense + (blockIdx.x & (kDenseSlots - 1)), (unsigned long long)wg_dense);
-        if (LHIST) {
-            // the tile's counts go to B in one pass: at most K atomics per tile instead of one per token
-            __syncthreads();
-            for (int k = threadIdx.x; k < K; k += blockDim.x) {
-                const uint32_t h = lds_hist[k];
-                if (h) atomicAdd(&p.cwk[(size_t)tile.row * (size_t)p.Kpad + k], (int)h);
-            }
-        }
     }
     if (MODE == MODE_LOGLIK) {
         double tot = readlane_f64(wave_incl_scan(ll_acc), 63);
@@ -560,21 +547,36 @@ __global__ void prefix_export_kernel(const float *rows, const double *l3_64, con
 }
 
 // ---------------------------------------------------------------------------------------------
-// CountByVZ from scratch (used after init / set_z; during iterations B is accumulated by the E-step)
+// CountByVZ for the words with dense rows of B.  The assignments arrive word-major (z_wm), so a word's tokens are
+// one contiguous segment; it is cut into slabs and each workgroup histograms one slab in LDS and adds the
+// non-zero bins to the word's row: at most min(slab, K) global atomics per slab instead of one per token.
+// Rows must be zero on entry (the Bhat kernel clears them after reading).  K too large for an LDS histogram:
+// one global atomic per token.
 // ---------------------------------------------------------------------------------------------
+struct VzItem { int32_t row; int32_t count; int64_t begin; };   // slab: count tokens from z_wm[begin] on
+
 template <typename ZT>
-__global__ void count_vz_kernel(const Tile *tiles, const uint32_t *tok_t, const ZT *z, int64_t t_base,
-                                int32_t *cwk, int Kpad) {
-    const Tile tile = tiles[blockIdx.x];
-    for (int i = threadIdx.x; i < tile.count; i += blockDim.x) {
-        const uint32_t t = tok_t[tile.begin + i];
-        const uint32_t k = (uint32_t)z[t_base + (int64_t)t];
-        atomicAdd(&cwk[(size_t)tile.row * (size_t)Kpad + k], 1);
+__global__ void __launch_bounds__(1024) count_vz_kernel(const VzItem *items, const ZT *z_wm, int32_t *cwk, int K,
+                                                        int Kpad, int use_lds) {
+    extern __shared__ uint32_t vz_hist[];
+    const VzItem it = items[blockIdx.x];
+    const ZT *__restrict__ zs = z_wm + it.begin;
+    int32_t *row = cwk + (size_t)it.row * (size_t)Kpad;
+    if (use_lds) {
+        for (int k = threadIdx.x; k < K; k += blockDim.x) vz_hist[k] = 0u;
+        __syncthreads();
+        for (int i = threadIdx.x; i < it.count; i += blockDim.x) atomicAdd(&vz_hist[(uint32_t)zs[i]], 1u);
+        __syncthreads();
+        for (int k = threadIdx.x; k < K; k += blockDim.x) {
+            const uint32_t h = vz_hist[k];
+            if (h) atomicAdd(&row[k], (int)h);
+        }
+    } else {
+        for (int i = threadIdx.x; i < it.count; i += blockDim.x) atomicAdd(&row[(uint32_t)zs[i]], 1);
     }
 }
 
-// word-major copy of the assignments of the light words' tokens (after init / set_z; during iterations the
-// E-step writes it)
+// word-major copy of the assignments (after init / set_z; during iterations the E-step writes it)
 template <typename ZT>
 __global__ void fill_zwm_kernel(const Tile *tiles, const uint32_t *tok_t, const ZT *z, int64_t t_base, ZT *z_wm) {
     const Tile tile = tiles[blockIdx.x];
