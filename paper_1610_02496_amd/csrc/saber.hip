@@ -159,9 +159,14 @@ static EStepParams make_params(saber_ctx *c, const Chunk &ch) {
     return p;
 }
 
-// dynamic LDS of a staged sampling workgroup: the Bhat row (K rounded to 4 floats) and the tree level (n3 floats)
-static size_t estep_lds_bytes(const saber_ctx *c) {
+// LDS of a staged sampling workgroup's row: the Bhat row (K rounded to 4 floats) and the tree level (n3 rounded to 4)
+static size_t estep_row_bytes(const saber_ctx *c) {
     return ((size_t)((c->K + 3) & ~3) + (size_t)((c->n3 + 3) & ~3)) * sizeof(float);
+}
+// dynamic LDS of a sampling workgroup: the row when staged, 16 bytes of control words, and in log-likelihood mode
+// one double per wavefront
+static size_t estep_lds_bytes(const saber_ctx *c, int mode) {
+    return (c->staged ? estep_row_bytes(c) : 0) + 16 + (mode == MODE_LOGLIK ? 16 * sizeof(double) : 0);
 }
 
 template <int MODE, bool STAGED, typename ZT>
@@ -173,6 +178,28 @@ static void launch_estep_b16(saber_ctx *c, dim3 grid, dim3 block, size_t lds, co
     }
     if (c->b16) hipLaunchKernelGGL((estep_kernel<MODE, STAGED, ZT, true, false>), grid, block, lds, c->stream, p);
     else hipLaunchKernelGGL((estep_kernel<MODE, STAGED, ZT, false, false>), grid, block, lds, c->stream, p);
+}
+
+// The staged 16/16 sampler addresses its Bhat row from LDS address 0: its kernels must have no static LDS in
+// front of the dynamic part.
+template <typename F>
+static int static_lds_is_zero(F kernel) {
+    hipFuncAttributes a;
+    HIP_TRY(hipFuncGetAttributes(&a, reinterpret_cast<const void *>(kernel)));
+    if (a.sharedSizeBytes != 0) return fail(SABER_EDEVICE, "sampling kernel built with %zu bytes of static LDS", (size_t)a.sharedSizeBytes);
+    return SABER_OK;
+}
+static int check_estep_lds_layout() {
+    SABER_TRY(static_lds_is_zero(estep_kernel<MODE_SAMPLE, true, uint16_t, true, false>));
+    SABER_TRY(static_lds_is_zero(estep_kernel<MODE_SAMPLE, true, uint16_t, true, true>));
+    SABER_TRY(static_lds_is_zero(estep_kernel<MODE_PROBS, true, uint16_t, true, false>));
+    SABER_TRY(static_lds_is_zero(estep_kernel<MODE_PROBS, true, uint16_t, true, true>));
+    SABER_TRY(static_lds_is_zero(estep_kernel<MODE_LOGLIK, true, uint16_t, true, false>));
+    SABER_TRY(static_lds_is_zero(estep_kernel<MODE_LOGLIK, true, uint16_t, true, true>));
+    SABER_TRY(static_lds_is_zero(estep_kernel<MODE_SAMPLE, true, int32_t, true, false>));
+    SABER_TRY(static_lds_is_zero(estep_kernel<MODE_PROBS, true, int32_t, true, false>));
+    SABER_TRY(static_lds_is_zero(estep_kernel<MODE_LOGLIK, true, int32_t, true, false>));
+    return SABER_OK;
 }
 
 // One E-step launch per tile class.  Dense-row tiles with at least stage_min_tokens tokens run with block_threads
@@ -193,7 +220,7 @@ static int launch_estep(saber_ctx *c, const Chunk &ch, EStepParams &p0) {
         p.tiles = p0.tiles + cl.first;
         if (p0.out_ll) p.out_ll = p0.out_ll + cl.first;
         const dim3 grid((unsigned)cl.count), block((unsigned)cl.block);
-        const size_t lds = c->staged ? estep_lds_bytes(c) : 0;
+        const size_t lds = estep_lds_bytes(c, MODE);
         if (c->staged) {
             if (c->z16) launch_estep_b16<MODE, true, uint16_t>(c, grid, block, lds, p, cl.light);
             else launch_estep_b16<MODE, true, int32_t>(c, grid, block, lds, p, false);
@@ -634,14 +661,14 @@ extern "C" int saber_init_ex(saber_ctx **out, const int64_t *doc_ptr, const int3
     c->nwords = (K + 31) / 32;
     c->topic_bits = bits; c->topic_mask = (1u << bits) - 1u;
     c->z16 = K <= 65536;
-    c->staged = opt.stage_phi && estep_lds_bytes(c) <= 60 * 1024;
+    c->staged = opt.stage_phi && estep_row_bytes(c) <= 60 * 1024;
     if (opt_in == nullptr || opt_in->block_threads <= 0) {
         // automatic workgroup size: the one that lets a CU hold the most wavefronts given the LDS footprint
         // (LDS is handed out in 512-byte pieces; a CU holds at most 32 wavefronts); ties go to the smaller size
         int lds_cu = 0;
         if (hipDeviceGetAttribute(&lds_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, 0) != hipSuccess || lds_cu <= 0)
             lds_cu = 64 * 1024;
-        const size_t need = c->staged ? ((estep_lds_bytes(c) + 160 + 511) / 512) * 512 : 512;
+        const size_t need = c->staged ? ((estep_lds_bytes(c, MODE_SAMPLE) + 144 + 511) / 512) * 512 : 512;
         int best = 256, best_waves = 0;
         for (int block : {256, 512, 1024}) {
             const int by_lds = (int)std::min<size_t>(64, (size_t)lds_cu / need), by_waves = 32 / (block / 64);
@@ -654,6 +681,7 @@ extern "C" int saber_init_ex(saber_ctx **out, const int64_t *doc_ptr, const int3
     c->vbeta = (float)V * beta;
     c->max_doc_len = maxlen;
     int rc;
+    if ((rc = check_estep_lds_layout()) != SABER_OK) { delete c; return rc; }
     try { rc = build(c, doc_ptr, word_ids); }
     catch (const std::bad_alloc &) { rc = fail(SABER_ENOMEM, "saber_init: out of host memory"); }
     if (rc != SABER_OK) { saber_free(c); return rc; }

@@ -210,26 +210,21 @@ __device__ __forceinline__ double row16_incl_scan(double v) {
 // Dense branch (problem 2, Sec. 2.3): position of x in the prefix sums of the word's Bhat row, four tokens per
 // call: the 16 lanes of DPP row g serve the token whose x they hold (all lanes of a row hold the same x).
 // The descent follows Sec. 3.2.4 with the stored level l3 (binary32 prefix sum at the end of every 64-topic
-// block; every 64th entry of it acts as the level above when K is large).  Prefix sums are non-decreasing, so
-// "first entry >= x" is the number of entries below x: every lane counts its share and one row-wide sum gives
+// block; every 16th, 256th, ... entry of it acts as the levels above).  Prefix sums are non-decreasing, so
+// "first entry >= x" is the number of entries below x: every lane tests one entry and one row-wide sum gives
 // the position.  The bottom level is not stored: the 64 prefix sums of the chosen block are rebuilt from the
 // Bhat values as round32(base + running sum in binary64), base = unrounded running sum at the block's start -
 // the numbers a stored table would hold, so the search is exact.  Returns the topic in every lane of the row.
 __device__ __forceinline__ uint32_t dense_query4(const float *phi_row, int phi_len, const float *l3,
                                                  const double *__restrict__ l3_64, int n3, int K, float x, int li) {
-    uint32_t cnt = 0;
-    int blk;
-    if (n3 <= 256) {
-        for (int i = li; i < n3; i += 16) cnt += (l3[i] < x) ? 1u : 0u;
-        blk = (int)row16_allsum(cnt);
-    } else {
-        const int n2 = (n3 + kWave - 1) / kWave;
-        for (int j = li; j < n2; j += 16) cnt += (l3[min((j + 1) * kWave - 1, n3 - 1)] < x) ? 1u : 0u;
-        const int j2 = min((int)row16_allsum(cnt), n2 - 1);
-        cnt = 0;
-#pragma unroll
-        for (int q = 0; q < 4; q++) { const int i = j2 * kWave + li * 4 + q; cnt += (i < n3 && l3[i] < x) ? 1u : 0u; }
-        blk = j2 * kWave + (int)row16_allsum(cnt);
+    // 16-ary descent over l3: lane li looks at the last entry of the li-th sub-range of the current window; the
+    // number of sub-ranges lying wholly below x is the index of the one holding the position
+    int stride = 1;
+    while (stride * 16 < n3) stride *= 16;
+    int blk = 0;
+    for (; stride >= 1; stride >>= 4) {
+        const float c = l3[min(blk + (li + 1) * stride - 1, n3 - 1)];
+        blk += min((int)row16_allsum(c < x ? 1u : 0u), 15) * stride;
     }
     blk = min(blk, n3 - 1);                                 // rounding left no block: the last one
     const double base = blk > 0 ? l3_64[blk - 1] : 0.0;
@@ -269,19 +264,28 @@ __device__ __forceinline__ uint4 load_block(const uint32_t *row, int rel_kd, int
     return make_uint4(v[0], v[1], v[2], v[3]);
 }
 
-// Bhat value of the entry's topic
-template <bool STAGED>
+// Bhat value of the entry's topic.  With 16/16 packing and the row in LDS the byte offset (topic * 4) is formed
+// by one shift that reads the low half of the entry.
+template <bool STAGED, bool B16>
 __device__ __forceinline__ float phi_of(uint32_t e, uint32_t tmask, const float *lds_phi, const float *__restrict__ phi_row) {
+    if (STAGED && B16) {
+        uint32_t off;
+        asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:WORD_0"
+            : "=v"(off) : "v"(2u), "v"(e));
+        // the staged row starts at LDS address 0 (the kernel has no static LDS; the host checks that at start-up)
+        typedef __attribute__((address_space(3))) const float lds_cfloat;
+        return *reinterpret_cast<lds_cfloat *>(off);
+    }
     return STAGED ? lds_phi[e & tmask] : phi_row[e & tmask];
 }
 
-template <bool STAGED>
+template <bool STAGED, bool B16>
 __device__ __forceinline__ void block_products(const uint4 e, uint32_t bits, uint32_t tmask,
                                                const float *lds_phi, const float *__restrict__ phi_row, RowBlock &b) {
-    const float f0 = phi_of<STAGED>(e.x, tmask, lds_phi, phi_row);
-    const float f1 = phi_of<STAGED>(e.y, tmask, lds_phi, phi_row);
-    const float f2 = phi_of<STAGED>(e.z, tmask, lds_phi, phi_row);
-    const float f3 = phi_of<STAGED>(e.w, tmask, lds_phi, phi_row);
+    const float f0 = phi_of<STAGED, B16>(e.x, tmask, lds_phi, phi_row);
+    const float f1 = phi_of<STAGED, B16>(e.y, tmask, lds_phi, phi_row);
+    const float f2 = phi_of<STAGED, B16>(e.z, tmask, lds_phi, phi_row);
+    const float f3 = phi_of<STAGED, B16>(e.w, tmask, lds_phi, phi_row);
     b.a0 = (float)(e.x >> bits) * f0;
     b.a1 = __builtin_fmaf((float)(e.y >> bits), f1, b.a0);
     b.a2 = __builtin_fmaf((float)(e.z >> bits), f2, b.a1);
@@ -309,15 +313,18 @@ __device__ __forceinline__ uint32_t search_block(const uint4 e, const RowBlock &
 template <int MODE, bool STAGED, typename ZT, bool B16, bool LIGHT>
 __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
     extern __shared__ float4 lds_f4[];
-    __shared__ double ll_wave[MODE == MODE_LOGLIK ? 16 : 1];
-    __shared__ int next_batch;   // batches of a tile are handed out to wavefronts as they become free
-    __shared__ unsigned int wg_dense;   // dense-branch tokens of this workgroup
-    // LDS (STAGED): [K rounded to 4] floats: the word's Bhat row; [n3] floats: the tree level above the bottom;
+    // LDS, all of it dynamic so that the Bhat row starts at address 0 and a gather needs no base added:
+    //   STAGED: [K rounded to 4] floats: the word's Bhat row; [n3 rounded to 4] floats: the tree level above the bottom
+    //   [4] words: batch ticket, dense-branch tokens of the workgroup;  LOGLIK: [16] doubles, one per wavefront
     // The footprint is kept minimal because it decides how many wavefronts a CU can hold: at K = 10,000 it is
-    // 40,628 bytes, which lets four 512-thread workgroups (32 wavefronts) share the 160 KB of a CU.
-    const int K4 = (p.K + 3) & ~3;
+    // 40,656 bytes, which lets four 512-thread workgroups (32 wavefronts) share the 160 KB of a CU.
+    const int K4 = STAGED ? (p.K + 3) & ~3 : 0;
     float *lds_phi = reinterpret_cast<float *>(lds_f4);
     float *lds_l3 = lds_phi + K4;
+    int *ctrl = reinterpret_cast<int *>(lds_l3 + (STAGED ? (p.n3 + 3) & ~3 : 0));
+    int &next_batch = ctrl[0];   // batches of a tile are handed out to wavefronts as they become free
+    unsigned int &wg_dense = reinterpret_cast<unsigned int *>(ctrl)[1];   // dense-branch tokens of this workgroup
+    double *ll_wave = reinterpret_cast<double *>(ctrl + 4);
     const Tile tile = p.tiles[blockIdx.x];
     const int K = p.K;
     const float *__restrict__ phi_row = LIGHT ? p.base : p.phi + (size_t)tile.row * (size_t)p.Kpad;
@@ -392,7 +399,7 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
             const unsigned long long in_run = (~0ull << s) & (s_end < kWave ? ~(~0ull << s_end) : ~0ull);
             // element-wise product A_d (.) Bhat_v, its prefix sums and its sum S (Alg. 2, product loop)
             RowBlock b0;
-            block_products<STAGED>(cur, bits, tmask, lds_phi, phi_row, b0);
+            block_products<STAGED, B16>(cur, bits, tmask, lds_phi, phi_row, b0);
             const float t0 = readlane_f32(b0.incl, 63);
             if (kd <= 4 * kWave) {
                 // the whole row sits in this block (the common case): straight-line coin and search
@@ -426,12 +433,12 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
             const int nblk = (kd + 4 * kWave - 1) / (4 * kWave);
             const uint4 e1 = load_block(row + 4 * kWave, kd - 4 * kWave, lane);
             RowBlock b1;
-            block_products<STAGED>(e1, bits, tmask, lds_phi, phi_row, b1);
+            block_products<STAGED, B16>(e1, bits, tmask, lds_phi, phi_row, b1);
             const float t1 = readlane_f32(b1.incl, 63);
             float S = t0 + t1;
             for (int blk = 2; blk < nblk; blk++) {
                 RowBlock bb;
-                block_products<STAGED>(load_block(row + blk * 4 * kWave, kd - blk * 4 * kWave, lane), bits, tmask,
+                block_products<STAGED, B16>(load_block(row + blk * 4 * kWave, kd - blk * 4 * kWave, lane), bits, tmask,
                                        lds_phi, phi_row, bb);
                 S = S + readlane_f32(bb.incl, 63);
             }
@@ -453,7 +460,7 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
                                 const int rel = kd - blk * 4 * kWave;
                                 const uint4 e = load_block(row + blk * 4 * kWave, rel, lane);
                                 RowBlock bb;
-                                block_products<STAGED>(e, bits, tmask, lds_phi, phi_row, bb);
+                                block_products<STAGED, B16>(e, bits, tmask, lds_phi, phi_row, bb);
                                 const float tot = readlane_f32(bb.incl, 63);
                                 if (blk == nblk - 1 || carry + tot >= x) { topic = search_block(e, bb, carry, x, rel, tmask); break; }
                                 carry = carry + tot;
