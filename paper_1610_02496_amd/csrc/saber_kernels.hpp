@@ -264,6 +264,21 @@ __device__ __forceinline__ uint4 load_block(const uint32_t *row, int rel_kd, int
     return make_uint4(v[0], v[1], v[2], v[3]);
 }
 
+// The same for a row given by its address halves and padded length in bytes (wave-uniform values read from the
+// lane of the run's first token).
+__device__ __forceinline__ uint4 load_block(uint32_t addr_lo, uint32_t addr_hi, uint32_t row_bytes, int lane) {
+    void *row = reinterpret_cast<void *>(((uint64_t)addr_hi << 32) | (uint64_t)addr_lo);
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(row, (short)0, (int)row_bytes, 0x00020000);
+    const auto v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane * 16, 0, 0);
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
+// clear bit `bit` of a wave-uniform mask (one scalar instruction)
+__device__ __forceinline__ unsigned long long clear_bit(unsigned long long m, int bit) {
+    asm("s_bitset0_b64 %0, %1" : "+s"(m) : "s"(bit));
+    return m;
+}
+
 // Bhat value of the entry's topic.  With 16/16 packing and the row in LDS the byte offset (topic * 4) is formed
 // by one shift that reads the low half of the entry.
 template <bool STAGED, bool B16>
@@ -384,44 +399,56 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
         // `rest` marks a lane i > s where a new document starts.
         const int d_prev = __builtin_amdgcn_update_dpp(-2, d, 0x138, 0xf, 0xf, false);   // wave_shr:1
         unsigned long long rest = __builtin_amdgcn_ballot_w64(act && d != d_prev) & ~1ull;
+        // every lane prepares the buffer descriptor words of its document's row, so that a run needs three
+        // lane reads and no scalar address arithmetic: address halves and the padded row length in bytes
+        const uint64_t row_addr = (uint64_t)reinterpret_cast<uintptr_t>(p.cd_ent) + ((uint64_t)rec.x << 7);
+        const uint32_t ra_lo = (uint32_t)row_addr, ra_hi = (uint32_t)(row_addr >> 32);
+        const uint32_t ra_bytes = ((rec.y + 3u) & ~3u) << 2;
+        unsigned long long below_s = 0ull;   // lanes before the current run
 
         // One run [s, s_end) of tokens of this word in one document: they share A_d (.) Bhat_v and S.
-        // `cur` holds the first block of the run's row (fetched during the previous run), kd its length and ru
-        // its position; the first block of the next run's row is fetched into `nxt` before this run's
+        // `cur` holds the first block of the run's row (fetched during the previous run) and cur_bytes the row's
+        // padded length; the first block of the next run's row is fetched into `nxt` before this run's
         // arithmetic starts.
-        auto do_run = [&](const uint4 &cur, const int kd, const uint32_t ru, uint4 &nxt, int &kd_nxt, uint32_t &ru_nxt) {
-            const int s_end = rest ? (int)__builtin_ctzll(rest) : n;
-            rest &= rest - 1ull;
-            if (s_end < n) {
-                kd_nxt = (int)readlane_u32(rec.y, s_end); ru_nxt = readlane_u32(rec.x, s_end);
-                nxt = load_block(p.cd_ent + (size_t)ru_nxt * 32u, kd_nxt, lane);
+        auto do_run = [&](const uint4 &cur, const uint32_t cur_bytes, uint4 &nxt, uint32_t &nxt_bytes) {
+            const bool more = rest != 0ull;       // run starts are marked on active lanes only
+            const int s_end = more ? (int)__builtin_ctzll(rest) : n;
+            if (more) {
+                rest = clear_bit(rest, s_end);
+                nxt_bytes = readlane_u32(ra_bytes, s_end);
+                nxt = load_block(readlane_u32(ra_lo, s_end), readlane_u32(ra_hi, s_end), nxt_bytes, lane);
             }
-            const unsigned long long in_run = (~0ull << s) & (s_end < kWave ? ~(~0ull << s_end) : ~0ull);
+            const unsigned long long below_end = ~0ull >> (kWave - s_end);   // 1 <= s_end <= 64
+            const unsigned long long in_run = below_end & ~below_s;
+            below_s = below_end;
             // element-wise product A_d (.) Bhat_v, its prefix sums and its sum S (Alg. 2, product loop)
             RowBlock b0;
             block_products<STAGED, B16>(cur, bits, tmask, lds_phi, phi_row, b0);
             const float t0 = readlane_f32(b0.incl, 63);
-            if (kd <= 4 * kWave) {
+            if (cur_bytes <= 16u * kWave) {
                 // the whole row sits in this block (the common case): straight-line coin and search
                 if (MODE == MODE_SAMPLE) {
                     unsigned long long sparse = __builtin_amdgcn_ballot_w64(u0 * (t0 + Q) < t0) & in_run;
                     dense_mask |= in_run & ~sparse;       // problem 2 is served after the runs, four tokens at a time
-                    const float xs = u1 * t0;
-                    const float base = b0.incl - b0.a3;
-                    const float p0 = base + b0.a0, p1 = base + b0.a1, p2 = base + b0.a2;
-                    const int last_lane = (kd - 1) >> 2;
-                    while (sparse) {
-                        // problem 1: position of x in the prefix sums of P
-                        const int r = (int)__builtin_ctzll(sparse);
-                        sparse &= sparse - 1ull;
-                        const float x = readlane_f32(xs, r);
-                        const unsigned long long m3 = __builtin_amdgcn_ballot_w64(b0.incl >= x);
-                        const int L = m3 ? (int)__builtin_ctzll(m3) : last_lane;
-                        uint32_t sel = cur.w;
-                        sel = p2 >= x ? cur.z : sel;
-                        sel = p1 >= x ? cur.y : sel;
-                        sel = p0 >= x ? cur.x : sel;
-                        my_z = llvm_amdgcn_writelane_u32(readlane_u32(sel, L) & tmask, (unsigned)r, my_z);
+                    if (sparse) {
+                        const float xs = u1 * t0;
+                        const float base = b0.incl - b0.a3;
+                        const float p0 = base + b0.a0, p1 = base + b0.a1, p2 = base + b0.a2;
+                        // lanes past the row's end repeat its last inclusive sum: if rounding leaves no lane, the
+                        // choice falls on the last one, whose padding repeats the row's last topic
+                        const unsigned long long last_lane_bit = 1ull << ((cur_bytes >> 4) - 1u);
+                        do {
+                            // problem 1: position of x in the prefix sums of P
+                            const int r = (int)__builtin_ctzll(sparse);
+                            sparse = clear_bit(sparse, r);
+                            const float x = readlane_f32(xs, r);
+                            const int L = (int)__builtin_ctzll(__builtin_amdgcn_ballot_w64(b0.incl >= x) | last_lane_bit);
+                            uint32_t sel = cur.w;
+                            sel = p2 >= x ? cur.z : sel;
+                            sel = p1 >= x ? cur.y : sel;
+                            sel = p0 >= x ? cur.x : sel;
+                            my_z = llvm_amdgcn_writelane_u32(readlane_u32(sel, L) & tmask, (unsigned)r, my_z);
+                        } while (sparse);
                     }
                 } else {
                     if (lane >= s && lane < s_end) my_S = t0;
@@ -429,7 +456,8 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
                 s = s_end;
                 return;
             }
-            const uint32_t *row = p.cd_ent + (size_t)ru * 32u;
+            const int kd = (int)readlane_u32(rec.y, s);
+            const uint32_t *row = p.cd_ent + (size_t)readlane_u32(rec.x, s) * 32u;
             const int nblk = (kd + 4 * kWave - 1) / (4 * kWave);
             const uint4 e1 = load_block(row + 4 * kWave, kd - 4 * kWave, lane);
             RowBlock b1;
@@ -439,7 +467,7 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
             for (int blk = 2; blk < nblk; blk++) {
                 RowBlock bb;
                 block_products<STAGED, B16>(load_block(row + blk * 4 * kWave, kd - blk * 4 * kWave, lane), bits, tmask,
-                                       lds_phi, phi_row, bb);
+                                            lds_phi, phi_row, bb);
                 S = S + readlane_f32(bb.incl, 63);
             }
             if (MODE == MODE_SAMPLE) {
@@ -475,14 +503,13 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
             s = s_end;
         };
 
-        int kd_a = (int)readlane_u32(rec.y, 0), kd_b = 0;
-        uint32_t ru_a = readlane_u32(rec.x, 0), ru_b = 0u;
-        uint4 blk_a = load_block(p.cd_ent + (size_t)ru_a * 32u, kd_a, lane);
+        uint32_t bytes_a = readlane_u32(ra_bytes, 0), bytes_b = 0u;
+        uint4 blk_a = load_block(readlane_u32(ra_lo, 0), readlane_u32(ra_hi, 0), bytes_a, lane);
         uint4 blk_b = make_uint4(0u, 0u, 0u, 0u);
         while (s < n) {
-            do_run(blk_a, kd_a, ru_a, blk_b, kd_b, ru_b);
+            do_run(blk_a, bytes_a, blk_b, bytes_b);
             if (s >= n) break;
-            do_run(blk_b, kd_b, ru_b, blk_a, kd_a, ru_a);
+            do_run(blk_b, bytes_b, blk_a, bytes_a);
         }
 
         if (MODE == MODE_SAMPLE && dense_mask) {
@@ -495,7 +522,7 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
 #pragma unroll
                 for (int q = 0; q < 4; q++) {
                     tl[q] = dense_mask ? (int)__builtin_ctzll(dense_mask) : -1;
-                    dense_mask &= dense_mask - 1ull;
+                    if (dense_mask) dense_mask = clear_bit(dense_mask, tl[q]);
                 }
                 const int mine = g == 0 ? tl[0] : g == 1 ? tl[1] : g == 2 ? tl[2] : tl[3];
                 const float x = __int_as_float(__builtin_amdgcn_ds_bpermute((mine < 0 ? lane : mine) << 2, __float_as_int(xd)));
