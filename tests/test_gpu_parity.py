@@ -159,6 +159,18 @@ def test_long_documents_and_global_row_fallback():
     assert_estep_parity(g, o)
 
 
+def test_mixed_row_lengths_in_one_tile():
+    """Lognormal lengths from a few tokens to a few thousand: rows of at most 128 entries (taken two at a time),
+    rows that fill one 256-entry block and rows of several blocks meet inside the same tiles."""
+    spec = corpusgen.CorpusSpec("mixed", 400, 600, 400 * 300, "lognormal", 300.0, 1.2, 30, 1.1, 0.05, 0.5, 3000, 1, 13)
+    c = corpusgen.generate(spec, nthreads=2)
+    g, o = make_pair(c, 3000, 50.0 / 3000, 0.01, 23)
+    kd = np.diff(o.cd[0])
+    assert (kd <= 128).sum() > 20 and ((kd > 128) & (kd <= 256)).sum() > 20 and (kd > 256).sum() > 20
+    assert_estep_parity(g, o)
+    assert_estep_parity(g, o)
+
+
 def test_empty_documents_and_single_tokens():
     doc_ptr = np.array([0, 0, 1, 1, 4, 4, 4, 9, 9], dtype=np.int64)
     word_ids = np.array([3, 0, 0, 2, 1, 1, 1, 3, 0], dtype=np.int32)
