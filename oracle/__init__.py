@@ -65,6 +65,8 @@ def lib():
         "orc_model_sample_tokens": (None, [c_void_p, c_void_p, c_i64, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
         "orc_model_loglik": (c_f64, [c_void_p]),
         "orc_model_iter": (c_u32, [c_void_p]),
+        "orc_holdout_loglik": (c_int, [c_void_p, c_i64, c_void_p, c_void_p, c_void_p, c_i32, c_u64, c_void_p, c_int,
+                                       c_void_p, c_void_p, c_void_p]),
     }
     for name in ("z", "cd_ptr", "cd_topic", "cd_count", "cwk", "ck", "phi", "c32", "sum64"):
         sig["orc_model_" + name] = (c_void_p, [c_void_p])
@@ -228,6 +230,25 @@ class Model:
 
     def loglik(self):
         return lib().orc_model_loglik(self._h)
+
+    def holdout_loglik(self, doc_ptr, word_ids, observed, n_fold, seed, z_init=None, nthreads=1):
+        """Document-completion log-likelihood of held-out documents under this model's frozen Bhat: fold in the
+        observed tokens for ``n_fold`` iterations, score the others.  Returns (ll per scored token, scored tokens,
+        final assignments of the observed tokens)."""
+        doc_ptr = np.ascontiguousarray(doc_ptr, dtype=np.int64)
+        word_ids = np.ascontiguousarray(word_ids, dtype=np.int32)
+        observed = np.ascontiguousarray(observed, dtype=np.uint8)
+        assert observed.size == word_ids.size == int(doc_ptr[-1])
+        n_obs = int(np.count_nonzero(observed))
+        if z_init is not None:
+            z_init = np.ascontiguousarray(z_init, dtype=np.int32); assert z_init.size == n_obs
+        z_out = np.empty(max(n_obs, 1), dtype=np.int32)
+        ll = c_f64(); scored = c_i64()
+        rc = lib().orc_holdout_loglik(self._h, doc_ptr.size - 1, _p(doc_ptr), _p(word_ids), _p(observed), n_fold, seed,
+                                      _p(z_init), nthreads, ctypes.addressof(ll), ctypes.addressof(scored), _p(z_out))
+        if rc:
+            raise ValueError("orc_holdout_loglik: %d" % rc)
+        return ll.value, scored.value, z_out[:n_obs]
 
     @property
     def iter(self):

@@ -39,7 +39,9 @@
  * worked inverse-CDF example of Fig. 2, count invariants and brute-force
  * histograms, column sums of Bhat, K=1 closed forms, tree query == linear scan
  * for several W, the split sampler's induced measure and chi-square against the
- * dense Eq. 1, planted-topic recovery, dense evaluation of the log-likelihood.
+ * dense Eq. 1, planted-topic recovery, dense evaluation of the log-likelihood;
+ * holdout log-likelihood: K=1 closed form, the no-observation closed form, dense
+ * evaluation from the returned assignments, improvement under fold-in.
  * The realised sample path z itself has no printed reference in the paper:
  * "parity unpinned" beyond the distributional and invariant pins above.
  */
@@ -399,6 +401,75 @@ void orc_model_sample_tokens(orc_model *m, const int64_t *tok, int64_t n, int32_
 double orc_model_loglik(orc_model *m) {
     return orc_loglik(m->D, m->doc_ptr, m->word_ids, m->K, m->alpha, m->cd_ptr, m->cd_topic, m->cd_count,
                       m->phi, m->sum64);
+}
+
+/* ------------------------------------------------------------------ holdout log-likelihood
+ * The quality metric Sec. 4 names: log-likelihood per token of held-out documents, "partially-observed
+ * document" approach.  The paper prints no formula; the reading taken is document completion: every held-out
+ * document is split into an observed part and a scored part (the caller's mask).  The model's Bhat, prefix
+ * table and row sums stay frozen.  Fold-in: the observed tokens get assignments by the same ESCA iteration as
+ * training (Alg. 1 restricted to these documents and to A): iteration 0 assigns z = floor(word0 K / 2^32) with
+ * the Philox counter = position of the token among the observed tokens, or the caller supplies z_init;
+ * iterations 1..n_fold run Alg. 2 for every observed token against A' = counts of the document's observed
+ * assignments (frozen during the iteration), then rebuild A'.  Score:
+ *     (1/T_s) sum over scored tokens t of [ ln(S_t + Q_w) - ln(L'_d + K alpha) ],
+ * S_t = sum_k A'_dk Bhat_wk, L'_d = observed tokens of the document: the predictive probability
+ * sum_k theta_dk Bhat_wk with theta_dk = (A'_dk + alpha) / (L'_d + K alpha).
+ * z_out (may be NULL) receives the final assignments of the observed tokens, in corpus order.
+ * Returns 0, or -1 on a bad argument / allocation failure. */
+int orc_holdout_loglik(const orc_model *m, int64_t D, const int64_t *doc_ptr, const int32_t *word_ids,
+                       const uint8_t *observed, int32_t n_fold, uint64_t seed, const int32_t *z_init,
+                       int nthreads, double *out_ll, int64_t *out_scored, int32_t *z_out) {
+    int64_t T = doc_ptr[D], To = 0;
+    for (int64_t t = 0; t < T; t++) { if (word_ids[t] < 0 || word_ids[t] >= m->V) return -1; To += observed[t] ? 1 : 0; }
+    size_t no = (size_t)(To > 0 ? To : 1);
+    int64_t *optr = (int64_t *)malloc(sizeof(int64_t) * (size_t)(D + 1));
+    int32_t *ow = (int32_t *)malloc(sizeof(int32_t) * no), *z = (int32_t *)malloc(sizeof(int32_t) * no);
+    int32_t *zn = (int32_t *)malloc(sizeof(int32_t) * no);
+    int64_t *cd_ptr = (int64_t *)malloc(sizeof(int64_t) * (size_t)(D + 1));
+    int32_t *cd_topic = (int32_t *)malloc(sizeof(int32_t) * no), *cd_count = (int32_t *)malloc(sizeof(int32_t) * no);
+    int rc = -1;
+    if (!optr || !ow || !z || !zn || !cd_ptr || !cd_topic || !cd_count) goto done;
+    /* the observed part as a corpus of its own */
+    optr[0] = 0;
+    for (int64_t d = 0, k = 0; d < D; d++) {
+        for (int64_t t = doc_ptr[d]; t < doc_ptr[d + 1]; t++) if (observed[t]) ow[k++] = word_ids[t];
+        optr[d + 1] = k;
+    }
+    if (z_init) {
+        for (int64_t t = 0; t < To; t++) { if (z_init[t] < 0 || z_init[t] >= m->K) goto done; z[t] = z_init[t]; }
+    } else {
+        orc_init_z(To, m->K, seed, z);
+    }
+    for (int32_t it = 1; it <= n_fold; it++) {
+        if (orc_count_by_dz(D, optr, z, m->K, cd_ptr, cd_topic, cd_count)) goto done;
+        orc_estep(D, optr, ow, m->K, m->alpha, cd_ptr, cd_topic, cd_count, m->phi, m->c32, m->sum64, seed,
+                  (uint32_t)it, zn, NULL, NULL, NULL, NULL, nthreads);
+        int32_t *tmp = z; z = zn; zn = tmp;
+    }
+    if (orc_count_by_dz(D, optr, z, m->K, cd_ptr, cd_topic, cd_count)) goto done;
+    {
+        double total = 0.0; int64_t scored = 0;
+        for (int64_t d = 0; d < D; d++) {
+            int64_t a = cd_ptr[d]; int32_t nnz = (int32_t)(cd_ptr[d + 1] - a);
+            double lognorm = log((double)(optr[d + 1] - optr[d]) + (double)m->K * (double)m->alpha);
+            for (int64_t t = doc_ptr[d]; t < doc_ptr[d + 1]; t++) {
+                if (observed[t]) continue;
+                const float *phi_w = m->phi + (size_t)word_ids[t] * (size_t)m->K;
+                double S = 0.0;
+                for (int32_t j = 0; j < nnz; j++) S += (double)cd_count[a + j] * (double)phi_w[cd_topic[a + j]];
+                total += log(S + (double)m->alpha * m->sum64[word_ids[t]]) - lognorm;
+                scored++;
+            }
+        }
+        *out_ll = scored > 0 ? total / (double)scored : 0.0;
+        *out_scored = scored;
+    }
+    if (z_out) memcpy(z_out, z, sizeof(int32_t) * (size_t)To);
+    rc = 0;
+done:
+    free(optr); free(ow); free(z); free(zn); free(cd_ptr); free(cd_topic); free(cd_count);
+    return rc;
 }
 
 /* accessors (pointers into the model; valid until the next mutating call) */
