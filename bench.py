@@ -68,7 +68,28 @@ def profiled_traffic(workload, steps, warmup):
     return None
 
 
-def run_gpu(corpus, K, steps, warmup, opts):
+def run_holdout(g, corpus, docs, n_foldin):
+    """Holdout log-likelihood by document completion on the model just trained.  The scored documents are a
+    prefix of the training corpus standing in for held-out ones (the synthetic corpus has no separate held-out
+    part): the figure of interest is the cost of the call, which includes the layout build and upload of the
+    documents, ``n_foldin`` fold-in iterations and the scoring pass."""
+    docs = min(docs, corpus.spec.D)
+    doc_ptr = np.ascontiguousarray(corpus.doc_ptr[: docs + 1])
+    T = int(doc_ptr[-1])
+    word_ids = np.ascontiguousarray(corpus.word_ids[:T])
+    pos = np.arange(T) - np.repeat(doc_ptr[:-1], np.diff(doc_ptr))
+    observed = (pos % 2 == 0).astype(np.uint8)
+    t0 = time.perf_counter()
+    ll, scored, _ = g.holdout_loglik(doc_ptr, word_ids, observed, n_foldin, 12345)
+    dt = time.perf_counter() - t0
+    n_obs = int(observed.sum())
+    return {"documents": docs, "observed_tokens": n_obs, "scored_tokens": scored, "n_foldin": n_foldin,
+            "seconds": dt, "foldin_tokens_per_s": n_obs * n_foldin / dt, "loglik_per_scored_token": ll,
+            "note": "documents are a prefix of the training corpus (stand-in for held-out documents); even positions "
+                    "observed, odd positions scored; seconds include layout build, upload, fold-in and scoring"}
+
+
+def run_gpu(corpus, K, steps, warmup, opts, holdout_docs=0):
     import torch
     import paper_1610_02496_amd as pk
     s = corpus.spec
@@ -105,6 +126,8 @@ def run_gpu(corpus, K, steps, warmup, opts):
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
                      "bytes_per_launch": bytes_total / launches, "ms_per_launch": ms_sample / launches},
     }
+    if holdout_docs:
+        res["holdout"] = run_holdout(g, corpus, holdout_docs, 10)
     g.close()
     return res
 
@@ -143,6 +166,8 @@ def main():
     ap.add_argument("--stage-min", type=int, default=0)
     ap.add_argument("--light-block", type=int, default=0)
     ap.add_argument("--probe-bytes", type=int, default=1 << 30, help="size of the copy-bandwidth probe (0 = skip)")
+    ap.add_argument("--holdout-docs", type=int, default=30000,
+                    help="documents scored by the holdout log-likelihood after the timed region (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards by document, "
@@ -172,7 +197,7 @@ def main():
         import paper_1610_02496_amd as pk
         copy_gbs = pk.bandwidth_probe(args.probe_bytes, 10)
         log("[bench] plain copy kernel: %.0f GB/s (read+write)" % copy_gbs)
-    main_res = run_gpu(corpus, spec.K, args.steps, args.warmup, opts)
+    main_res = run_gpu(corpus, spec.K, args.steps, args.warmup, opts, args.holdout_docs)
     main_res["roofline"]["copy_kernel_gbs"] = copy_gbs
     if not opts and not args.docs:
         main_res["roofline"]["traffic"] = profiled_traffic(args.workload, args.steps, args.warmup)
@@ -195,8 +220,10 @@ def main():
                                "iterations %d..%d from the Philox initial assignment"
                                % (spec.name, spec.D, spec.V, corpus.T, spec.K, args.warmup + 1, args.warmup + args.steps)},
         "roofline": main_res["roofline"], "cpu_baseline": cpu,
-        "detail": {k: v for k, v in main_res.items() if k != "roofline"},
+        "detail": {k: v for k, v in main_res.items() if k not in ("roofline", "holdout")},
     }
+    if "holdout" in main_res:
+        out["holdout"] = main_res["holdout"]
     if also is not None:
         out["also"] = also
     print(json.dumps(out), flush=True)

@@ -137,6 +137,29 @@ int saber_counts(saber_ctx *ctx, int64_t *cd_row_ptr, int32_t *cd_topic, int32_t
  */
 int saber_loglik(saber_ctx *ctx, double *per_token_ll);
 
+/*
+ * Holdout log-likelihood per token of held-out documents, "partially-observed document" approach (the quality
+ * metric of Sec. 4; the paper prints no formula, the reading taken is document completion).  The model of ctx
+ * (Bhat, trees) stays frozen and ctx is not changed.
+ *   doc_ptr [D+1], word_ids [T]  the held-out documents, as for saber_init (same V)
+ *   observed [T]                 non-zero: the token is folded in; zero: the token is scored
+ *   n_foldin                     iterations of Alg. 1 restricted to these documents and to A: the observed
+ *                                tokens sample from p(k) ~ (A'_dk + alpha) Bhat_vk, A' = counts of the document's
+ *                                observed assignments, frozen during an iteration and rebuilt after it
+ *   seed                         Philox key of the fold-in; the counter of a token is its position among the
+ *                                observed tokens; iteration 0 assigns z = floor(word0 K / 2^32)
+ *   z_init                       NULL, or the assignments of the observed tokens (corpus order) to start from
+ *                                instead of iteration 0
+ *   z_out                        NULL, or receives the final assignments of the observed tokens
+ *   loglik, n_scored             (1/T_s) sum over scored tokens of [ ln(S_t + Q_w) - ln(L'_d + K alpha) ] with
+ *                                S_t = sum_k A'_dk Bhat_wk and L'_d = observed tokens of the document; T_s
+ * All pointers are host pointers owned by the caller.  Documents longer than the count bits of the model's
+ * packing allow are refused (ERANGE).  Allocates and frees device memory for the held-out documents.
+ */
+int saber_holdout_loglik(saber_ctx *ctx, const int64_t *doc_ptr, const int32_t *word_ids, const uint8_t *observed,
+                         int64_t D, int32_t n_foldin, uint64_t seed, const int32_t *z_init, int32_t *z_out,
+                         double *loglik, int64_t *n_scored);
+
 void saber_free(saber_ctx *ctx);
 
 /* Message of the calling thread's last failed call (static storage, never NULL). */

@@ -18,7 +18,7 @@ _STATUS = {0: "SABER_OK", -1: "SABER_EINVAL", -2: "SABER_ENOMEM", -3: "SABER_EDE
 
 # every symbol include/saber.h declares
 EXPORTS = ["saber_options_default", "saber_init_ex", "saber_init", "saber_iterate", "saber_counts_nnz",
-           "saber_counts", "saber_loglik", "saber_free", "saber_last_error", "saber_get_z", "saber_set_z",
+           "saber_counts", "saber_loglik", "saber_holdout_loglik", "saber_free", "saber_last_error", "saber_get_z", "saber_set_z",
            "saber_get_iteration", "saber_token_probs", "saber_get_phi", "saber_get_stats", "saber_reset_stats",
            "saber_get_stream", "saber_bandwidth_probe"]
 
@@ -77,6 +77,7 @@ def load_library():
         "saber_counts_nnz": (ctypes.c_int, [vp, vp]),
         "saber_counts": (ctypes.c_int, [vp, vp, vp, vp, vp, vp]),
         "saber_loglik": (ctypes.c_int, [vp, vp]),
+        "saber_holdout_loglik": (ctypes.c_int, [vp, vp, vp, vp, i64, i32, u64, vp, vp, vp, vp]),
         "saber_free": (None, [vp]),
         "saber_last_error": (ctypes.c_char_p, []),
         "saber_get_z": (ctypes.c_int, [vp, vp]),
@@ -180,6 +181,27 @@ class Saber:
         v = ctypes.c_double()
         _check(load_library().saber_loglik(self._h, ctypes.addressof(v)))
         return v.value
+
+    def holdout_loglik(self, doc_ptr, word_ids, observed, n_foldin, seed, z_init=None):
+        """Document-completion log-likelihood of held-out documents; returns (ll per scored token, scored tokens,
+        final assignments of the observed tokens)."""
+        doc_ptr = np.ascontiguousarray(doc_ptr, dtype=np.int64)
+        word_ids = np.ascontiguousarray(word_ids, dtype=np.int32)
+        observed = np.ascontiguousarray(observed, dtype=np.uint8)
+        if observed.size != word_ids.size or word_ids.size != int(doc_ptr[-1]):
+            raise ValueError("doc_ptr, word_ids and observed do not describe the same token list")
+        n_obs = int(np.count_nonzero(observed))
+        if z_init is not None:
+            z_init = np.ascontiguousarray(z_init, dtype=np.int32)
+            if z_init.size != n_obs:
+                raise ValueError("z_init must hold one assignment per observed token")
+        z_out = np.zeros(max(n_obs, 1), dtype=np.int32)
+        ll = ctypes.c_double(); scored = ctypes.c_int64()
+        _check(load_library().saber_holdout_loglik(self._h, _ptr(doc_ptr), _ptr(word_ids), _ptr(observed),
+                                                   doc_ptr.size - 1, n_foldin, seed,
+                                                   None if z_init is None else _ptr(z_init), _ptr(z_out),
+                                                   ctypes.addressof(ll), ctypes.addressof(scored)))
+        return ll.value, scored.value, z_out[:n_obs]
 
     def get_z(self):
         z = np.zeros(self.T, dtype=np.int32)

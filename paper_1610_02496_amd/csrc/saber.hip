@@ -88,6 +88,10 @@ struct saber_ctx {
     VzItem *vz_items = nullptr;       // slabs of the dense-row words' segments of z_wm
     int64_t n_vz_items = 0;
     std::vector<int32_t> h_word_row;  // host: word -> dense row (>= 0) or -(light row) - 1
+    // A context built on a trained model (held-out documents): it borrows the model's word classes, Bhat, tree
+    // levels and sparse rows, owns only its own tokens, z and rows of A, and never rebuilds B.
+    const saber_ctx *parent = nullptr;
+    bool no_state = false;            // no assignments of its own (tokens that are only scored)
     int32_t *cwk = nullptr;           // [V_dense+1][Kpad]
     unsigned long long *ck = nullptr; // [K] topic totals
     float *denom = nullptr;           // [K] denominators of Eq. 2
@@ -131,11 +135,14 @@ extern "C" void saber_free(saber_ctx *c) {
     if (!c) return;
     if (c->stream) (void)hipStreamSynchronize(c->stream);
     dev_free(c->z); dev_free(c->tok_doc); dev_free(c->tok_t); dev_free(c->tiles); dev_free(c->docrec);
-    dev_free(c->cd_ent); dev_free(c->doc_ptr); dev_free(c->short_docs); dev_free(c->long_docs); dev_free(c->cwk);
-    dev_free(c->ck); dev_free(c->denom); dev_free(c->phi); dev_free(c->l3_64); dev_free(c->l3); dev_free(c->sumphi); dev_free(c->doc_words);
-    dev_free(c->counters); dev_free(c->dense_slots); dev_free(c->ll_partial);
-    dev_free(c->row_word); dev_free(c->light_words); dev_free(c->light_short); dev_free(c->light_long);
-    dev_free(c->light_tok_ptr); dev_free(c->wrec); dev_free(c->lw_ent); dev_free(c->lw_phi); dev_free(c->z_wm); dev_free(c->vz_items);
+    dev_free(c->cd_ent); dev_free(c->doc_ptr); dev_free(c->short_docs); dev_free(c->long_docs);
+    dev_free(c->doc_words); dev_free(c->counters); dev_free(c->dense_slots); dev_free(c->ll_partial); dev_free(c->z_wm);
+    if (!c->parent) {   // the model's arrays belong to the model
+        dev_free(c->cwk); dev_free(c->ck); dev_free(c->denom); dev_free(c->phi); dev_free(c->l3_64); dev_free(c->l3);
+        dev_free(c->sumphi); dev_free(c->row_word); dev_free(c->light_words); dev_free(c->light_short);
+        dev_free(c->light_long); dev_free(c->light_tok_ptr); dev_free(c->wrec); dev_free(c->lw_ent); dev_free(c->lw_phi);
+        dev_free(c->vz_items);
+    }
     if (c->have_events) for (auto &e : c->ev) if (e) (void)hipEventDestroy(e);
     if (c->stream) (void)hipStreamDestroy(c->stream);
     delete c;
@@ -362,6 +369,10 @@ static int launch_count_vz(saber_ctx *c) {
 // The M-step after the assignments changed outside an E-step: all four rebuilds of Alg. 1.
 static int full_mstep(saber_ctx *c) {
     SABER_TRY(launch_count_dz(c));
+    if (c->parent) {   // held-out documents: A only, the model stays frozen
+        HIP_TRY(hipStreamSynchronize(c->stream));
+        return SABER_OK;
+    }
     SABER_TRY(launch_fill_zwm(c));
     SABER_TRY(launch_count_vz(c));
     SABER_TRY(launch_topic_totals(c));
@@ -418,6 +429,7 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     std::vector<int64_t> n_v((size_t)V, 0);
     for (int64_t t = 0; t < T; t++) n_v[(size_t)word_ids[t]]++;
     const bool light_ok = c->staged && c->z16 && c->opt.light_word_tokens > 0;
+    const saber_ctx *par = c->parent;   // then the model's word classes are taken over
     // a packed entry of a sparse row has at least 16 count bits when the assignments are 16-bit
     c->opt.light_word_tokens = std::min(c->opt.light_word_tokens, 65536);
     c->h_word_row.assign((size_t)V, 0);
@@ -427,7 +439,7 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     {
         int64_t lunits = 0;
         for (int32_t v = 0; v < V; v++) {
-            if (light_ok && n_v[(size_t)v] < c->opt.light_word_tokens) {
+            if (par ? par->h_word_row[(size_t)v] < 0 : (light_ok && n_v[(size_t)v] < c->opt.light_word_tokens)) {
                 const int32_t li = (int32_t)h_light_words.size();
                 c->h_word_row[(size_t)v] = -li - 1;
                 h_light_words.push_back(v);
@@ -539,26 +551,34 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     SABER_TRY(dev_alloc(&c->tiles, h_tiles.size())); SABER_TRY(dev_alloc(&c->docrec, (size_t)D));
     SABER_TRY(dev_alloc(&c->cd_ent, (size_t)c->cd_cap)); SABER_TRY(dev_alloc(&c->doc_ptr, (size_t)D + 1));
     SABER_TRY(dev_alloc(&c->short_docs, h_short.size())); SABER_TRY(dev_alloc(&c->long_docs, h_long.size()));
+    if (par) {
+        // borrowed from the model: everything the sampler reads about words
+        c->phi = par->phi; c->l3 = par->l3; c->l3_64 = par->l3_64; c->sumphi = par->sumphi;
+        c->wrec = par->wrec; c->lw_ent = par->lw_ent; c->lw_phi = par->lw_phi;
+    } else {
     SABER_TRY(dev_alloc(&c->cwk, vk)); SABER_TRY(dev_alloc(&c->ck, (size_t)K)); SABER_TRY(dev_alloc(&c->denom, (size_t)K));
     SABER_TRY(dev_alloc(&c->phi, vk)); SABER_TRY(dev_alloc(&c->l3_64, ((size_t)V + 1) * (size_t)c->n3));
     SABER_TRY(dev_alloc(&c->row_word, h_row_word.size())); SABER_TRY(dev_alloc(&c->light_words, h_light_words.size()));
     SABER_TRY(dev_alloc(&c->light_short, h_light_short.size())); SABER_TRY(dev_alloc(&c->light_long, h_light_long.size()));
     SABER_TRY(dev_alloc(&c->light_tok_ptr, h_light_tok_ptr.size())); SABER_TRY(dev_alloc(&c->wrec, h_wrec.size()));
     SABER_TRY(dev_alloc(&c->lw_ent, (size_t)c->lw_cap)); SABER_TRY(dev_alloc(&c->lw_phi, (size_t)c->lw_cap));
+    }
     if (c->z16) SABER_TRY(dev_alloc((uint16_t **)&c->z_wm, (size_t)T)); else SABER_TRY(dev_alloc((int32_t **)&c->z_wm, (size_t)T));
+    if (!par) {
     SABER_TRY(dev_alloc(&c->vz_items, h_vz_items.size()));
     if (!h_vz_items.empty())
         HIP_TRY(hipMemcpy(c->vz_items, h_vz_items.data(), sizeof(VzItem) * h_vz_items.size(), hipMemcpyHostToDevice));
     HIP_TRY(hipMemcpy(c->row_word, h_row_word.data(), sizeof(int32_t) * h_row_word.size(), hipMemcpyHostToDevice));
     HIP_TRY(hipMemcpy(c->light_tok_ptr, h_light_tok_ptr.data(), sizeof(int64_t) * h_light_tok_ptr.size(), hipMemcpyHostToDevice));
-    if (c->V_light) {
+    }
+    if (c->V_light && !par) {
         HIP_TRY(hipMemcpy(c->light_words, h_light_words.data(), sizeof(int32_t) * h_light_words.size(), hipMemcpyHostToDevice));
         HIP_TRY(hipMemcpy(c->wrec, h_wrec.data(), sizeof(uint2) * h_wrec.size(), hipMemcpyHostToDevice));
         if (!h_light_short.empty()) HIP_TRY(hipMemcpy(c->light_short, h_light_short.data(), sizeof(int32_t) * h_light_short.size(), hipMemcpyHostToDevice));
         if (!h_light_long.empty()) HIP_TRY(hipMemcpy(c->light_long, h_light_long.data(), sizeof(int32_t) * h_light_long.size(), hipMemcpyHostToDevice));
     }
     SABER_TRY(dev_alloc(&c->doc_words, (size_t)D));
-    SABER_TRY(dev_alloc(&c->l3, ((size_t)V + 1) * (size_t)c->n3pad)); SABER_TRY(dev_alloc(&c->sumphi, (size_t)V + 1));
+    if (!par) { SABER_TRY(dev_alloc(&c->l3, ((size_t)V + 1) * (size_t)c->n3pad)); SABER_TRY(dev_alloc(&c->sumphi, (size_t)V + 1)); }
     SABER_TRY(dev_alloc(&c->counters, (size_t)kMaxTimedIters * kCtr));
     SABER_TRY(dev_alloc(&c->dense_slots, (size_t)kMaxTimedIters * kDenseSlots));
     SABER_TRY(dev_alloc(&c->ll_partial, (size_t)std::max<int64_t>(c->max_chunk_tiles, 1)));
@@ -572,8 +592,12 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     HIP_TRY(hipMemcpy(c->doc_ptr, doc_ptr, sizeof(int64_t) * ((size_t)D + 1), hipMemcpyHostToDevice));
     if (!h_short.empty()) HIP_TRY(hipMemcpy(c->short_docs, h_short.data(), sizeof(int32_t) * h_short.size(), hipMemcpyHostToDevice));
     if (!h_long.empty()) HIP_TRY(hipMemcpy(c->long_docs, h_long.data(), sizeof(int32_t) * h_long.size(), hipMemcpyHostToDevice));
-    hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for((int64_t)vk, 256, 8192)), dim3(256), 0, c->stream, (uint32_t *)c->cwk, 0u, vk);
-    HIP_TRY(hipGetLastError());
+    if (!par) {
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for((int64_t)vk, 256, 8192)), dim3(256), 0, c->stream, (uint32_t *)c->cwk, 0u, vk);
+        HIP_TRY(hipGetLastError());
+    }
+    c->stats.tokens = T; c->stats.tiles = c->total_tiles;
+    if (c->no_state) { HIP_TRY(hipStreamSynchronize(c->stream)); return SABER_OK; }
 
     // ---- iteration 0: Philox assignment, then the M-step ----
     if (T) {
@@ -586,16 +610,18 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
         HIP_TRY(hipGetLastError());
     }
     SABER_TRY(full_mstep(c));
+    if (par) return SABER_OK;
     SABER_TRY(refresh_workload_stats(c));
-    c->stats.tokens = T; c->stats.tiles = c->total_tiles;
     c->stats.words_present = 0;
     for (const Chunk &ch : c->chunks) c->stats.words_present += ch.words_present;
     c->stats.light_tokens = c->T_light;
     return SABER_OK;
 }
 
-extern "C" int saber_init_ex(saber_ctx **out, const int64_t *doc_ptr, const int32_t *word_ids, int64_t D, int32_t V,
-                             int32_t K, float alpha, float beta, uint64_t seed, const saber_options *opt_in) {
+// saber_init_ex, or with `parent` a context for held-out documents that borrows the parent's model
+static int create_ctx(saber_ctx **out, const int64_t *doc_ptr, const int32_t *word_ids, int64_t D, int32_t V,
+                      int32_t K, float alpha, float beta, uint64_t seed, const saber_options *opt_in,
+                      const saber_ctx *parent, bool no_state) {
     if (out) *out = nullptr;
     if (!out || !doc_ptr) return fail(SABER_EINVAL, "saber_init: null argument");
     if (D < 0 || V < 1 || K < 1) return fail(SABER_EINVAL, "saber_init: need D >= 0, V >= 1, K >= 1");
@@ -616,8 +642,9 @@ extern "C" int saber_init_ex(saber_ctx **out, const int64_t *doc_ptr, const int3
         if (word_ids[t] < 0 || word_ids[t] >= V)
             return fail(SABER_EINVAL, "saber_init: word id %d at token %lld is outside [0,%d)", word_ids[t], (long long)t, V);
     uint32_t bits = 1; while ((1u << bits) < (uint32_t)K) bits++;
-    const bool b16 = K <= 65536 && maxlen < 65536;   // the common case: topic and count both fit 16 bits
+    bool b16 = K <= 65536 && maxlen < 65536;   // the common case: topic and count both fit 16 bits
     if (b16) bits = 16;
+    if (parent) { b16 = parent->b16; bits = parent->topic_bits; }   // the model's sparse rows of B fix the packing
     if (maxlen >= (1ll << (32 - bits)))
         return fail(SABER_ERANGE, "saber_init: longest document (%lld tokens) does not fit the %u count bits left by K = %d",
                     (long long)maxlen, 32 - bits, K);
@@ -654,6 +681,7 @@ extern "C" int saber_init_ex(saber_ctx **out, const int64_t *doc_ptr, const int3
     saber_ctx *c = new (std::nothrow) saber_ctx();
     if (!c) return fail(SABER_ENOMEM, "saber_init: out of host memory");
     c->D = D; c->T = T; c->V = V; c->K = K; c->alpha = alpha; c->beta = beta; c->seed = seed; c->opt = opt;
+    c->parent = parent; c->no_state = no_state;
     c->Kpad = (K + 63) / 64 * 64;
     c->n3 = c->Kpad / 64;
     c->n3pad = (c->n3 + 63) / 64 * 64;
@@ -687,6 +715,11 @@ extern "C" int saber_init_ex(saber_ctx **out, const int64_t *doc_ptr, const int3
     if (rc != SABER_OK) { saber_free(c); return rc; }
     *out = c;
     return SABER_OK;
+}
+
+extern "C" int saber_init_ex(saber_ctx **out, const int64_t *doc_ptr, const int32_t *word_ids, int64_t D, int32_t V,
+                             int32_t K, float alpha, float beta, uint64_t seed, const saber_options *opt_in) {
+    return create_ctx(out, doc_ptr, word_ids, D, V, K, alpha, beta, seed, opt_in, nullptr, false);
 }
 
 extern "C" int saber_init(saber_ctx **out, const int64_t *doc_ptr, const int32_t *word_ids, int64_t D, int32_t V,
@@ -874,6 +907,86 @@ extern "C" int saber_loglik(saber_ctx *c, double *out) {
     } catch (const std::bad_alloc &) { return fail(SABER_ENOMEM, "saber_loglik: out of host memory"); }
     *out = (total - c->ll_const) / (double)c->T;
     return SABER_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// holdout log-likelihood (document completion on held-out documents, model frozen)
+// ------------------------------------------------------------------------------------------------
+// n E-steps + CountByDZ on a context that borrows a model: Alg. 1 restricted to A
+static int foldin_iterate(saber_ctx *c, int32_t n) {
+    for (int32_t i = 0; i < n; i++) {
+        c->iter++;
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for((int64_t)kDenseSlots * 2, 256)), dim3(256), 0, c->stream,
+                           (uint32_t *)c->dense_slots, 0u, (size_t)kDenseSlots * 2);
+        HIP_TRY(hipGetLastError());
+        for (const Chunk &ch : c->chunks) {
+            EStepParams p = make_params(c, ch);
+            p.n_dense = c->dense_slots;
+            SABER_TRY(launch_estep<MODE_SAMPLE>(c, ch, p));
+        }
+        SABER_TRY(launch_count_dz(c));
+    }
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    return SABER_OK;
+}
+
+extern "C" int saber_holdout_loglik(saber_ctx *m, const int64_t *doc_ptr, const int32_t *word_ids,
+                                    const uint8_t *observed, int64_t D, int32_t n_foldin, uint64_t seed,
+                                    const int32_t *z_init, int32_t *z_out, double *loglik, int64_t *n_scored) {
+    if (!m || !doc_ptr || !loglik || !n_scored || D < 0 || n_foldin < 0)
+        return fail(SABER_EINVAL, "saber_holdout_loglik: bad argument");
+    if (m->parent) return fail(SABER_EINVAL, "saber_holdout_loglik: the model must be a context made by saber_init");
+    if (doc_ptr[0] != 0) return fail(SABER_EINVAL, "saber_holdout_loglik: doc_ptr[0] must be 0");
+    for (int64_t d = 0; d < D; d++)
+        if (doc_ptr[d + 1] < doc_ptr[d]) return fail(SABER_EINVAL, "saber_holdout_loglik: doc_ptr decreases at document %lld", (long long)d);
+    const int64_t T = doc_ptr[D];
+    if (T > 0 && (!word_ids || !observed)) return fail(SABER_EINVAL, "saber_holdout_loglik: null token arrays");
+    saber_ctx *obs = nullptr, *scr = nullptr;
+    int rc = SABER_OK;
+    try {
+        // the observed part and the scored part as two corpora over the same documents
+        std::vector<int64_t> optr((size_t)D + 1, 0), sptr((size_t)D + 1, 0);
+        std::vector<int32_t> ow, sw;
+        ow.reserve((size_t)T / 2 + 1); sw.reserve((size_t)T / 2 + 1);
+        for (int64_t d = 0; d < D; d++) {
+            for (int64_t t = doc_ptr[d]; t < doc_ptr[d + 1]; t++) (observed[t] ? ow : sw).push_back(word_ids[t]);
+            optr[(size_t)d + 1] = (int64_t)ow.size(); sptr[(size_t)d + 1] = (int64_t)sw.size();
+        }
+        saber_options opt = m->opt;
+        opt.profile = 0; opt.n_chunks = 1;
+        rc = create_ctx(&obs, optr.data(), ow.data(), D, m->V, m->K, m->alpha, m->beta, seed, &opt, m, false);
+        if (rc == SABER_OK && z_init) rc = saber_set_z(obs, z_init, 0);
+        if (rc == SABER_OK) rc = foldin_iterate(obs, n_foldin);
+        if (rc == SABER_OK && z_out) rc = saber_get_z(obs, z_out);
+        if (rc == SABER_OK) rc = create_ctx(&scr, sptr.data(), sw.data(), D, m->V, m->K, m->alpha, m->beta, seed, &opt, m, true);
+        double total = 0.0;
+        if (rc == SABER_OK && scr->T > 0) {
+            std::vector<double> part;
+            for (const Chunk &ch : scr->chunks) {
+                if (ch.ntiles == 0) continue;
+                EStepParams p = make_params(scr, ch);
+                p.docrec = obs->docrec; p.cd_ent = obs->cd_ent;   // theta comes from the observed part
+                p.out_ll = scr->ll_partial;
+                if ((rc = launch_estep<MODE_LOGLIK>(scr, ch, p)) != SABER_OK) break;
+                hipError_t e = hipStreamSynchronize(scr->stream);
+                part.resize((size_t)ch.ntiles);
+                if (e == hipSuccess) e = hipMemcpy(part.data(), scr->ll_partial, sizeof(double) * (size_t)ch.ntiles, hipMemcpyDeviceToHost);
+                if (e != hipSuccess) { rc = fail(SABER_EDEVICE, "saber_holdout_loglik: %s", hipGetErrorString(e)); break; }
+                for (double v : part) total += v;   // fixed order: the result is reproducible
+            }
+            // the normaliser ln(L'_d + K alpha) of theta, once per scored token
+            for (int64_t d = 0; d < D; d++) {
+                const int64_t ns = sptr[(size_t)d + 1] - sptr[(size_t)d];
+                if (ns) total -= (double)ns * std::log((double)(optr[(size_t)d + 1] - optr[(size_t)d]) + (double)m->K * (double)m->alpha);
+            }
+        }
+        if (rc == SABER_OK) {
+            *n_scored = scr->T;
+            *loglik = scr->T > 0 ? total / (double)scr->T : 0.0;
+        }
+    } catch (const std::bad_alloc &) { rc = fail(SABER_ENOMEM, "saber_holdout_loglik: out of host memory"); }
+    saber_free(scr); saber_free(obs);
+    return rc;
 }
 
 extern "C" int saber_get_z(saber_ctx *c, int32_t *z) {

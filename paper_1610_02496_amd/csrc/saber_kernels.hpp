@@ -374,9 +374,10 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
     int bs = (tile.count + nwaves - 1) / nwaves;
     bs = bs > kWave ? kWave : bs;
 
-    for (;;) {
+    for (int round = 0;; round++) {
         int ticket = 0;
-        if (lane == 0) ticket = atomicAdd(&next_batch, 1);
+        if (MODE == MODE_LOGLIK) ticket = round * nwaves + wave;   // fixed assignment: the sums come out bit-identical every time
+        else if (lane == 0) ticket = atomicAdd(&next_batch, 1);
         const int batch = __builtin_amdgcn_readfirstlane(ticket) * bs;   // wave-uniform: loop control stays scalar
         if (batch >= tile.count) break;
         const int n = __builtin_amdgcn_readfirstlane(min(bs, tile.count - batch));   // wave-uniform by construction
