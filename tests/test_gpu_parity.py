@@ -267,3 +267,40 @@ def test_error_paths():
         g.token_probs(np.array([2]))
     with pytest.raises(pk.SaberError):
         pk.Saber(dp, w, 2, 3, 0.1, 0.01, 1, block_threads=100)
+
+
+# ------------------------------------------------------------------------------------------- does it learn
+def test_gpu_chain_recovers_planted_topics_and_generalises():
+    """The GPU path on its own (free-running, 120 iterations) on data drawn from the LDA process with 10 well
+    separated topics: the log-likelihood rises to the level of the planted assignment, the fitted topic-word
+    columns match the planted ones, and folding in half of each held-out document predicts the other half much
+    better than a uniform mixture does."""
+    from scipy.optimize import linear_sum_assignment
+    spec = corpusgen.CorpusSpec("rec", 800, 800, 64000, "poisson", 80.0, 0.0, 10, 1.1, 0.02, 0.1, 10, 1, 11)
+    full = corpusgen.generate(spec, nthreads=2)
+    D_train = 600
+    cut = int(full.doc_ptr[D_train])
+    dp, w = full.doc_ptr[:D_train + 1], full.word_ids[:cut]
+    pk = saber()
+    g = pk.Saber(dp, w, spec.V, 10, 0.1, 0.01, 5)
+    ll = [g.loglik()]
+    for _ in range(4):
+        g.iterate(30); ll.append(g.loglik())
+    assert all(b > a for a, b in zip(ll, ll[1:]))
+    truth = oracle.Model(dp, w, spec.V, 10, 0.1, 0.01, 5)
+    truth.set_z(full.true_topic[:cut])
+    assert ll[0] < truth.loglik() - 0.4 and abs(ll[-1] - truth.loglik()) < 0.06
+    phi, _ = g.get_phi(np.arange(spec.V, dtype=np.int32))
+    unit = lambda a: a / np.linalg.norm(a, axis=0, keepdims=True)
+    sim = unit(phi.astype(np.float64)).T @ unit(truth.phi.astype(np.float64))
+    r, cidx = linear_sum_assignment(-sim)
+    assert (sim[r, cidx] > 0.9).sum() >= 8
+    # held-out documents of the same planted model
+    hp = full.doc_ptr[D_train:] - cut; hw = full.word_ids[cut:]
+    pos = np.arange(hw.size) - np.repeat(hp[:-1], np.diff(hp))
+    mask = (pos % 2 == 0).astype(np.uint8)
+    uniform = g.holdout_loglik(hp, hw, np.zeros_like(mask), 0, 1)[0]
+    folded = [g.holdout_loglik(hp, hw, mask, n, 1)[0] for n in (0, 2, 20)]
+    assert folded[2] > folded[1] > folded[0] and folded[2] > uniform + 0.3
+    assert folded[2] < ll[-1] + 0.3
+    g.close(); truth.close()
