@@ -16,6 +16,7 @@
  */
 #include <math.h>
 #include <stdint.h>
+#include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
 #ifdef _OPENMP
@@ -161,11 +162,21 @@ int lda_corpus_fill(uint64_t seed, int64_t D, int32_t V, int32_t K_true, double 
         for (int32_t v = 0; v < V; v++) { run += exp(row[v] - mx); row[v] = run; }
     }
 
+    /* LDA_CORPUS_PROGRESS=n: report on stderr every time another n documents are done (long generations) */
+    const char *prog_env = getenv("LDA_CORPUS_PROGRESS");
+    const int64_t prog_every = prog_env ? atoll(prog_env) : 0;
+    int64_t docs_done = 0;
 #pragma omp parallel num_threads(nthreads)
     {
         double *theta = (double *)malloc(sizeof(double) * (size_t)K_true);
 #pragma omp for schedule(dynamic, 64)
         for (int64_t d = 0; d < D; d++) {
+            if (prog_every > 0) {
+                int64_t n;
+#pragma omp atomic capture
+                n = ++docs_done;
+                if (n % prog_every == 0) { fprintf(stderr, "[corpusgen] %lld of %lld documents\n", (long long)n, (long long)D); fflush(stderr); }
+            }
             int64_t b = doc_ptr[d], e = doc_ptr[d + 1];
             if (e <= b) continue;
             rng_t r; rng_seed(&r, seed, 3, (uint64_t)d);
