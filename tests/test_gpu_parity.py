@@ -92,6 +92,9 @@ def test_init_state_matches_oracle():
     assert st["nnz_cd"] == o.cd[0][-1] and st["tokens"] == c.T
     lens = np.diff(c.doc_ptr)
     assert st["next_row_entries"] == int((np.diff(o.cd[0]) * lens).sum())
+    # what the sampler has to fetch: a row once per (word, document) pair, i.e. K_d times the distinct words of d
+    U = np.array([np.unique(c.word_ids[a:b]).size for a, b in zip(c.doc_ptr[:-1], c.doc_ptr[1:])])
+    assert st["next_row_fetch"] == int((np.diff(o.cd[0]) * U).sum())
     # words with fewer than K/2 tokens keep their row of B sparse
     n_v = np.bincount(c.word_ids, minlength=c.spec.V)
     light = n_v < 50 // 2
