@@ -752,7 +752,7 @@ extern "C" int saber_iterate(saber_ctx *c, int32_t n) {
             hipEvent_t *ev = c->ev + (size_t)b * EV_PER_ITER;
             c->iter++;
             if (prof) HIP_TRY(hipEventRecord(ev[EV_BEGIN], c->stream));
-            // E-step: z <- Sample(A_d, Bhat_v, Q_v, T_v) for every token; B accumulates as a by-product
+            // E-step: z <- Sample(A_d, Bhat_v, Q_v, T_v) for every token, written in document order and in word order
             for (const Chunk &ch : c->chunks) {
                 EStepParams p = make_params(c, ch);
                 p.n_dense = c->dense_slots + (size_t)kDenseSlots * b;

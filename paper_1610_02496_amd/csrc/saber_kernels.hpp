@@ -590,6 +590,29 @@ __global__ void prefix_export_kernel(const float *rows, const double *l3_64, con
 // ---------------------------------------------------------------------------------------------
 struct VzItem { int32_t row; int32_t count; int64_t begin; };   // slab: count tokens from z_wm[begin] on
 
+// f(topic) for each of the n assignments at zs, the workgroup's threads sharing the work: 16-byte loads (8 or 4
+// assignments per lane and load) over the aligned middle, single loads for the unaligned head and the tail.
+// A one-assignment-per-load loop is bound by the latency of its dependent loads, not by bandwidth.
+template <typename ZT, typename F>
+__device__ __forceinline__ void block_for_each_z(const ZT *__restrict__ zs, int64_t n, F f) {
+    constexpr int kPer = 16 / (int)sizeof(ZT);
+    int64_t head = (int64_t)(((16u - (unsigned)(reinterpret_cast<uintptr_t>(zs) & 15u)) & 15u) / sizeof(ZT));
+    if (head > n) head = n;
+    for (int64_t i = threadIdx.x; i < head; i += blockDim.x) f((uint32_t)zs[i]);
+    const int64_t nvec = (n - head) / kPer;
+    const uint4 *__restrict__ v = reinterpret_cast<const uint4 *>(zs + head);
+    for (int64_t j = threadIdx.x; j < nvec; j += blockDim.x) {
+        const uint4 q = v[j];
+        if (sizeof(ZT) == 2) {
+            f(q.x & 0xffffu); f(q.x >> 16); f(q.y & 0xffffu); f(q.y >> 16);
+            f(q.z & 0xffffu); f(q.z >> 16); f(q.w & 0xffffu); f(q.w >> 16);
+        } else {
+            f(q.x); f(q.y); f(q.z); f(q.w);
+        }
+    }
+    for (int64_t i = head + nvec * kPer + threadIdx.x; i < n; i += blockDim.x) f((uint32_t)zs[i]);
+}
+
 template <typename ZT>
 __global__ void __launch_bounds__(1024) count_vz_kernel(const VzItem *items, const ZT *z_wm, int32_t *cwk, int K,
                                                         int Kpad, int use_lds) {
@@ -600,14 +623,14 @@ __global__ void __launch_bounds__(1024) count_vz_kernel(const VzItem *items, con
     if (use_lds) {
         for (int k = threadIdx.x; k < K; k += blockDim.x) vz_hist[k] = 0u;
         __syncthreads();
-        for (int i = threadIdx.x; i < it.count; i += blockDim.x) atomicAdd(&vz_hist[(uint32_t)zs[i]], 1u);
+        block_for_each_z(zs, (int64_t)it.count, [&](uint32_t k) { atomicAdd(&vz_hist[k], 1u); });
         __syncthreads();
         for (int k = threadIdx.x; k < K; k += blockDim.x) {
             const uint32_t h = vz_hist[k];
             if (h) atomicAdd(&row[k], (int)h);
         }
     } else {
-        for (int i = threadIdx.x; i < it.count; i += blockDim.x) atomicAdd(&row[(uint32_t)zs[i]], 1);
+        block_for_each_z(zs, (int64_t)it.count, [&](uint32_t k) { atomicAdd(&row[k], 1); });
     }
 }
 
@@ -621,11 +644,15 @@ __global__ void fill_zwm_kernel(const Tile *tiles, const uint32_t *tok_t, const 
 
 // ---------------------------------------------------------------------------------------------
 // Block-wide exclusive scan of one uint32 per thread; returns the exclusive prefix, *total = block sum.
-// scratch must hold blockDim.x/64 + 1 values.  Contains two __syncthreads().
+// scratch must hold blockDim.x/64 + 1 values.  Contains two __syncthreads() when the block has several wavefronts.
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *scratch, uint32_t *total) {
     const int lane = lane_id(), wave = threadIdx.x / kWave, nwaves = (blockDim.x + kWave - 1) / kWave;
     const uint32_t incl = wave_incl_scan(v);
+    if (blockDim.x <= kWave) {   // a single wavefront needs neither LDS nor barriers
+        *total = readlane_u32(incl, kWave - 1);
+        return incl - v;
+    }
     if (lane == kWave - 1) scratch[wave] = incl;
     __syncthreads();
     uint32_t off = 0, tot = 0;
@@ -660,10 +687,7 @@ __global__ void __launch_bounds__(1024) count_dz_kernel(const int32_t *doc_list,
 
     for (int w = threadIdx.x; w < nwords; w += blockDim.x) bitmap[w] = 0u;
     __syncthreads();
-    for (int i = threadIdx.x; i < len; i += blockDim.x) {
-        const uint32_t k = (uint32_t)zd[i];
-        atomicOr(&bitmap[k >> 5], 1u << (k & 31u));
-    }
+    block_for_each_z(zd, (int64_t)len, [&](uint32_t k) { atomicOr(&bitmap[k >> 5], 1u << (k & 31u)); });
     __syncthreads();
     // ranks: exclusive prefix of popcounts over the bitmap words
     uint32_t carry = 0;
@@ -686,12 +710,11 @@ __global__ void __launch_bounds__(1024) count_dz_kernel(const int32_t *doc_list,
         while (m) { const int b = __ffs((int)m) - 1; m &= m - 1u; ent[r++] = (uint32_t)(w * 32 + b); }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < len; i += blockDim.x) {
-        const uint32_t k = (uint32_t)zd[i];
+    block_for_each_z(zd, (int64_t)len, [&](uint32_t k) {
         const uint32_t wd = bitmap[k >> 5];
         const uint32_t r = wpre[k >> 5] + (uint32_t)__popc(wd & ((1u << (k & 31u)) - 1u));
         atomicAdd(&ent[r], 1u << topic_bits);
-    }
+    });
     __syncthreads();
     if (in_lds)
         for (int r = threadIdx.x; r < kd; r += blockDim.x) row[r] = ent_lds[r];
@@ -716,11 +739,11 @@ __global__ void topic_totals_kernel(const ZT *z, int64_t T, int64_t per_block, u
     if (use_lds) {
         for (int k = threadIdx.x; k < K; k += blockDim.x) hist[k] = 0u;
         __syncthreads();
-        for (int64_t t = b + threadIdx.x; t < e; t += blockDim.x) atomicAdd(&hist[(uint32_t)z[t]], 1u);
+        block_for_each_z(z + b, e - b, [&](uint32_t k) { atomicAdd(&hist[k], 1u); });
         __syncthreads();
         for (int k = threadIdx.x; k < K; k += blockDim.x) { const uint32_t h = hist[k]; if (h) atomicAdd(&ck[k], (unsigned long long)h); }
     } else {
-        for (int64_t t = b + threadIdx.x; t < e; t += blockDim.x) atomicAdd(&ck[(uint32_t)z[t]], 1ull);
+        block_for_each_z(z + b, e - b, [&](uint32_t k) { atomicAdd(&ck[k], 1ull); });
     }
 }
 
@@ -731,7 +754,7 @@ __global__ void topic_totals_kernel(const ZT *z, int64_t T, int64_t per_block, u
 //   l3[i]    = round32(l3_64[i])                                           -- tree level above the bottom, W = 64
 // Pad columns k in [K, Kpad) get Bhat = 0, so the last block's running sum is the row total.
 // The bottom level (one prefix sum per topic) is not stored; the sampler rebuilds the 64 entries it needs.
-// The row of B is cleared after it has been read, ready to accumulate the next E-step.
+// The row of B is cleared after it has been read, ready for the next CountByVZ.
 // ---------------------------------------------------------------------------------------------
 // Denominators of Eq. 2, one per topic: float(C_k) + float(V) * beta (the conversion rounds to nearest even).
 __global__ void denominators_kernel(const unsigned long long *ck, float *denom, int K, float vbeta) {
