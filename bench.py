@@ -166,6 +166,8 @@ def main():
     ap.add_argument("--stage-min", type=int, default=0)
     ap.add_argument("--light-block", type=int, default=0)
     ap.add_argument("--probe-bytes", type=int, default=1 << 30, help="size of the copy-bandwidth probe (0 = skip)")
+    ap.add_argument("--opt", action="append", default=[], metavar="NAME=INT",
+                    help="any other field of saber_options, for experiments (e.g. --opt dz_lds_entries=2048)")
     ap.add_argument("--holdout-docs", type=int, default=30000,
                     help="documents scored by the holdout log-likelihood after the timed region (0 = skip)")
     args = ap.parse_args()
@@ -191,6 +193,9 @@ def main():
     if args.chunks: opts["n_chunks"] = args.chunks
     if args.stage_min: opts["stage_min_tokens"] = args.stage_min
     if args.light_block: opts["light_block_threads"] = args.light_block
+    for kv in args.opt:
+        name, val = kv.split("=")
+        opts[name] = int(val)
 
     copy_gbs = None
     if args.probe_bytes:

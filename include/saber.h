@@ -58,7 +58,8 @@ typedef struct saber_options {
     int32_t profile;        /* 1: time every kernel group with HIP events (see saber_get_stats); default 0 */
     int32_t long_doc_tokens;/* documents longer than this use a 256-thread workgroup in CountByDZ; default 512 */
     int32_t dz_lds_entries; /* LDS capacity (entries) of one CountByDZ workgroup before it falls back to
-                               accumulating in the global row; default 8192 */
+                               accumulating in the global row; default 2048 (a larger buffer halves the
+                               workgroups a CU can hold) */
     int32_t stage_min_tokens;   /* tiles with at least this many tokens are launched with block_threads threads, smaller
                                    ones with light_block_threads; default 1 (one class) */
     int32_t light_block_threads;/* workgroup size for the smaller tiles; default: as block_threads */

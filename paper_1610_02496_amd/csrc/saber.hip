@@ -128,7 +128,7 @@ extern "C" void saber_options_default(saber_options *opt) {
     if (!opt) return;
     memset(opt, 0, sizeof(*opt));
     opt->n_chunks = 0; opt->block_threads = 0; opt->tile_tokens = 8192; opt->stage_phi = 1; opt->profile = 0;
-    opt->long_doc_tokens = 512; opt->dz_lds_entries = 8192; opt->stage_min_tokens = 0; opt->light_block_threads = 0; opt->light_word_tokens = 0;
+    opt->long_doc_tokens = 512; opt->dz_lds_entries = 2048; opt->stage_min_tokens = 0; opt->light_block_threads = 0; opt->light_word_tokens = 0;
 }
 
 extern "C" void saber_free(saber_ctx *c) {
