@@ -174,6 +174,25 @@ def test_mixed_row_lengths_in_one_tile():
     assert_estep_parity(g, o)
 
 
+def test_large_counts_in_a_row():
+    """Few topics and documents of 6,000 to 30,000 tokens: single entries of A with counts of many thousands next
+    to ordinary rows (16/16 packing is used up to its limit of 65,535 tokens per document)."""
+    rng = np.random.default_rng(5)
+    lens = np.r_[rng.integers(6000, 30000, 6), rng.integers(50, 300, 40)]
+    doc_ptr = np.r_[0, np.cumsum(lens)].astype(np.int64)
+    word_ids = rng.integers(0, 50, int(doc_ptr[-1])).astype(np.int32)
+    pk = saber()
+    for K in (3, 8):
+        g = pk.Saber(doc_ptr, word_ids, 50, K, 0.5, 0.01, 9)
+        o = oracle.Model(doc_ptr, word_ids, 50, K, 0.5, 0.01, 9)
+        assert o.cd[2].max() > 2048 and (o.cd[2] <= 2048).any()
+        assert_counts_equal(g, o)
+        assert_estep_parity(g, o)
+        assert_estep_parity(g, o)
+        assert abs(g.loglik() - o.loglik()) <= 1e-6 * abs(o.loglik())
+        g.close(); o.close()
+
+
 def test_empty_documents_and_single_tokens():
     doc_ptr = np.array([0, 0, 1, 1, 4, 4, 4, 9, 9], dtype=np.int64)
     word_ids = np.array([3, 0, 0, 2, 1, 1, 1, 3, 0], dtype=np.int32)
