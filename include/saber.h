@@ -54,7 +54,8 @@ typedef struct saber_options {
     int32_t block_threads;  /* threads per workgroup of the sampling kernel (multiple of 64 up to 1024);
                                default: the size that lets a CU hold the most wavefronts given the LDS the Bhat row takes */
     int32_t tile_tokens;    /* most tokens of one word handled by one workgroup; default 8192 */
-    int32_t stage_phi;      /* 1: keep the word's Bhat row in LDS when it fits, 0: always gather from global; default 1 */
+    int32_t stage_phi;      /* 1: keep the word's Bhat row in LDS when it fits (up to 150 KB: K <= 37,800), 0: always
+                               gather from global; default 1 */
     int32_t profile;        /* 1: time every kernel group with HIP events (see saber_get_stats); default 0 */
     int32_t long_doc_tokens;/* documents longer than this use a 256-thread workgroup in CountByDZ; default 512 */
     int32_t dz_lds_entries; /* LDS capacity (entries) of one CountByDZ workgroup before it falls back to

@@ -176,15 +176,23 @@ static size_t estep_lds_bytes(const saber_ctx *c, int mode) {
     return (c->staged ? estep_row_bytes(c) : 0) + 16 + (mode == MODE_LOGLIK ? 16 * sizeof(double) : 0);
 }
 
+// a workgroup may use more than the default 64 KB of LDS (up to the CU's 160 KB) once the kernel has been told so
+template <typename Kern>
+static void launch_with_lds(Kern kern, dim3 grid, dim3 block, size_t lds, hipStream_t stream, const EStepParams &p) {
+    if (lds > 64 * 1024)
+        (void)hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL(kern, grid, block, lds, stream, p);
+}
+
 template <int MODE, bool STAGED, typename ZT>
 static void launch_estep_b16(saber_ctx *c, dim3 grid, dim3 block, size_t lds, const EStepParams &p, bool light) {
     if (light) {   // light words exist only in the staged, 16-bit-z configuration
-        if (c->b16) hipLaunchKernelGGL((estep_kernel<MODE, true, uint16_t, true, true>), grid, block, lds, c->stream, p);
-        else hipLaunchKernelGGL((estep_kernel<MODE, true, uint16_t, false, true>), grid, block, lds, c->stream, p);
+        if (c->b16) launch_with_lds(estep_kernel<MODE, true, uint16_t, true, true>, grid, block, lds, c->stream, p);
+        else launch_with_lds(estep_kernel<MODE, true, uint16_t, false, true>, grid, block, lds, c->stream, p);
         return;
     }
-    if (c->b16) hipLaunchKernelGGL((estep_kernel<MODE, STAGED, ZT, true, false>), grid, block, lds, c->stream, p);
-    else hipLaunchKernelGGL((estep_kernel<MODE, STAGED, ZT, false, false>), grid, block, lds, c->stream, p);
+    if (c->b16) launch_with_lds(estep_kernel<MODE, STAGED, ZT, true, false>, grid, block, lds, c->stream, p);
+    else launch_with_lds(estep_kernel<MODE, STAGED, ZT, false, false>, grid, block, lds, c->stream, p);
 }
 
 // The staged 16/16 sampler addresses its Bhat row from LDS address 0: its kernels must have no static LDS in
@@ -693,7 +701,12 @@ static int create_ctx(saber_ctx **out, const int64_t *doc_ptr, const int32_t *wo
     c->nwords = (K + 31) / 32;
     c->topic_bits = bits; c->topic_mask = (1u << bits) - 1u;
     c->z16 = K <= 65536;
-    c->staged = opt.stage_phi && estep_row_bytes(c) <= 60 * 1024;
+    // the word's Bhat row is staged in LDS when it fits a workgroup's share: up to 150 KB of the CU's 160 KB
+    int lds_per_cu = 0;
+    if (hipDeviceGetAttribute(&lds_per_cu, hipDeviceAttributeMaxSharedMemoryPerMultiprocessor, 0) != hipSuccess || lds_per_cu <= 0)
+        lds_per_cu = 64 * 1024;
+    const size_t stage_limit = std::min<size_t>(150 * 1024, (size_t)lds_per_cu > 10 * 1024 ? (size_t)lds_per_cu - 10 * 1024 : 0);
+    c->staged = opt.stage_phi && estep_row_bytes(c) <= std::max<size_t>(stage_limit, 54 * 1024);
     if (opt_in == nullptr || opt_in->block_threads <= 0) {
         // automatic workgroup size: the one that lets a CU hold the most wavefronts given the LDS footprint
         // (LDS is handed out in 512-byte pieces; a CU holds at most 32 wavefronts); ties go to the smaller size

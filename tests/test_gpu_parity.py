@@ -122,6 +122,9 @@ def test_philox_seed_and_64bit_seed():
     (1000, {"light_word_tokens": 1 << 20}),      # every word keeps a sparse row of B
     (1000, {"light_word_tokens": 40, "n_chunks": 3, "tile_tokens": 16, "long_doc_tokens": 16, "dz_lds_entries": 8}),
     (130, {"light_word_tokens": 1 << 20}),
+    (20000, {}),                                 # Bhat row of 80 KB in LDS: two workgroups per CU
+    (37000, {"light_word_tokens": 300}),         # 148 KB: one workgroup per CU; above that the row stays in global memory
+    (40000, {}),                                 # not staged
 ])
 def test_one_estep_from_random_state(K, opts):
     c = corpusgen.tiny(30 + K % 7, 400, 900, 25, 70.0)
