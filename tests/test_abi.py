@@ -45,6 +45,10 @@ def test_validation_happens_before_any_device_work():
     with pytest.raises(pk.SaberError) as e:
         pk.Saber(dp, np.array([0, 1], dtype=np.int32), 2, 1 << 20, 0.1, 0.01, 1)
     assert e.value.code == pk.binding.SABER_ERANGE
+    # K = 262144 needs 18 topic bits, which leaves 14 bits for a count: a document of 2^14 tokens is refused
+    with pytest.raises(pk.SaberError) as e:
+        pk.Saber(np.array([0, 1 << 14], dtype=np.int64), np.zeros(1 << 14, dtype=np.int32), 2, 262144, 0.1, 0.01, 1)
+    assert e.value.code == pk.binding.SABER_ERANGE and "count bits" in str(e.value)
 
 
 def test_no_gpu_fails_loudly():

@@ -196,6 +196,32 @@ def test_large_counts_in_a_row():
         g.close(); o.close()
 
 
+def test_document_longer_than_16_bit_counts():
+    """A document of 65,536 tokens or more no longer fits 16-bit counts: entries of A are then packed with just
+    enough topic bits for K and the rest for the count, and the kernels take the shifts at run time.  K = 50 keeps
+    every word dense, K = 1000 makes about half of the words light (sparse rows of B with the same packing)."""
+    rng = np.random.default_rng(6)
+    lens = np.r_[70000, rng.integers(40, 400, 30), 66000, rng.integers(40, 400, 30)]
+    doc_ptr = np.r_[0, np.cumsum(lens)].astype(np.int64)
+    word_ids = rng.integers(0, 300, int(doc_ptr[-1])).astype(np.int32)
+    word_ids[:70000] = rng.integers(0, 12, 70000)          # the long document leans on a few words: large counts
+    pk = saber()
+    for K in (50, 1000):
+        g = pk.Saber(doc_ptr, word_ids, 300, K, 0.5, 0.01, 4)
+        o = oracle.Model(doc_ptr, word_ids, 300, K, 0.5, 0.01, 4)
+        assert (g.get_stats()["light_words_present"] > 0) == (K == 1000)
+        assert_counts_equal(g, o)
+        assert_estep_parity(g, o)
+        # concentrate the long documents on two topics: single counts above 65,535 would not fit 16 bits
+        z = o.z.copy(); z[:70000] = np.where(np.arange(70000) % 16 == 0, 1, 0)
+        g.set_z(z, 1); o.set_z(z, 1)
+        assert o.cd[2].max() > 65535
+        assert_counts_equal(g, o)
+        assert_estep_parity(g, o)
+        assert abs(g.loglik() - o.loglik()) <= 1e-6 * abs(o.loglik())
+        g.close(); o.close()
+
+
 def test_empty_documents_and_single_tokens():
     doc_ptr = np.array([0, 0, 1, 1, 4, 4, 4, 9, 9], dtype=np.int64)
     word_ids = np.array([3, 0, 0, 2, 1, 1, 1, 3, 0], dtype=np.int32)
