@@ -67,7 +67,13 @@ typedef struct saber_options {
     int32_t light_word_tokens;  /* words with fewer tokens than this keep their row of B sparse (rebuilt by a segmented
                                    count, like a row of A) and their Bhat row is formed in LDS from a base vector and
                                    the non-zeros; default K/2; negative: every word keeps a dense row */
-    int32_t reserved[6];
+    int32_t stream_workers;     /* 0 (default): the token arrays of every chunk stay in device memory.  1..8: they stay in
+                                   pinned host memory and each chunk is copied into one of this many device buffers for
+                                   its sampling pass, its assignments going back to the host afterwards (the host
+                                   streaming of Sec. 3.1.2 with this many workers): copies of one chunk overlap the
+                                   sampling of another once there are two.  For corpora beyond device memory: only
+                                   2 bytes per token and the rows of A stay resident.  Results are the same. */
+    int32_t reserved[5];
 } saber_options;
 
 /* Sums over the iterations run since the last saber_reset_stats.  The ms_* fields need profile=1. */

@@ -44,7 +44,11 @@ struct Chunk {
     // tiles of the chunk: [0, n_dense) belong to words with dense B rows, sorted by size, the first n_heavy of
     // them forming the class of large tiles; [n_dense, ntiles) belong to light words (sparse B rows)
     int64_t n_heavy = 0, n_dense = 0;
+    // the chunk's documents inside the (ascending) lists of short and of long documents
+    int64_t short0 = 0, nshort = 0, long0 = 0, nlong = 0;
 };
+
+constexpr int kMaxSlots = 8;
 
 constexpr int kMaxTimedIters = 32;
 constexpr int kCtr = 8;   // device counters per timed iteration
@@ -109,6 +113,17 @@ struct saber_ctx {
     bool have_events = false;
     saber_stats stats{};
     std::vector<int64_t> doc_len;     // host copy of the document lengths (statistics only)
+    // Host streaming (Sec. 3.1.2), n_slots > 0: tok_doc, tok_t and z live in pinned host memory; a chunk's part of
+    // them is copied into one of n_slots device buffers for the chunk's pass and its new assignments are copied
+    // back.  z_wm (2 bytes per token) and the rows of A stay in device memory.  Copies run on two streams of their
+    // own (one per direction) and are ordered against the compute stream with events per buffer.
+    int n_slots = 0, next_slot = 0;
+    int64_t slot_tokens = 0;
+    int32_t *h_tok_doc = nullptr; uint32_t *h_tok_t = nullptr; void *h_z = nullptr;
+    int32_t *slot_tok_doc[kMaxSlots] = {}; uint32_t *slot_tok_t[kMaxSlots] = {}; void *slot_z[kMaxSlots] = {};
+    hipStream_t s_in = nullptr, s_out = nullptr;
+    hipEvent_t ev_loaded[kMaxSlots] = {}, ev_computed[kMaxSlots] = {}, ev_done[kMaxSlots] = {};
+    bool slot_used[kMaxSlots] = {};
 };
 
 template <typename T>
@@ -144,6 +159,17 @@ extern "C" void saber_free(saber_ctx *c) {
         dev_free(c->vz_items);
     }
     if (c->have_events) for (auto &e : c->ev) if (e) (void)hipEventDestroy(e);
+    if (c->s_in) { (void)hipStreamSynchronize(c->s_in); (void)hipStreamDestroy(c->s_in); }
+    if (c->s_out) { (void)hipStreamSynchronize(c->s_out); (void)hipStreamDestroy(c->s_out); }
+    for (int s = 0; s < kMaxSlots; s++) {
+        dev_free(c->slot_tok_doc[s]); dev_free(c->slot_tok_t[s]); dev_free(c->slot_z[s]);
+        if (c->ev_loaded[s]) (void)hipEventDestroy(c->ev_loaded[s]);
+        if (c->ev_computed[s]) (void)hipEventDestroy(c->ev_computed[s]);
+        if (c->ev_done[s]) (void)hipEventDestroy(c->ev_done[s]);
+    }
+    if (c->h_tok_doc) (void)hipHostFree(c->h_tok_doc);
+    if (c->h_tok_t) (void)hipHostFree(c->h_tok_t);
+    if (c->h_z) (void)hipHostFree(c->h_z);
     if (c->stream) (void)hipStreamDestroy(c->stream);
     delete c;
 }
@@ -151,13 +177,22 @@ extern "C" void saber_free(saber_ctx *c) {
 // ------------------------------------------------------------------------------------------------
 // launch helpers
 // ------------------------------------------------------------------------------------------------
-static EStepParams make_params(saber_ctx *c, const Chunk &ch) {
+// The assignments as the kernels index them, by canonical token number: the resident array, or for a chunk held
+// in a buffer the address at which token t0 of the chunk is the buffer's first element.
+static void *z_view(const saber_ctx *c, const Chunk &ch, int slot) {
+    if (slot < 0) return c->z;
+    const uintptr_t zs = c->z16 ? 2 : 4;
+    return reinterpret_cast<void *>(reinterpret_cast<uintptr_t>(c->slot_z[slot]) - (uintptr_t)ch.t0 * zs);
+}
+
+static EStepParams make_params(saber_ctx *c, const Chunk &ch, int slot = -1) {
     EStepParams p{};
     p.tiles = c->tiles + ch.tile0;
-    p.tok_doc = c->tok_doc + ch.t0; p.tok_t = c->tok_t + ch.t0;
+    if (slot < 0) { p.tok_doc = c->tok_doc + ch.t0; p.tok_t = c->tok_t + ch.t0; }
+    else { p.tok_doc = c->slot_tok_doc[slot]; p.tok_t = c->slot_tok_t[slot]; }
     p.docrec = c->docrec; p.cd_ent = c->cd_ent;
     p.phi = c->phi; p.l3 = c->l3; p.l3_64 = c->l3_64; p.sumphi = c->sumphi;
-    p.z = c->z;
+    p.z = z_view(c, ch, slot);
     p.base = c->phi + (size_t)c->V_dense * (size_t)c->Kpad;
     p.wrec = c->wrec; p.lw_ent = c->lw_ent; p.lw_phi = c->lw_phi; p.z_wm = c->z_wm;
     p.t_base = ch.t0; p.K = c->K; p.Kpad = c->Kpad; p.n3 = c->n3; p.n3pad = c->n3pad;
@@ -285,6 +320,50 @@ static int launch_count_dz(saber_ctx *c) {
                                   c->cd_ent);
 }
 
+// CountByDZ for the documents of one chunk whose assignments sit in a buffer
+static int launch_count_dz_chunk(saber_ctx *c, const Chunk &ch, int slot) {
+    return launch_segmented_count(c, c->short_docs + ch.short0, ch.nshort, c->long_docs + ch.long0, ch.nlong, c->doc_ptr,
+                                  z_view(c, ch, slot), c->docrec, c->cd_ent);
+}
+
+// ---- host streaming ----
+// Takes the next buffer (round robin) for chunk `ch`: once the buffer's previous user is finished with it, the
+// chunk's token arrays (and with_z: its assignments) are copied in, and the compute stream is made to wait for them.
+static int stream_acquire(saber_ctx *c, const Chunk &ch, bool with_tok, bool with_z, int *slot) {
+    const int s = c->next_slot;
+    c->next_slot = (c->next_slot + 1) % c->n_slots;
+    if (ch.ntok > c->slot_tokens) return fail(SABER_ESTATE, "chunk of %lld tokens exceeds the streaming buffers", (long long)ch.ntok);
+    if (c->slot_used[s]) HIP_TRY(hipStreamWaitEvent(c->s_in, c->ev_done[s], 0));
+    const size_t n = (size_t)ch.ntok, zs = c->z16 ? 2 : 4;
+    if (with_tok && n) {
+        HIP_TRY(hipMemcpyAsync(c->slot_tok_doc[s], c->h_tok_doc + ch.t0, n * sizeof(int32_t), hipMemcpyHostToDevice, c->s_in));
+        HIP_TRY(hipMemcpyAsync(c->slot_tok_t[s], c->h_tok_t + ch.t0, n * sizeof(uint32_t), hipMemcpyHostToDevice, c->s_in));
+    }
+    if (with_z && n)
+        HIP_TRY(hipMemcpyAsync(c->slot_z[s], (const char *)c->h_z + (size_t)ch.t0 * zs, n * zs, hipMemcpyHostToDevice, c->s_in));
+    HIP_TRY(hipEventRecord(c->ev_loaded[s], c->s_in));
+    HIP_TRY(hipStreamWaitEvent(c->stream, c->ev_loaded[s], 0));
+    *slot = s;
+    return SABER_OK;
+}
+// After the chunk's kernels have been queued: z_out copies the buffer's assignments to the host copy of z; the
+// buffer may be taken again once that is done.
+static int stream_release(saber_ctx *c, const Chunk &ch, int s, bool z_out) {
+    HIP_TRY(hipEventRecord(c->ev_computed[s], c->stream));
+    HIP_TRY(hipStreamWaitEvent(c->s_out, c->ev_computed[s], 0));
+    const size_t zs = c->z16 ? 2 : 4;
+    if (z_out && ch.ntok)
+        HIP_TRY(hipMemcpyAsync((char *)c->h_z + (size_t)ch.t0 * zs, c->slot_z[s], (size_t)ch.ntok * zs, hipMemcpyDeviceToHost, c->s_out));
+    HIP_TRY(hipEventRecord(c->ev_done[s], c->s_out));
+    c->slot_used[s] = true;
+    return SABER_OK;
+}
+static int sync_all(saber_ctx *c) {
+    HIP_TRY(hipStreamSynchronize(c->stream));
+    if (c->n_slots) { HIP_TRY(hipStreamSynchronize(c->s_in)); HIP_TRY(hipStreamSynchronize(c->s_out)); }
+    return SABER_OK;
+}
+
 // CountByVZ + Preprocess + BuildTree for the light words (sparse rows of B); needs the base vector, i.e. runs
 // after launch_phi
 static int launch_light_words(saber_ctx *c) {
@@ -323,12 +402,15 @@ static int launch_topic_totals(saber_ctx *c) {
     const int64_t per_block = 65536;
     const int64_t nblocks = (c->T + per_block - 1) / per_block;
     const size_t lds = use_lds ? (size_t)c->K * 4 : 0;
+    // a histogram of all assignments: their order does not matter, and with host streaming the word-major copy is
+    // the one that is resident
+    const void *zsrc = c->n_slots ? c->z_wm : c->z;
     if (c->z16)
         hipLaunchKernelGGL((topic_totals_kernel<uint16_t>), dim3((unsigned)nblocks), dim3(256), lds, c->stream,
-                           (const uint16_t *)c->z, c->T, per_block, c->ck, c->K, use_lds);
+                           (const uint16_t *)zsrc, c->T, per_block, c->ck, c->K, use_lds);
     else
         hipLaunchKernelGGL((topic_totals_kernel<int32_t>), dim3((unsigned)nblocks), dim3(256), lds, c->stream,
-                           (const int32_t *)c->z, c->T, per_block, c->ck, c->K, use_lds);
+                           (const int32_t *)zsrc, c->T, per_block, c->ck, c->K, use_lds);
     HIP_TRY(hipGetLastError());
     return SABER_OK;
 }
@@ -343,17 +425,21 @@ static int launch_phi(saber_ctx *c) {
 }
 
 // Word-major copy of z (after init / set_z; an E-step writes it itself).
+static int launch_fill_zwm_chunk(saber_ctx *c, const Chunk &ch, int slot) {
+    if (ch.ntiles == 0) return SABER_OK;
+    const uint32_t *tok_t = slot < 0 ? c->tok_t + ch.t0 : c->slot_tok_t[slot];
+    const void *z = z_view(c, ch, slot);
+    if (c->z16)
+        hipLaunchKernelGGL((fill_zwm_kernel<uint16_t>), dim3((unsigned)ch.ntiles), dim3(256), 0, c->stream,
+                           c->tiles + ch.tile0, tok_t, (const uint16_t *)z, ch.t0, (uint16_t *)c->z_wm);
+    else
+        hipLaunchKernelGGL((fill_zwm_kernel<int32_t>), dim3((unsigned)ch.ntiles), dim3(256), 0, c->stream,
+                           c->tiles + ch.tile0, tok_t, (const int32_t *)z, ch.t0, (int32_t *)c->z_wm);
+    HIP_TRY(hipGetLastError());
+    return SABER_OK;
+}
 static int launch_fill_zwm(saber_ctx *c) {
-    for (const Chunk &ch : c->chunks) {
-        if (ch.ntiles == 0) continue;
-        if (c->z16)
-            hipLaunchKernelGGL((fill_zwm_kernel<uint16_t>), dim3((unsigned)ch.ntiles), dim3(256), 0, c->stream,
-                               c->tiles + ch.tile0, c->tok_t + ch.t0, (const uint16_t *)c->z, ch.t0, (uint16_t *)c->z_wm);
-        else
-            hipLaunchKernelGGL((fill_zwm_kernel<int32_t>), dim3((unsigned)ch.ntiles), dim3(256), 0, c->stream,
-                               c->tiles + ch.tile0, c->tok_t + ch.t0, (const int32_t *)c->z, ch.t0, (int32_t *)c->z_wm);
-        HIP_TRY(hipGetLastError());
-    }
+    for (const Chunk &ch : c->chunks) SABER_TRY(launch_fill_zwm_chunk(c, ch, -1));
     return SABER_OK;
 }
 
@@ -376,17 +462,27 @@ static int launch_count_vz(saber_ctx *c) {
 
 // The M-step after the assignments changed outside an E-step: all four rebuilds of Alg. 1.
 static int full_mstep(saber_ctx *c) {
-    SABER_TRY(launch_count_dz(c));
+    if (c->n_slots) {   // chunk by chunk from the host copy of z: rows of A and the word-major copy
+        for (const Chunk &ch : c->chunks) {
+            int s;
+            SABER_TRY(stream_acquire(c, ch, true, true, &s));
+            SABER_TRY(launch_count_dz_chunk(c, ch, s));
+            SABER_TRY(launch_fill_zwm_chunk(c, ch, s));
+            SABER_TRY(stream_release(c, ch, s, false));
+        }
+    } else {
+        SABER_TRY(launch_count_dz(c));
+    }
     if (c->parent) {   // held-out documents: A only, the model stays frozen
         HIP_TRY(hipStreamSynchronize(c->stream));
         return SABER_OK;
     }
-    SABER_TRY(launch_fill_zwm(c));
+    if (!c->n_slots) SABER_TRY(launch_fill_zwm(c));
     SABER_TRY(launch_count_vz(c));
     SABER_TRY(launch_topic_totals(c));
     SABER_TRY(launch_phi(c));
     SABER_TRY(launch_light_words(c));
-    HIP_TRY(hipStreamSynchronize(c->stream));
+    SABER_TRY(sync_all(c));
     return SABER_OK;
 }
 
@@ -400,6 +496,19 @@ static int refresh_workload_stats(saber_ctx *c) {
     HIP_TRY(hipMemcpy(h, c->counters, sizeof(h), hipMemcpyDeviceToHost));
     c->stats.nnz_cd = (int64_t)h[1]; c->stats.next_row_entries = (int64_t)h[2]; c->stats.next_row_fetch = (int64_t)h[3];
     c->stats.next_light_entries = (int64_t)h[4];
+    return SABER_OK;
+}
+
+// iteration 0: the Philox draw of Alg. 1's initialisation for the canonical tokens [t0, t1); z is indexed by token
+static int launch_init_z(saber_ctx *c, void *z, int64_t t0, int64_t t1) {
+    if (t1 <= t0) return SABER_OK;
+    if (c->z16)
+        hipLaunchKernelGGL((init_z_kernel<uint16_t>), dim3(grid_for(t1 - t0, 256, 8192)), dim3(256), 0, c->stream,
+                           (uint16_t *)z, t0, t1, (uint32_t)c->K, (uint32_t)c->seed, (uint32_t)(c->seed >> 32));
+    else
+        hipLaunchKernelGGL((init_z_kernel<int32_t>), dim3(grid_for(t1 - t0, 256, 8192)), dim3(256), 0, c->stream,
+                           (int32_t *)z, t0, t1, (uint32_t)c->K, (uint32_t)c->seed, (uint32_t)(c->seed >> 32));
+    HIP_TRY(hipGetLastError());
     return SABER_OK;
 }
 
@@ -484,8 +593,20 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
         }
         c->n_vz_items = (int64_t)h_vz_items.size();
     }
-    std::vector<int32_t> h_tok_doc((size_t)std::max<int64_t>(T, 1));
-    std::vector<uint32_t> h_tok_t((size_t)std::max<int64_t>(T, 1));
+    // the word-major token arrays: ordinary host memory on the way to the device, or with host streaming the
+    // pinned arrays that stay
+    std::vector<int32_t> v_tok_doc; std::vector<uint32_t> v_tok_t;
+    int32_t *h_tok_doc; uint32_t *h_tok_t;
+    if (c->n_slots) {
+        const size_t zs = c->z16 ? 2 : 4, n = (size_t)std::max<int64_t>(T, 1);
+        HIP_TRY(hipHostMalloc((void **)&c->h_tok_doc, n * sizeof(int32_t), hipHostMallocDefault));
+        HIP_TRY(hipHostMalloc((void **)&c->h_tok_t, n * sizeof(uint32_t), hipHostMallocDefault));
+        HIP_TRY(hipHostMalloc(&c->h_z, n * zs, hipHostMallocDefault));
+        h_tok_doc = c->h_tok_doc; h_tok_t = c->h_tok_t;
+    } else {
+        v_tok_doc.resize((size_t)std::max<int64_t>(T, 1)); v_tok_t.resize((size_t)std::max<int64_t>(T, 1));
+        h_tok_doc = v_tok_doc.data(); h_tok_t = v_tok_t.data();
+    }
     std::vector<Tile> h_tiles;
     std::vector<int64_t> wcount((size_t)V + 1);
     const int tile_tokens = c->opt.tile_tokens;
@@ -551,11 +672,31 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     }
     c->ll_const = llc; c->cd_cap = units * 32;
     c->n_short = (int64_t)h_short.size(); c->n_long = (int64_t)h_long.size();
+    for (Chunk &ch : c->chunks) {   // both lists ascend by document: a chunk's documents are a contiguous part of each
+        ch.short0 = std::lower_bound(h_short.begin(), h_short.end(), (int32_t)ch.d0) - h_short.begin();
+        ch.nshort = (std::lower_bound(h_short.begin(), h_short.end(), (int32_t)std::min<int64_t>(ch.d1, 0x7fffffff)) - h_short.begin()) - ch.short0;
+        ch.long0 = std::lower_bound(h_long.begin(), h_long.end(), (int32_t)ch.d0) - h_long.begin();
+        ch.nlong = (std::lower_bound(h_long.begin(), h_long.end(), (int32_t)std::min<int64_t>(ch.d1, 0x7fffffff)) - h_long.begin()) - ch.long0;
+        c->slot_tokens = std::max(c->slot_tokens, ch.ntok);
+    }
 
     // ---- device memory ----
     const size_t vk = ((size_t)c->V_dense + 1) * (size_t)c->Kpad;
-    if (c->z16) SABER_TRY(dev_alloc((uint16_t **)&c->z, (size_t)T)); else SABER_TRY(dev_alloc((int32_t **)&c->z, (size_t)T));
-    SABER_TRY(dev_alloc(&c->tok_doc, (size_t)T)); SABER_TRY(dev_alloc(&c->tok_t, (size_t)T));
+    if (c->n_slots) {
+        HIP_TRY(hipStreamCreateWithFlags(&c->s_in, hipStreamNonBlocking));
+        HIP_TRY(hipStreamCreateWithFlags(&c->s_out, hipStreamNonBlocking));
+        for (int s = 0; s < c->n_slots; s++) {
+            SABER_TRY(dev_alloc(&c->slot_tok_doc[s], (size_t)c->slot_tokens)); SABER_TRY(dev_alloc(&c->slot_tok_t[s], (size_t)c->slot_tokens));
+            if (c->z16) SABER_TRY(dev_alloc((uint16_t **)&c->slot_z[s], (size_t)c->slot_tokens));
+            else SABER_TRY(dev_alloc((int32_t **)&c->slot_z[s], (size_t)c->slot_tokens));
+            HIP_TRY(hipEventCreateWithFlags(&c->ev_loaded[s], hipEventDisableTiming));
+            HIP_TRY(hipEventCreateWithFlags(&c->ev_computed[s], hipEventDisableTiming));
+            HIP_TRY(hipEventCreateWithFlags(&c->ev_done[s], hipEventDisableTiming));
+        }
+    } else {
+        if (c->z16) SABER_TRY(dev_alloc((uint16_t **)&c->z, (size_t)T)); else SABER_TRY(dev_alloc((int32_t **)&c->z, (size_t)T));
+        SABER_TRY(dev_alloc(&c->tok_doc, (size_t)T)); SABER_TRY(dev_alloc(&c->tok_t, (size_t)T));
+    }
     SABER_TRY(dev_alloc(&c->tiles, h_tiles.size())); SABER_TRY(dev_alloc(&c->docrec, (size_t)D));
     SABER_TRY(dev_alloc(&c->cd_ent, (size_t)c->cd_cap)); SABER_TRY(dev_alloc(&c->doc_ptr, (size_t)D + 1));
     SABER_TRY(dev_alloc(&c->short_docs, h_short.size())); SABER_TRY(dev_alloc(&c->long_docs, h_long.size()));
@@ -590,9 +731,9 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     SABER_TRY(dev_alloc(&c->counters, (size_t)kMaxTimedIters * kCtr));
     SABER_TRY(dev_alloc(&c->dense_slots, (size_t)kMaxTimedIters * kDenseSlots));
     SABER_TRY(dev_alloc(&c->ll_partial, (size_t)std::max<int64_t>(c->max_chunk_tiles, 1)));
-    if (T) {
-        HIP_TRY(hipMemcpy(c->tok_doc, h_tok_doc.data(), sizeof(int32_t) * (size_t)T, hipMemcpyHostToDevice));
-        HIP_TRY(hipMemcpy(c->tok_t, h_tok_t.data(), sizeof(uint32_t) * (size_t)T, hipMemcpyHostToDevice));
+    if (T && !c->n_slots) {
+        HIP_TRY(hipMemcpy(c->tok_doc, h_tok_doc, sizeof(int32_t) * (size_t)T, hipMemcpyHostToDevice));
+        HIP_TRY(hipMemcpy(c->tok_t, h_tok_t, sizeof(uint32_t) * (size_t)T, hipMemcpyHostToDevice));
     }
     if (!h_tiles.empty()) HIP_TRY(hipMemcpy(c->tiles, h_tiles.data(), sizeof(Tile) * h_tiles.size(), hipMemcpyHostToDevice));
     if (D) HIP_TRY(hipMemcpy(c->docrec, h_rec.data(), sizeof(uint2) * (size_t)D, hipMemcpyHostToDevice));
@@ -608,14 +749,16 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     if (c->no_state) { HIP_TRY(hipStreamSynchronize(c->stream)); return SABER_OK; }
 
     // ---- iteration 0: Philox assignment, then the M-step ----
-    if (T) {
-        if (c->z16)
-            hipLaunchKernelGGL((init_z_kernel<uint16_t>), dim3(grid_for(T, 256, 8192)), dim3(256), 0, c->stream,
-                               (uint16_t *)c->z, T, (uint32_t)K, (uint32_t)c->seed, (uint32_t)(c->seed >> 32));
-        else
-            hipLaunchKernelGGL((init_z_kernel<int32_t>), dim3(grid_for(T, 256, 8192)), dim3(256), 0, c->stream,
-                               (int32_t *)c->z, T, (uint32_t)K, (uint32_t)c->seed, (uint32_t)(c->seed >> 32));
-        HIP_TRY(hipGetLastError());
+    if (c->n_slots) {   // the same draw chunk by chunk, into the host copy of z
+        for (const Chunk &ch : c->chunks) {
+            int s;
+            SABER_TRY(stream_acquire(c, ch, false, false, &s));
+            SABER_TRY(launch_init_z(c, z_view(c, ch, s), ch.t0, ch.t0 + ch.ntok));
+            SABER_TRY(stream_release(c, ch, s, true));
+        }
+        SABER_TRY(sync_all(c));
+    } else if (T) {
+        SABER_TRY(launch_init_z(c, c->z, 0, T));
     }
     SABER_TRY(full_mstep(c));
     if (par) return SABER_OK;
@@ -667,6 +810,7 @@ static int create_ctx(saber_ctx **out, const int64_t *doc_ptr, const int32_t *wo
         if (opt_in->stage_min_tokens > 0) opt.stage_min_tokens = opt_in->stage_min_tokens;
         if (opt_in->light_block_threads > 0) opt.light_block_threads = opt_in->light_block_threads;
         opt.light_word_tokens = opt_in->light_word_tokens;
+        opt.stream_workers = opt_in->stream_workers;
         opt.stage_phi = opt_in->stage_phi; opt.profile = opt_in->profile;
         if (opt_in->stage_phi < 0) opt.stage_phi = 1;
     }
@@ -676,6 +820,9 @@ static int create_ctx(saber_ctx **out, const int64_t *doc_ptr, const int32_t *wo
     if (opt.light_block_threads > 0 && (opt.light_block_threads % 64 || opt.light_block_threads > 1024))
         return fail(SABER_EINVAL, "saber_init: light_block_threads must be a multiple of 64 in [64,1024]");
     if (opt.stage_min_tokens <= 0) opt.stage_min_tokens = 1;
+    if (opt.stream_workers < 0 || opt.stream_workers > kMaxSlots)
+        return fail(SABER_EINVAL, "saber_init: stream_workers must be in [0,%d]", kMaxSlots);
+    if (parent) opt.stream_workers = 0;   // held-out documents are few: always resident
     if (opt.light_word_tokens == 0) opt.light_word_tokens = std::max(1, K / 2);   // < 0 keeps every word dense
     // automatic: chunks of at most 128 M tokens.  The sampling pass of a chunk reads every row of A of the chunk once
     // per word of the document; at about 0.4 non-zeros per token these rows (4 bytes per entry) then fit the 256 MB
@@ -694,6 +841,7 @@ static int create_ctx(saber_ctx **out, const int64_t *doc_ptr, const int32_t *wo
     if (!c) return fail(SABER_ENOMEM, "saber_init: out of host memory");
     c->D = D; c->T = T; c->V = V; c->K = K; c->alpha = alpha; c->beta = beta; c->seed = seed; c->opt = opt;
     c->parent = parent; c->no_state = no_state;
+    c->n_slots = opt.stream_workers;
     c->Kpad = (K + 63) / 64 * 64;
     c->n3 = c->Kpad / 64;
     c->n3pad = (c->n3 + 63) / 64 * 64;
@@ -767,13 +915,21 @@ extern "C" int saber_iterate(saber_ctx *c, int32_t n) {
             if (prof) HIP_TRY(hipEventRecord(ev[EV_BEGIN], c->stream));
             // E-step: z <- Sample(A_d, Bhat_v, Q_v, T_v) for every token, written in document order and in word order
             for (const Chunk &ch : c->chunks) {
-                EStepParams p = make_params(c, ch);
+                int s = -1;
+                if (c->n_slots) SABER_TRY(stream_acquire(c, ch, true, false, &s));
+                EStepParams p = make_params(c, ch, s);
                 p.n_dense = c->dense_slots + (size_t)kDenseSlots * b;
                 SABER_TRY(launch_estep<MODE_SAMPLE>(c, ch, p));
+                if (c->n_slots) {
+                    // the chunk's rows of A are rebuilt while its new assignments are still on the device; the
+                    // sampling of later chunks reads other documents' rows only
+                    SABER_TRY(launch_count_dz_chunk(c, ch, s));
+                    SABER_TRY(stream_release(c, ch, s, true));
+                }
             }
             if (prof) HIP_TRY(hipEventRecord(ev[EV_SAMPLE], c->stream));
             // M-step
-            SABER_TRY(launch_count_dz(c));
+            if (!c->n_slots) SABER_TRY(launch_count_dz(c));
             if (prof) HIP_TRY(hipEventRecord(ev[EV_DZ], c->stream));
             SABER_TRY(launch_topic_totals(c));
             if (prof) HIP_TRY(hipEventRecord(ev[EV_CK], c->stream));
@@ -786,7 +942,7 @@ extern "C" int saber_iterate(saber_ctx *c, int32_t n) {
             HIP_TRY(hipGetLastError());
             SABER_TRY(launch_row_stats(c, c->counters + kCtr * b + 1));
         }
-        HIP_TRY(hipStreamSynchronize(c->stream));
+        SABER_TRY(sync_all(c));
         unsigned long long h[kMaxTimedIters * kCtr];
         HIP_TRY(hipMemcpy(h, c->counters, sizeof(h), hipMemcpyDeviceToHost));
         for (int b = 0; b < batch; b++) {
@@ -913,9 +1069,12 @@ extern "C" int saber_loglik(saber_ctx *c, double *out) {
         std::vector<double> part;
         for (const Chunk &ch : c->chunks) {
             if (ch.ntiles == 0) continue;
-            EStepParams p = make_params(c, ch);
+            int s = -1;
+            if (c->n_slots) SABER_TRY(stream_acquire(c, ch, true, false, &s));
+            EStepParams p = make_params(c, ch, s);
             p.out_ll = c->ll_partial;
             SABER_TRY(launch_estep<MODE_LOGLIK>(c, ch, p));
+            if (c->n_slots) SABER_TRY(stream_release(c, ch, s, false));
             HIP_TRY(hipStreamSynchronize(c->stream));
             part.resize((size_t)ch.ntiles);
             HIP_TRY(hipMemcpy(part.data(), c->ll_partial, sizeof(double) * (size_t)ch.ntiles, hipMemcpyDeviceToHost));
@@ -1009,6 +1168,12 @@ extern "C" int saber_holdout_loglik(saber_ctx *m, const int64_t *doc_ptr, const 
 extern "C" int saber_get_z(saber_ctx *c, int32_t *z) {
     if (!c || !z) return fail(SABER_EINVAL, "saber_get_z: null argument");
     if (c->T == 0) return SABER_OK;
+    if (c->n_slots) {   // the host copy is complete once the copy streams are idle
+        SABER_TRY(sync_all(c));
+        if (c->z16) { const uint16_t *h = (const uint16_t *)c->h_z; for (int64_t t = 0; t < c->T; t++) z[t] = (int32_t)h[t]; }
+        else memcpy(z, c->h_z, sizeof(int32_t) * (size_t)c->T);
+        return SABER_OK;
+    }
     if (!c->z16) { HIP_TRY(hipMemcpy(z, c->z, sizeof(int32_t) * (size_t)c->T, hipMemcpyDeviceToHost)); return SABER_OK; }
     int32_t *tmp = nullptr;
     SABER_TRY(dev_alloc(&tmp, (size_t)c->T));
@@ -1026,7 +1191,11 @@ extern "C" int saber_set_z(saber_ctx *c, const int32_t *z, uint32_t iter) {
     if (!c || (!z && c->T)) return fail(SABER_EINVAL, "saber_set_z: null argument");
     for (int64_t t = 0; t < c->T; t++)
         if (z[t] < 0 || z[t] >= c->K) return fail(SABER_EINVAL, "saber_set_z: topic %d at token %lld is outside [0,%d)", z[t], (long long)t, c->K);
-    if (c->T) {
+    if (c->T && c->n_slots) {
+        SABER_TRY(sync_all(c));
+        if (c->z16) { uint16_t *h = (uint16_t *)c->h_z; for (int64_t t = 0; t < c->T; t++) h[t] = (uint16_t)z[t]; }
+        else memcpy(c->h_z, z, sizeof(int32_t) * (size_t)c->T);
+    } else if (c->T) {
         int32_t *tmp = nullptr;
         SABER_TRY(dev_alloc(&tmp, (size_t)c->T));
         hipError_t e = hipMemcpy(tmp, z, sizeof(int32_t) * (size_t)c->T, hipMemcpyHostToDevice);
@@ -1064,9 +1233,12 @@ extern "C" int saber_token_probs(saber_ctx *c, const int64_t *tok, int64_t m, fl
     if ((rc = dev_alloc(&dS, (size_t)c->T)) || (rc = dev_alloc(&dQ, (size_t)c->T)) || (rc = dev_alloc(&gS, (size_t)m)) ||
         (rc = dev_alloc(&gQ, (size_t)m)) || (rc = dev_alloc(&dtok, (size_t)m))) { cleanup(); return rc; }
     for (const Chunk &ch : c->chunks) {
-        EStepParams p = make_params(c, ch);
+        int s = -1;
+        if (c->n_slots && (rc = stream_acquire(c, ch, true, false, &s))) { cleanup(); return rc; }
+        EStepParams p = make_params(c, ch, s);
         p.out_S = dS; p.out_Q = dQ;
         if ((rc = launch_estep<MODE_PROBS>(c, ch, p))) { cleanup(); return rc; }
+        if (c->n_slots && (rc = stream_release(c, ch, s, false))) { cleanup(); return rc; }
     }
     std::vector<float> hS((size_t)m), hQ((size_t)m);
     hipError_t e = hipMemcpyAsync(dtok, tok, sizeof(int64_t) * (size_t)m, hipMemcpyHostToDevice, c->stream);

@@ -126,9 +126,9 @@ __global__ void fill_u32_kernel(uint32_t *p, uint32_t value, size_t n) {
 }
 
 template <typename ZT>
-__global__ void init_z_kernel(ZT *z, int64_t T, uint32_t K, uint32_t seed_lo, uint32_t seed_hi) {
-    int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (int64_t)gridDim.x * blockDim.x;
-    for (; t < T; t += stride) {
+__global__ void init_z_kernel(ZT *z, int64_t t0, int64_t t1, uint32_t K, uint32_t seed_lo, uint32_t seed_hi) {
+    int64_t t = t0 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (int64_t)gridDim.x * blockDim.x;
+    for (; t < t1; t += stride) {
         Rand2 r = philox_token(seed_lo, seed_hi, (uint64_t)t, 0u);
         z[t] = (ZT)__umulhi(r.r0, K);   // floor(word0 * K / 2^32)
     }
