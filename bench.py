@@ -132,6 +132,25 @@ def run_gpu(corpus, K, steps, warmup, opts, holdout_docs=0):
     return res
 
 
+def run_streaming(corpus, K, steps, warmup, workers, chunks):
+    """Host streaming (Sec. 3.1.2): the same iterations with the token lists in pinned host memory, `workers`
+    device buffers and `chunks` document chunks; 4 bytes per token and iteration cross the host link."""
+    import torch
+    import paper_1610_02496_amd as pk
+    s = corpus.spec
+    g = pk.Saber(corpus.doc_ptr, corpus.word_ids, s.V, K, 50.0 / K, s.beta, s.seed, stream_workers=workers, n_chunks=chunks)
+    g.iterate(warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    g.iterate(steps)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    res = {"workers": workers, "chunks": chunks, "tokens_per_s": corpus.T * steps / dt, "ms_per_step": dt * 1e3 / steps,
+           "host_link_bytes_per_token": 4, "host_link_gbs": 4.0 * corpus.T * steps / dt / 1e9, "loglik": g.loglik()}
+    g.close()
+    return res
+
+
 def run_cpu_baseline(corpus, K, docs, threads):
     """The oracle, as it stands, on a document prefix of the same corpus: one full iteration (E-step + M-step)."""
     import oracle
@@ -168,6 +187,8 @@ def main():
     ap.add_argument("--probe-bytes", type=int, default=1 << 30, help="size of the copy-bandwidth probe (0 = skip)")
     ap.add_argument("--opt", action="append", default=[], metavar="NAME=INT",
                     help="any other field of saber_options, for experiments (e.g. --opt dz_lds_entries=2048)")
+    ap.add_argument("--streaming", default="3:4", metavar="WORKERS:CHUNKS",
+                    help="also time the iterations with host streaming in this configuration ('' = skip)")
     ap.add_argument("--holdout-docs", type=int, default=30000,
                     help="documents scored by the holdout log-likelihood after the timed region (0 = skip)")
     args = ap.parse_args()
@@ -211,6 +232,12 @@ def main():
     if args.workload == "C3" and not args.no_also:
         also = run_gpu(corpus, 1000, args.steps, args.warmup, opts)
         log("[bench] K=1000: %s" % json.dumps(also))
+    streaming = None
+    if args.streaming and not opts:
+        w, nch = (int(x) for x in args.streaming.split(":"))
+        streaming = run_streaming(corpus, spec.K, args.steps, args.warmup, w, nch)
+        streaming["vs_resident"] = streaming["tokens_per_s"] / main_res["tokens_per_s"]
+        log("[bench] host streaming: %s" % json.dumps(streaming))
     cpu = None
     if not args.no_cpu_baseline:
         cpu = run_cpu_baseline(corpus, spec.K, args.cpu_docs, 1)
@@ -229,6 +256,8 @@ def main():
     }
     if "holdout" in main_res:
         out["holdout"] = main_res["holdout"]
+    if streaming is not None:
+        out["streaming"] = streaming
     if also is not None:
         out["also"] = also
     print(json.dumps(out), flush=True)

@@ -67,12 +67,16 @@ typedef struct saber_options {
     int32_t light_word_tokens;  /* words with fewer tokens than this keep their row of B sparse (rebuilt by a segmented
                                    count, like a row of A) and their Bhat row is formed in LDS from a base vector and
                                    the non-zeros; default K/2; negative: every word keeps a dense row */
-    int32_t stream_workers;     /* 0 (default): the token arrays of every chunk stay in device memory.  1..8: they stay in
-                                   pinned host memory and each chunk is copied into one of this many device buffers for
-                                   its sampling pass, its assignments going back to the host afterwards (the host
-                                   streaming of Sec. 3.1.2 with this many workers): copies of one chunk overlap the
-                                   sampling of another once there are two.  For corpora beyond device memory: only
-                                   2 bytes per token and the rows of A stay resident.  Results are the same. */
+    int32_t stream_workers;     /* 0 (default): the token arrays of every chunk stay in device memory.  1..8: host
+                                   streaming (Sec. 3.1.2) with this many workers: the chunks' token lists stay in
+                                   pinned host memory (4 bytes per token) and each chunk is copied into one of this
+                                   many device buffers for its pass, so that with two or more the copy of one chunk
+                                   overlaps the sampling of another (three hide it reliably).  The chunk's rows of A
+                                   are rebuilt right after its sampling, while its new assignments are in the
+                                   buffer; resident are the rows of A and 2 bytes per token (the word-major
+                                   assignments), which is what lets a corpus several times the device memory run.
+                                   Results are the same.  With profile=1, ms_sample then covers the whole chunk loop
+                                   (copies waited for, sampling, CountByDZ) and ms_count_dz is zero. */
     int32_t reserved[5];
 } saber_options;
 

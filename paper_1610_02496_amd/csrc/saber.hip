@@ -113,16 +113,21 @@ struct saber_ctx {
     bool have_events = false;
     saber_stats stats{};
     std::vector<int64_t> doc_len;     // host copy of the document lengths (statistics only)
-    // Host streaming (Sec. 3.1.2), n_slots > 0: tok_doc, tok_t and z live in pinned host memory; a chunk's part of
-    // them is copied into one of n_slots device buffers for the chunk's pass and its new assignments are copied
-    // back.  z_wm (2 bytes per token) and the rows of A stay in device memory.  Copies run on two streams of their
-    // own (one per direction) and are ordered against the compute stream with events per buffer.
+    // Host streaming (Sec. 3.1.2), n_slots > 0: tok_t lives in pinned host memory; a chunk's part of it is copied
+    // into one of n_slots device buffers for the chunk's pass (4 bytes per token and iteration over the host link).
+    // The rest is derived or kept on the device: the chunk's tok_doc follows from doc_ptr (doc_coarse, the document
+    // of every 64th token, bounds the search to a step or two); its assignments in document order exist only in the
+    // buffer, between the sampling kernel that writes them and the CountByDZ that turns them into rows of A, and
+    // are re-created from the word-major copy when asked for; z_wm (2 bytes per token) and the rows of A are
+    // resident.  Copies run on a stream of their own and are ordered against the compute stream with two events
+    // per buffer.
     int n_slots = 0, next_slot = 0;
     int64_t slot_tokens = 0;
-    int32_t *h_tok_doc = nullptr; uint32_t *h_tok_t = nullptr; void *h_z = nullptr;
+    uint32_t *h_tok_t = nullptr;
+    int32_t *doc_coarse = nullptr;    // [T/64 + 2] document of token 64 j (of the last token beyond the end)
     int32_t *slot_tok_doc[kMaxSlots] = {}; uint32_t *slot_tok_t[kMaxSlots] = {}; void *slot_z[kMaxSlots] = {};
-    hipStream_t s_in = nullptr, s_out = nullptr;
-    hipEvent_t ev_loaded[kMaxSlots] = {}, ev_computed[kMaxSlots] = {}, ev_done[kMaxSlots] = {};
+    hipStream_t s_in = nullptr;
+    hipEvent_t ev_loaded[kMaxSlots] = {}, ev_done[kMaxSlots] = {};
     bool slot_used[kMaxSlots] = {};
 };
 
@@ -160,16 +165,13 @@ extern "C" void saber_free(saber_ctx *c) {
     }
     if (c->have_events) for (auto &e : c->ev) if (e) (void)hipEventDestroy(e);
     if (c->s_in) { (void)hipStreamSynchronize(c->s_in); (void)hipStreamDestroy(c->s_in); }
-    if (c->s_out) { (void)hipStreamSynchronize(c->s_out); (void)hipStreamDestroy(c->s_out); }
     for (int s = 0; s < kMaxSlots; s++) {
         dev_free(c->slot_tok_doc[s]); dev_free(c->slot_tok_t[s]); dev_free(c->slot_z[s]);
         if (c->ev_loaded[s]) (void)hipEventDestroy(c->ev_loaded[s]);
-        if (c->ev_computed[s]) (void)hipEventDestroy(c->ev_computed[s]);
         if (c->ev_done[s]) (void)hipEventDestroy(c->ev_done[s]);
     }
-    if (c->h_tok_doc) (void)hipHostFree(c->h_tok_doc);
+    dev_free(c->doc_coarse);
     if (c->h_tok_t) (void)hipHostFree(c->h_tok_t);
-    if (c->h_z) (void)hipHostFree(c->h_z);
     if (c->stream) (void)hipStreamDestroy(c->stream);
     delete c;
 }
@@ -327,40 +329,32 @@ static int launch_count_dz_chunk(saber_ctx *c, const Chunk &ch, int slot) {
 }
 
 // ---- host streaming ----
-// Takes the next buffer (round robin) for chunk `ch`: once the buffer's previous user is finished with it, the
-// chunk's token arrays (and with_z: its assignments) are copied in, and the compute stream is made to wait for them.
-static int stream_acquire(saber_ctx *c, const Chunk &ch, bool with_tok, bool with_z, int *slot) {
+// Takes the next buffer (round robin) for chunk `ch`: once the kernels of the buffer's previous user have run, the
+// chunk's tok_t is copied in, the compute stream is made to wait for it, and tok_doc is derived.
+static int stream_acquire(saber_ctx *c, const Chunk &ch, int *slot) {
     const int s = c->next_slot;
     c->next_slot = (c->next_slot + 1) % c->n_slots;
     if (ch.ntok > c->slot_tokens) return fail(SABER_ESTATE, "chunk of %lld tokens exceeds the streaming buffers", (long long)ch.ntok);
     if (c->slot_used[s]) HIP_TRY(hipStreamWaitEvent(c->s_in, c->ev_done[s], 0));
-    const size_t n = (size_t)ch.ntok, zs = c->z16 ? 2 : 4;
-    if (with_tok && n) {
-        HIP_TRY(hipMemcpyAsync(c->slot_tok_doc[s], c->h_tok_doc + ch.t0, n * sizeof(int32_t), hipMemcpyHostToDevice, c->s_in));
-        HIP_TRY(hipMemcpyAsync(c->slot_tok_t[s], c->h_tok_t + ch.t0, n * sizeof(uint32_t), hipMemcpyHostToDevice, c->s_in));
-    }
-    if (with_z && n)
-        HIP_TRY(hipMemcpyAsync(c->slot_z[s], (const char *)c->h_z + (size_t)ch.t0 * zs, n * zs, hipMemcpyHostToDevice, c->s_in));
+    *slot = s;
+    if (ch.ntok == 0) return SABER_OK;
+    HIP_TRY(hipMemcpyAsync(c->slot_tok_t[s], c->h_tok_t + ch.t0, (size_t)ch.ntok * sizeof(uint32_t), hipMemcpyHostToDevice, c->s_in));
     HIP_TRY(hipEventRecord(c->ev_loaded[s], c->s_in));
     HIP_TRY(hipStreamWaitEvent(c->stream, c->ev_loaded[s], 0));
-    *slot = s;
+    hipLaunchKernelGGL(expand_tok_doc_kernel, dim3(grid_for(ch.ntok, 256)), dim3(256), 0, c->stream, c->slot_tok_t[s],
+                       ch.ntok, ch.t0, c->doc_coarse, c->doc_ptr, c->slot_tok_doc[s]);
+    HIP_TRY(hipGetLastError());
     return SABER_OK;
 }
-// After the chunk's kernels have been queued: z_out copies the buffer's assignments to the host copy of z; the
-// buffer may be taken again once that is done.
-static int stream_release(saber_ctx *c, const Chunk &ch, int s, bool z_out) {
-    HIP_TRY(hipEventRecord(c->ev_computed[s], c->stream));
-    HIP_TRY(hipStreamWaitEvent(c->s_out, c->ev_computed[s], 0));
-    const size_t zs = c->z16 ? 2 : 4;
-    if (z_out && ch.ntok)
-        HIP_TRY(hipMemcpyAsync((char *)c->h_z + (size_t)ch.t0 * zs, c->slot_z[s], (size_t)ch.ntok * zs, hipMemcpyDeviceToHost, c->s_out));
-    HIP_TRY(hipEventRecord(c->ev_done[s], c->s_out));
+// After the chunk's kernels have been queued: the buffer may be overwritten once they have run.
+static int stream_release(saber_ctx *c, int s) {
+    HIP_TRY(hipEventRecord(c->ev_done[s], c->stream));
     c->slot_used[s] = true;
     return SABER_OK;
 }
 static int sync_all(saber_ctx *c) {
     HIP_TRY(hipStreamSynchronize(c->stream));
-    if (c->n_slots) { HIP_TRY(hipStreamSynchronize(c->s_in)); HIP_TRY(hipStreamSynchronize(c->s_out)); }
+    if (c->n_slots) HIP_TRY(hipStreamSynchronize(c->s_in));
     return SABER_OK;
 }
 
@@ -460,15 +454,43 @@ static int launch_count_vz(saber_ctx *c) {
     return SABER_OK;
 }
 
+// iteration 0: the Philox draw of Alg. 1's initialisation for the canonical tokens [t0, t1); z is indexed by token
+static int launch_init_z(saber_ctx *c, void *z, int64_t t0, int64_t t1) {
+    if (t1 <= t0) return SABER_OK;
+    if (c->z16)
+        hipLaunchKernelGGL((init_z_kernel<uint16_t>), dim3(grid_for(t1 - t0, 256, 8192)), dim3(256), 0, c->stream,
+                           (uint16_t *)z, t0, t1, (uint32_t)c->K, (uint32_t)c->seed, (uint32_t)(c->seed >> 32));
+    else
+        hipLaunchKernelGGL((init_z_kernel<int32_t>), dim3(grid_for(t1 - t0, 256, 8192)), dim3(256), 0, c->stream,
+                           (int32_t *)z, t0, t1, (uint32_t)c->K, (uint32_t)c->seed, (uint32_t)(c->seed >> 32));
+    HIP_TRY(hipGetLastError());
+    return SABER_OK;
+}
+
 // The M-step after the assignments changed outside an E-step: all four rebuilds of Alg. 1.
-static int full_mstep(saber_ctx *c) {
-    if (c->n_slots) {   // chunk by chunk from the host copy of z: rows of A and the word-major copy
+// With host streaming the assignments are not on the device: they come chunk by chunk from user_z, or when that
+// is null from the Philox draw of iteration 0.
+static int full_mstep(saber_ctx *c, const int32_t *user_z = nullptr) {
+    if (c->n_slots) {   // chunk by chunk: rows of A and the word-major copy
+        std::vector<uint16_t> stage;
         for (const Chunk &ch : c->chunks) {
             int s;
-            SABER_TRY(stream_acquire(c, ch, true, true, &s));
+            SABER_TRY(stream_acquire(c, ch, &s));
+            if (user_z && ch.ntok) {
+                HIP_TRY(hipStreamSynchronize(c->stream));   // the buffer's earlier kernels are done: plain copy
+                const void *src = user_z + ch.t0;
+                if (c->z16) {
+                    stage.resize((size_t)ch.ntok);
+                    for (int64_t i = 0; i < ch.ntok; i++) stage[(size_t)i] = (uint16_t)user_z[ch.t0 + i];
+                    src = stage.data();
+                }
+                HIP_TRY(hipMemcpy(c->slot_z[s], src, (size_t)ch.ntok * (c->z16 ? 2 : 4), hipMemcpyHostToDevice));
+            } else {
+                SABER_TRY(launch_init_z(c, z_view(c, ch, s), ch.t0, ch.t0 + ch.ntok));
+            }
             SABER_TRY(launch_count_dz_chunk(c, ch, s));
             SABER_TRY(launch_fill_zwm_chunk(c, ch, s));
-            SABER_TRY(stream_release(c, ch, s, false));
+            SABER_TRY(stream_release(c, s));
         }
     } else {
         SABER_TRY(launch_count_dz(c));
@@ -496,19 +518,6 @@ static int refresh_workload_stats(saber_ctx *c) {
     HIP_TRY(hipMemcpy(h, c->counters, sizeof(h), hipMemcpyDeviceToHost));
     c->stats.nnz_cd = (int64_t)h[1]; c->stats.next_row_entries = (int64_t)h[2]; c->stats.next_row_fetch = (int64_t)h[3];
     c->stats.next_light_entries = (int64_t)h[4];
-    return SABER_OK;
-}
-
-// iteration 0: the Philox draw of Alg. 1's initialisation for the canonical tokens [t0, t1); z is indexed by token
-static int launch_init_z(saber_ctx *c, void *z, int64_t t0, int64_t t1) {
-    if (t1 <= t0) return SABER_OK;
-    if (c->z16)
-        hipLaunchKernelGGL((init_z_kernel<uint16_t>), dim3(grid_for(t1 - t0, 256, 8192)), dim3(256), 0, c->stream,
-                           (uint16_t *)z, t0, t1, (uint32_t)c->K, (uint32_t)c->seed, (uint32_t)(c->seed >> 32));
-    else
-        hipLaunchKernelGGL((init_z_kernel<int32_t>), dim3(grid_for(t1 - t0, 256, 8192)), dim3(256), 0, c->stream,
-                           (int32_t *)z, t0, t1, (uint32_t)c->K, (uint32_t)c->seed, (uint32_t)(c->seed >> 32));
-    HIP_TRY(hipGetLastError());
     return SABER_OK;
 }
 
@@ -598,11 +607,9 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     std::vector<int32_t> v_tok_doc; std::vector<uint32_t> v_tok_t;
     int32_t *h_tok_doc; uint32_t *h_tok_t;
     if (c->n_slots) {
-        const size_t zs = c->z16 ? 2 : 4, n = (size_t)std::max<int64_t>(T, 1);
-        HIP_TRY(hipHostMalloc((void **)&c->h_tok_doc, n * sizeof(int32_t), hipHostMallocDefault));
+        const size_t n = (size_t)std::max<int64_t>(T, 1);
         HIP_TRY(hipHostMalloc((void **)&c->h_tok_t, n * sizeof(uint32_t), hipHostMallocDefault));
-        HIP_TRY(hipHostMalloc(&c->h_z, n * zs, hipHostMallocDefault));
-        h_tok_doc = c->h_tok_doc; h_tok_t = c->h_tok_t;
+        h_tok_doc = nullptr; h_tok_t = c->h_tok_t;   // tok_doc is derived on the device
     } else {
         v_tok_doc.resize((size_t)std::max<int64_t>(T, 1)); v_tok_t.resize((size_t)std::max<int64_t>(T, 1));
         h_tok_doc = v_tok_doc.data(); h_tok_t = v_tok_t.data();
@@ -628,7 +635,8 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
         for (int64_t d = ch.d0; d < ch.d1; d++)
             for (int64_t t = doc_ptr[d]; t < doc_ptr[d + 1]; t++) {
                 const int64_t pos = ch.t0 + wcount[(size_t)word_ids[t]]++;
-                h_tok_doc[(size_t)pos] = (int32_t)d; h_tok_t[(size_t)pos] = (uint32_t)(t - ch.t0);
+                if (h_tok_doc) h_tok_doc[(size_t)pos] = (int32_t)d;
+                h_tok_t[(size_t)pos] = (uint32_t)(t - ch.t0);
             }
         // tiles of dense-row words first, then those of light words; inside each group heavy tiles first so the
         // tail of a launch is made of small ones (Sec. 3.4)
@@ -684,15 +692,24 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     const size_t vk = ((size_t)c->V_dense + 1) * (size_t)c->Kpad;
     if (c->n_slots) {
         HIP_TRY(hipStreamCreateWithFlags(&c->s_in, hipStreamNonBlocking));
-        HIP_TRY(hipStreamCreateWithFlags(&c->s_out, hipStreamNonBlocking));
         for (int s = 0; s < c->n_slots; s++) {
             SABER_TRY(dev_alloc(&c->slot_tok_doc[s], (size_t)c->slot_tokens)); SABER_TRY(dev_alloc(&c->slot_tok_t[s], (size_t)c->slot_tokens));
             if (c->z16) SABER_TRY(dev_alloc((uint16_t **)&c->slot_z[s], (size_t)c->slot_tokens));
             else SABER_TRY(dev_alloc((int32_t **)&c->slot_z[s], (size_t)c->slot_tokens));
             HIP_TRY(hipEventCreateWithFlags(&c->ev_loaded[s], hipEventDisableTiming));
-            HIP_TRY(hipEventCreateWithFlags(&c->ev_computed[s], hipEventDisableTiming));
             HIP_TRY(hipEventCreateWithFlags(&c->ev_done[s], hipEventDisableTiming));
         }
+        std::vector<int32_t> coarse((size_t)(T / 64 + 2), 0);
+        int64_t d = 0, last = 0;
+        for (int64_t dd = 0; dd < D; dd++) if (doc_ptr[dd + 1] > doc_ptr[dd]) last = dd;
+        for (size_t j = 0; j < coarse.size(); j++) {
+            const int64_t t = (int64_t)j * 64;
+            if (t >= T) { coarse[j] = (int32_t)last; continue; }
+            while (doc_ptr[d + 1] <= t) d++;
+            coarse[j] = (int32_t)d;
+        }
+        SABER_TRY(dev_alloc(&c->doc_coarse, coarse.size()));
+        HIP_TRY(hipMemcpy(c->doc_coarse, coarse.data(), sizeof(int32_t) * coarse.size(), hipMemcpyHostToDevice));
     } else {
         if (c->z16) SABER_TRY(dev_alloc((uint16_t **)&c->z, (size_t)T)); else SABER_TRY(dev_alloc((int32_t **)&c->z, (size_t)T));
         SABER_TRY(dev_alloc(&c->tok_doc, (size_t)T)); SABER_TRY(dev_alloc(&c->tok_t, (size_t)T));
@@ -749,17 +766,7 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     if (c->no_state) { HIP_TRY(hipStreamSynchronize(c->stream)); return SABER_OK; }
 
     // ---- iteration 0: Philox assignment, then the M-step ----
-    if (c->n_slots) {   // the same draw chunk by chunk, into the host copy of z
-        for (const Chunk &ch : c->chunks) {
-            int s;
-            SABER_TRY(stream_acquire(c, ch, false, false, &s));
-            SABER_TRY(launch_init_z(c, z_view(c, ch, s), ch.t0, ch.t0 + ch.ntok));
-            SABER_TRY(stream_release(c, ch, s, true));
-        }
-        SABER_TRY(sync_all(c));
-    } else if (T) {
-        SABER_TRY(launch_init_z(c, c->z, 0, T));
-    }
+    if (!c->n_slots) SABER_TRY(launch_init_z(c, c->z, 0, T));   // with host streaming: chunk by chunk, in full_mstep
     SABER_TRY(full_mstep(c));
     if (par) return SABER_OK;
     SABER_TRY(refresh_workload_stats(c));
@@ -916,15 +923,15 @@ extern "C" int saber_iterate(saber_ctx *c, int32_t n) {
             // E-step: z <- Sample(A_d, Bhat_v, Q_v, T_v) for every token, written in document order and in word order
             for (const Chunk &ch : c->chunks) {
                 int s = -1;
-                if (c->n_slots) SABER_TRY(stream_acquire(c, ch, true, false, &s));
+                if (c->n_slots) SABER_TRY(stream_acquire(c, ch, &s));
                 EStepParams p = make_params(c, ch, s);
                 p.n_dense = c->dense_slots + (size_t)kDenseSlots * b;
                 SABER_TRY(launch_estep<MODE_SAMPLE>(c, ch, p));
                 if (c->n_slots) {
-                    // the chunk's rows of A are rebuilt while its new assignments are still on the device; the
-                    // sampling of later chunks reads other documents' rows only
+                    // the chunk's rows of A are rebuilt while its new assignments are in the buffer (the sampling
+                    // of later chunks reads other documents' rows only); after that only z_wm keeps them
                     SABER_TRY(launch_count_dz_chunk(c, ch, s));
-                    SABER_TRY(stream_release(c, ch, s, true));
+                    SABER_TRY(stream_release(c, s));
                 }
             }
             if (prof) HIP_TRY(hipEventRecord(ev[EV_SAMPLE], c->stream));
@@ -1070,11 +1077,11 @@ extern "C" int saber_loglik(saber_ctx *c, double *out) {
         for (const Chunk &ch : c->chunks) {
             if (ch.ntiles == 0) continue;
             int s = -1;
-            if (c->n_slots) SABER_TRY(stream_acquire(c, ch, true, false, &s));
+            if (c->n_slots) SABER_TRY(stream_acquire(c, ch, &s));
             EStepParams p = make_params(c, ch, s);
             p.out_ll = c->ll_partial;
             SABER_TRY(launch_estep<MODE_LOGLIK>(c, ch, p));
-            if (c->n_slots) SABER_TRY(stream_release(c, ch, s, false));
+            if (c->n_slots) SABER_TRY(stream_release(c, s));
             HIP_TRY(hipStreamSynchronize(c->stream));
             part.resize((size_t)ch.ntiles);
             HIP_TRY(hipMemcpy(part.data(), c->ll_partial, sizeof(double) * (size_t)ch.ntiles, hipMemcpyDeviceToHost));
@@ -1168,10 +1175,31 @@ extern "C" int saber_holdout_loglik(saber_ctx *m, const int64_t *doc_ptr, const 
 extern "C" int saber_get_z(saber_ctx *c, int32_t *z) {
     if (!c || !z) return fail(SABER_EINVAL, "saber_get_z: null argument");
     if (c->T == 0) return SABER_OK;
-    if (c->n_slots) {   // the host copy is complete once the copy streams are idle
-        SABER_TRY(sync_all(c));
-        if (c->z16) { const uint16_t *h = (const uint16_t *)c->h_z; for (int64_t t = 0; t < c->T; t++) z[t] = (int32_t)h[t]; }
-        else memcpy(z, c->h_z, sizeof(int32_t) * (size_t)c->T);
+    if (c->n_slots) {   // document order is re-created chunk by chunk from the word-major copy
+        try {
+            std::vector<uint16_t> stage;
+            for (const Chunk &ch : c->chunks) {
+                if (ch.ntok == 0) continue;
+                int s;
+                SABER_TRY(stream_acquire(c, ch, &s));
+                if (c->z16)
+                    hipLaunchKernelGGL((scatter_zwm_kernel<uint16_t>), dim3((unsigned)ch.ntiles), dim3(256), 0, c->stream,
+                                       c->tiles + ch.tile0, c->slot_tok_t[s], (const uint16_t *)c->z_wm, (uint16_t *)c->slot_z[s]);
+                else
+                    hipLaunchKernelGGL((scatter_zwm_kernel<int32_t>), dim3((unsigned)ch.ntiles), dim3(256), 0, c->stream,
+                                       c->tiles + ch.tile0, c->slot_tok_t[s], (const int32_t *)c->z_wm, (int32_t *)c->slot_z[s]);
+                HIP_TRY(hipGetLastError());
+                SABER_TRY(stream_release(c, s));
+                HIP_TRY(hipStreamSynchronize(c->stream));
+                if (c->z16) {
+                    stage.resize((size_t)ch.ntok);
+                    HIP_TRY(hipMemcpy(stage.data(), c->slot_z[s], (size_t)ch.ntok * 2, hipMemcpyDeviceToHost));
+                    for (int64_t i = 0; i < ch.ntok; i++) z[ch.t0 + i] = (int32_t)stage[(size_t)i];
+                } else {
+                    HIP_TRY(hipMemcpy(z + ch.t0, c->slot_z[s], (size_t)ch.ntok * 4, hipMemcpyDeviceToHost));
+                }
+            }
+        } catch (const std::bad_alloc &) { return fail(SABER_ENOMEM, "saber_get_z: out of host memory"); }
         return SABER_OK;
     }
     if (!c->z16) { HIP_TRY(hipMemcpy(z, c->z, sizeof(int32_t) * (size_t)c->T, hipMemcpyDeviceToHost)); return SABER_OK; }
@@ -1191,11 +1219,7 @@ extern "C" int saber_set_z(saber_ctx *c, const int32_t *z, uint32_t iter) {
     if (!c || (!z && c->T)) return fail(SABER_EINVAL, "saber_set_z: null argument");
     for (int64_t t = 0; t < c->T; t++)
         if (z[t] < 0 || z[t] >= c->K) return fail(SABER_EINVAL, "saber_set_z: topic %d at token %lld is outside [0,%d)", z[t], (long long)t, c->K);
-    if (c->T && c->n_slots) {
-        SABER_TRY(sync_all(c));
-        if (c->z16) { uint16_t *h = (uint16_t *)c->h_z; for (int64_t t = 0; t < c->T; t++) h[t] = (uint16_t)z[t]; }
-        else memcpy(c->h_z, z, sizeof(int32_t) * (size_t)c->T);
-    } else if (c->T) {
+    if (c->T && !c->n_slots) {
         int32_t *tmp = nullptr;
         SABER_TRY(dev_alloc(&tmp, (size_t)c->T));
         hipError_t e = hipMemcpy(tmp, z, sizeof(int32_t) * (size_t)c->T, hipMemcpyHostToDevice);
@@ -1211,7 +1235,8 @@ extern "C" int saber_set_z(saber_ctx *c, const int32_t *z, uint32_t iter) {
         if (e != hipSuccess) return fail(SABER_EDEVICE, "saber_set_z: %s", hipGetErrorString(e));
     }
     c->iter = iter;
-    SABER_TRY(full_mstep(c));
+    try { SABER_TRY(full_mstep(c, c->n_slots ? z : nullptr)); }
+    catch (const std::bad_alloc &) { return fail(SABER_ENOMEM, "saber_set_z: out of host memory"); }
     SABER_TRY(refresh_workload_stats(c));
     return SABER_OK;
 }
@@ -1234,11 +1259,11 @@ extern "C" int saber_token_probs(saber_ctx *c, const int64_t *tok, int64_t m, fl
         (rc = dev_alloc(&gQ, (size_t)m)) || (rc = dev_alloc(&dtok, (size_t)m))) { cleanup(); return rc; }
     for (const Chunk &ch : c->chunks) {
         int s = -1;
-        if (c->n_slots && (rc = stream_acquire(c, ch, true, false, &s))) { cleanup(); return rc; }
+        if (c->n_slots && (rc = stream_acquire(c, ch, &s))) { cleanup(); return rc; }
         EStepParams p = make_params(c, ch, s);
         p.out_S = dS; p.out_Q = dQ;
         if ((rc = launch_estep<MODE_PROBS>(c, ch, p))) { cleanup(); return rc; }
-        if (c->n_slots && (rc = stream_release(c, ch, s, false))) { cleanup(); return rc; }
+        if (c->n_slots && (rc = stream_release(c, s))) { cleanup(); return rc; }
     }
     std::vector<float> hS((size_t)m), hQ((size_t)m);
     hipError_t e = hipMemcpyAsync(dtok, tok, sizeof(int64_t) * (size_t)m, hipMemcpyHostToDevice, c->stream);

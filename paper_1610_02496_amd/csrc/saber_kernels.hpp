@@ -634,6 +634,34 @@ __global__ void __launch_bounds__(1024) count_vz_kernel(const VzItem *items, con
     }
 }
 
+// Host streaming: a chunk's assignments in document order (relative to the chunk's first token) out of the
+// word-major copy; the inverse of fill_zwm_kernel.
+template <typename ZT>
+__global__ void scatter_zwm_kernel(const Tile *tiles, const uint32_t *tok_t, const ZT *z_wm, ZT *z_chunk) {
+    const Tile tile = tiles[blockIdx.x];
+    for (int i = threadIdx.x; i < tile.count; i += blockDim.x)
+        z_chunk[tok_t[tile.begin + i]] = z_wm[tile.wm_begin + i];
+}
+
+// Host streaming: the document of every token of a chunk, from the canonical token numbers.  The document of
+// token t is the last d with doc_ptr[d] <= t; coarse[j] is that document for t = 64 j, so the search runs over
+// the few documents between two neighbouring entries.
+__global__ void expand_tok_doc_kernel(const uint32_t *__restrict__ tok_t, int64_t n, int64_t t0,
+                                      const int32_t *__restrict__ coarse, const int64_t *__restrict__ doc_ptr,
+                                      int32_t *__restrict__ tok_doc) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) {
+        const int64_t t = t0 + (int64_t)tok_t[i];
+        int32_t lo = coarse[t >> 6], hi = coarse[(t >> 6) + 1];
+        while (lo < hi) {
+            const int32_t mid = lo + ((hi - lo + 1) >> 1);
+            if (doc_ptr[mid] <= t) lo = mid; else hi = mid - 1;
+        }
+        tok_doc[i] = lo;
+    }
+}
+
 // word-major copy of the assignments (after init / set_z; during iterations the E-step writes it)
 template <typename ZT>
 __global__ void fill_zwm_kernel(const Tile *tiles, const uint32_t *tok_t, const ZT *z, int64_t t_base, ZT *z_wm) {

@@ -295,6 +295,9 @@ def test_host_streaming_matches_oracle_and_resident_path(K):
     z0 = ref.get_z()
     ref.iterate(3)
     z3, ll3 = ref.get_z(), ref.loglik()
+    held = corpusgen.tiny(55, 40, c.spec.V, 15, 60.0)          # held-out documents over the same vocabulary
+    observed = (np.arange(held.T) % 2 == 0).astype(np.uint8)
+    hold3 = ref.holdout_loglik(held.doc_ptr, held.word_ids, observed, 3, 5)
     for workers, chunks in [(1, 1), (1, 4), (2, 5), (3, 7), (8, 3)]:
         g = pk.Saber(c.doc_ptr, c.word_ids, c.spec.V, K, alpha, 0.01, 77, stream_workers=workers, n_chunks=chunks)
         o = oracle.Model(c.doc_ptr, c.word_ids, c.spec.V, K, alpha, 0.01, 77)
@@ -308,6 +311,9 @@ def test_host_streaming_matches_oracle_and_resident_path(K):
         assert g.loglik() == ll3 if chunks == 1 else abs(g.loglik() - ll3) <= 1e-12 * abs(ll3)
         o.set_z(z3, 3)
         assert_counts_equal(g, o)
+        # held-out documents are scored on the model only: same model, same bits
+        h = g.holdout_loglik(held.doc_ptr, held.word_ids, observed, 3, 5)
+        assert h[0] == hold3[0] and h[1] == hold3[1] and np.array_equal(h[2], hold3[2])
         g.close(); o.close()
     with pytest.raises(pk.SaberError):
         pk.Saber(c.doc_ptr, c.word_ids, c.spec.V, K, alpha, 0.01, 77, stream_workers=9)
