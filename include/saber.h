@@ -77,7 +77,12 @@ typedef struct saber_options {
                                    assignments), which is what lets a corpus several times the device memory run.
                                    Results are the same.  With profile=1, ms_sample then covers the whole chunk loop
                                    (copies waited for, sampling, CountByDZ) and ms_count_dz is zero. */
-    int32_t reserved[5];
+    int32_t ablation;           /* measurement aid, default 0: bit 0 samples the tokens in document order instead of
+                                   word order (the layout before Sec. 3.1.3: the row of A is fetched once per document,
+                                   Bhat is gathered from global memory; every word then keeps a dense row and
+                                   stream_workers must be 0); bit 1 rebuilds A by a radix sort of all (document, topic)
+                                   pairs instead of the segmented count of Sec. 3.3.  Results are the same. */
+    int32_t reserved[4];
 } saber_options;
 
 /* Sums over the iterations run since the last saber_reset_stats.  The ms_* fields need profile=1. */

@@ -34,7 +34,7 @@ class Options(ctypes.Structure):
                 ("stage_phi", ctypes.c_int32), ("profile", ctypes.c_int32), ("long_doc_tokens", ctypes.c_int32),
                 ("dz_lds_entries", ctypes.c_int32), ("stage_min_tokens", ctypes.c_int32),
                 ("light_block_threads", ctypes.c_int32), ("light_word_tokens", ctypes.c_int32),
-                ("stream_workers", ctypes.c_int32), ("reserved", ctypes.c_int32 * 5)]
+                ("stream_workers", ctypes.c_int32), ("ablation", ctypes.c_int32), ("reserved", ctypes.c_int32 * 4)]
 
 
 class Stats(ctypes.Structure):

@@ -2,6 +2,7 @@
 // per-iteration launch sequence of Alg. 1.  Every step of the path runs in the kernels of
 // saber_kernels.hpp; nothing here computes counts or samples on the CPU.
 #include "saber_kernels.hpp"
+#include "saber_ablation.hpp"
 #include "../../include/saber.h"
 
 #include <algorithm>
@@ -12,6 +13,8 @@
 #include <cstring>
 #include <new>
 #include <vector>
+
+#include <rocprim/rocprim.hpp>
 
 using namespace saber;
 
@@ -129,6 +132,14 @@ struct saber_ctx {
     hipStream_t s_in = nullptr;
     hipEvent_t ev_loaded[kMaxSlots] = {}, ev_done[kMaxSlots] = {};
     bool slot_used[kMaxSlots] = {};
+    // ablation variants (saber_options.ablation): document-order sampling needs the words in canonical order and
+    // the word -> row map; the sort-based rebuild of A needs key buffers and the sort's work space
+    int32_t *word_ids_d = nullptr, *word_row_d = nullptr;
+    uint64_t *sort_keys = nullptr, *sort_keys_out = nullptr;
+    uint32_t *sort_rank = nullptr;
+    void *sort_tmp = nullptr;
+    size_t sort_tmp_bytes = 0;
+    unsigned sort_end_bit = 0;
 };
 
 template <typename T>
@@ -171,6 +182,8 @@ extern "C" void saber_free(saber_ctx *c) {
         if (c->ev_done[s]) (void)hipEventDestroy(c->ev_done[s]);
     }
     dev_free(c->doc_coarse);
+    dev_free(c->word_ids_d); dev_free(c->word_row_d); dev_free(c->sort_keys); dev_free(c->sort_keys_out);
+    dev_free(c->sort_rank); dev_free(c->sort_tmp);
     if (c->h_tok_t) (void)hipHostFree(c->h_tok_t);
     if (c->stream) (void)hipStreamDestroy(c->stream);
     delete c;
@@ -317,7 +330,31 @@ static int launch_segmented_count(saber_ctx *c, const int32_t *short_list, int64
     return SABER_OK;
 }
 
+// Ablation: A rebuilt by sorting the (document, topic) pairs of all tokens
+static int launch_sort_rebuild(saber_ctx *c) {
+    if (c->T == 0 || c->D == 0) return SABER_OK;
+    const dim3 grid((unsigned)((c->D + 3) / 4)), block(256);
+    if (c->z16)
+        hipLaunchKernelGGL((sort_keys_kernel<uint16_t>), grid, block, 0, c->stream, c->doc_ptr, (const uint16_t *)c->z, c->D,
+                           c->topic_bits, c->sort_keys);
+    else
+        hipLaunchKernelGGL((sort_keys_kernel<int32_t>), grid, block, 0, c->stream, c->doc_ptr, (const int32_t *)c->z, c->D,
+                           c->topic_bits, c->sort_keys);
+    HIP_TRY(hipGetLastError());
+    size_t bytes = c->sort_tmp_bytes;
+    HIP_TRY(rocprim::radix_sort_keys(c->sort_tmp, bytes, c->sort_keys, c->sort_keys_out, (size_t)c->T, 0u, c->sort_end_bit,
+                                     c->stream));
+    hipLaunchKernelGGL(sort_mark_kernel, grid, block, 0, c->stream, c->doc_ptr, c->sort_keys_out, c->D, c->topic_mask,
+                       c->docrec, c->cd_ent, c->sort_rank);
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(sort_count_kernel, grid, block, 0, c->stream, c->doc_ptr, c->sort_rank, c->D, c->docrec, c->cd_ent,
+                       c->topic_bits);
+    HIP_TRY(hipGetLastError());
+    return SABER_OK;
+}
+
 static int launch_count_dz(saber_ctx *c) {
+    if (c->opt.ablation & 2) return launch_sort_rebuild(c);
     return launch_segmented_count(c, c->short_docs, c->n_short, c->long_docs, c->n_long, c->doc_ptr, c->z, c->docrec,
                                   c->cd_ent);
 }
@@ -435,6 +472,24 @@ static int launch_fill_zwm_chunk(saber_ctx *c, const Chunk &ch, int slot) {
 static int launch_fill_zwm(saber_ctx *c) {
     for (const Chunk &ch : c->chunks) SABER_TRY(launch_fill_zwm_chunk(c, ch, -1));
     return SABER_OK;
+}
+
+// Ablation: the E-step over the tokens in document order, then the word-major copy from z
+static int launch_estep_docmajor(saber_ctx *c, unsigned long long *n_dense) {
+    if (c->T == 0 || c->D == 0) return SABER_OK;
+    DocMajorParams p{};
+    p.doc_ptr = c->doc_ptr; p.word_ids = c->word_ids_d; p.word_row = c->word_row_d;
+    p.docrec = c->docrec; p.cd_ent = c->cd_ent;
+    p.phi = c->phi; p.l3 = c->l3; p.sumphi = c->sumphi; p.l3_64 = c->l3_64;
+    p.z = c->z; p.n_dense = n_dense; p.D = c->D;
+    p.K = c->K; p.Kpad = c->Kpad; p.n3 = c->n3; p.n3pad = c->n3pad;
+    p.topic_bits = c->topic_bits; p.topic_mask = c->topic_mask; p.alpha = c->alpha;
+    p.seed_lo = (uint32_t)c->seed; p.seed_hi = (uint32_t)(c->seed >> 32); p.iter = c->iter;
+    const dim3 grid((unsigned)((c->D + 3) / 4)), block(256);
+    if (c->z16) hipLaunchKernelGGL((estep_docmajor_kernel<uint16_t>), grid, block, 0, c->stream, p);
+    else hipLaunchKernelGGL((estep_docmajor_kernel<int32_t>), grid, block, 0, c->stream, p);
+    HIP_TRY(hipGetLastError());
+    return launch_fill_zwm(c);
 }
 
 // CountByVZ for the dense rows of B out of the word-major assignments; the rows must be all zero on entry
@@ -744,6 +799,22 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
         if (!h_light_long.empty()) HIP_TRY(hipMemcpy(c->light_long, h_light_long.data(), sizeof(int32_t) * h_light_long.size(), hipMemcpyHostToDevice));
     }
     SABER_TRY(dev_alloc(&c->doc_words, (size_t)D));
+    if (c->opt.ablation & 1) {
+        SABER_TRY(dev_alloc(&c->word_ids_d, (size_t)T)); SABER_TRY(dev_alloc(&c->word_row_d, (size_t)V));
+        if (T) HIP_TRY(hipMemcpy(c->word_ids_d, word_ids, sizeof(int32_t) * (size_t)T, hipMemcpyHostToDevice));
+        HIP_TRY(hipMemcpy(c->word_row_d, c->h_word_row.data(), sizeof(int32_t) * (size_t)V, hipMemcpyHostToDevice));
+    }
+    if (c->opt.ablation & 2) {
+        unsigned dbits = 1; while (dbits < 32 && (1ll << dbits) < std::max<int64_t>(D, 1)) dbits++;
+        c->sort_end_bit = c->topic_bits + dbits;
+        SABER_TRY(dev_alloc(&c->sort_keys, (size_t)T)); SABER_TRY(dev_alloc(&c->sort_keys_out, (size_t)T));
+        SABER_TRY(dev_alloc(&c->sort_rank, (size_t)T));
+        size_t bytes = 0;
+        HIP_TRY(rocprim::radix_sort_keys(nullptr, bytes, c->sort_keys, c->sort_keys_out, (size_t)std::max<int64_t>(T, 1), 0u,
+                                         c->sort_end_bit, c->stream));
+        c->sort_tmp_bytes = std::max<size_t>(bytes, 1);
+        HIP_TRY(hipMalloc(&c->sort_tmp, c->sort_tmp_bytes));
+    }
     if (!par) { SABER_TRY(dev_alloc(&c->l3, ((size_t)V + 1) * (size_t)c->n3pad)); SABER_TRY(dev_alloc(&c->sumphi, (size_t)V + 1)); }
     SABER_TRY(dev_alloc(&c->counters, (size_t)kMaxTimedIters * kCtr));
     SABER_TRY(dev_alloc(&c->dense_slots, (size_t)kMaxTimedIters * kDenseSlots));
@@ -818,6 +889,7 @@ static int create_ctx(saber_ctx **out, const int64_t *doc_ptr, const int32_t *wo
         if (opt_in->light_block_threads > 0) opt.light_block_threads = opt_in->light_block_threads;
         opt.light_word_tokens = opt_in->light_word_tokens;
         opt.stream_workers = opt_in->stream_workers;
+        opt.ablation = opt_in->ablation;
         opt.stage_phi = opt_in->stage_phi; opt.profile = opt_in->profile;
         if (opt_in->stage_phi < 0) opt.stage_phi = 1;
     }
@@ -829,7 +901,10 @@ static int create_ctx(saber_ctx **out, const int64_t *doc_ptr, const int32_t *wo
     if (opt.stage_min_tokens <= 0) opt.stage_min_tokens = 1;
     if (opt.stream_workers < 0 || opt.stream_workers > kMaxSlots)
         return fail(SABER_EINVAL, "saber_init: stream_workers must be in [0,%d]", kMaxSlots);
-    if (parent) opt.stream_workers = 0;   // held-out documents are few: always resident
+    if (parent) { opt.stream_workers = 0; opt.ablation = 0; }   // held-out documents are few: always resident, regular kernels
+    if (opt.ablation < 0 || opt.ablation > 3) return fail(SABER_EINVAL, "saber_init: ablation must be in [0,3]");
+    if (opt.ablation && opt.stream_workers) return fail(SABER_EINVAL, "saber_init: the ablation variants need stream_workers = 0");
+    if (opt.ablation & 1) opt.light_word_tokens = -1;   // document order gathers Bhat from dense rows
     if (opt.light_word_tokens == 0) opt.light_word_tokens = std::max(1, K / 2);   // < 0 keeps every word dense
     // automatic: chunks of at most 128 M tokens.  The sampling pass of a chunk reads every row of A of the chunk once
     // per word of the document; at about 0.4 non-zeros per token these rows (4 bytes per entry) then fit the 256 MB
@@ -921,7 +996,8 @@ extern "C" int saber_iterate(saber_ctx *c, int32_t n) {
             c->iter++;
             if (prof) HIP_TRY(hipEventRecord(ev[EV_BEGIN], c->stream));
             // E-step: z <- Sample(A_d, Bhat_v, Q_v, T_v) for every token, written in document order and in word order
-            for (const Chunk &ch : c->chunks) {
+            if (c->opt.ablation & 1) SABER_TRY(launch_estep_docmajor(c, c->dense_slots + (size_t)kDenseSlots * b));
+            else for (const Chunk &ch : c->chunks) {
                 int s = -1;
                 if (c->n_slots) SABER_TRY(stream_acquire(c, ch, &s));
                 EStepParams p = make_params(c, ch, s);

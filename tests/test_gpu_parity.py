@@ -319,6 +319,41 @@ def test_host_streaming_matches_oracle_and_resident_path(K):
         pk.Saber(c.doc_ptr, c.word_ids, c.spec.V, K, alpha, 0.01, 77, stream_workers=9)
 
 
+@pytest.mark.parametrize("ablation", [1, 2, 3])
+def test_ablation_variants_match_oracle_and_default_path(ablation):
+    """The measurement variants of Sec. 4.2's decomposition (bit 0: tokens sampled in document order, bit 1: A rebuilt
+    by sorting all (document, topic) pairs) compute what the regular kernels compute: oracle parity step by step,
+    and z bit-identical to the default path after several iterations.  Rows of one, two and more 256-entry blocks,
+    empty documents, both widths of z."""
+    pk = saber()
+    spec = corpusgen.CorpusSpec("mixed", 300, 600, 300 * 300, "lognormal", 300.0, 1.2, 30, 1.1, 0.05, 0.5, 3000, 1, 14)
+    cases = [(corpusgen.tiny(56, 300, 500, 15, 80.0), 300, 0.2),
+             (corpusgen.generate(spec, nthreads=2), 3000, 50.0 / 3000),
+             (corpusgen.tiny(57, 120, 60, 6, 50.0), 70000, 0.01)]
+    for c, K, alpha in cases:
+        ref = pk.Saber(c.doc_ptr, c.word_ids, c.spec.V, K, alpha, 0.01, 21, light_word_tokens=-1)
+        ref.iterate(3)
+        g, o = make_pair(c, K, alpha, 0.01, 21, ablation=ablation)
+        assert_counts_equal(g, o)
+        assert_estep_parity(g, o)
+        assert_estep_parity(g, o)
+        g2 = pk.Saber(c.doc_ptr, c.word_ids, c.spec.V, K, alpha, 0.01, 21, ablation=ablation)
+        g2.iterate(3)
+        assert np.array_equal(g2.get_z(), ref.get_z()), (K, ablation)
+        assert g2.get_stats()["sum_tokens_dense"] == ref.get_stats()["sum_tokens_dense"]
+        for x in (ref, g, g2): x.close()
+        o.close()
+    dp = np.array([0, 0, 1, 1, 4, 4, 4, 9, 9], dtype=np.int64)
+    w = np.array([3, 0, 0, 2, 1, 1, 1, 3, 0], dtype=np.int32)
+    g = pk.Saber(dp, w, 5, 7, 0.3, 0.01, 11, ablation=ablation)
+    o = oracle.Model(dp, w, 5, 7, 0.3, 0.01, 11)
+    assert_counts_equal(g, o)
+    for _ in range(3):
+        assert_estep_parity(g, o, min_agree=0.0)
+    with pytest.raises(pk.SaberError):
+        pk.Saber(dp, w, 5, 7, 0.3, 0.01, 11, ablation=ablation, stream_workers=2)
+
+
 def test_set_z_roundtrip_and_determinism():
     c = corpusgen.tiny(52, 200, 300, 10, 50.0)
     pk = saber()
