@@ -211,6 +211,16 @@ int saber_reset_stats(saber_ctx *ctx);
 /* HIP stream the library launches on (a hipStream_t), for callers that want to order work against it. */
 int saber_get_stream(saber_ctx *ctx, void **hip_stream);
 
+/* Measurement aid for the choice between the alias table and the tree (Sec. 3.2.3): builds an alias table (Vose's
+ * construction, one thread per row) from the current Bhat row of every word that keeps a dense row, and reports
+ * the device time of that build in *ms_build and the number of rows in *rows_built (may be null); the sampler
+ * does not use the tables.  For the m words listed (host array; each must keep a dense row, see
+ * light_word_tokens) the table is returned in prob[m][K] and alias[m][K] (host): bucket k yields topic k with
+ * probability prob, else topic alias.  All memory the call needs is allocated and freed inside it (20 bytes per
+ * row and topic; more than 64 GB is refused with SABER_ERANGE). */
+int saber_alias_build_probe(saber_ctx *ctx, const int32_t *words, int32_t m, float *prob, int32_t *alias,
+                            double *ms_build, int32_t *rows_built);
+
 /* Measurement aid, independent of any context: copies `bytes` bytes device-to-device `reps` times with a
  * plain streaming kernel and reports read+write bandwidth in GB/s (the achievable-HBM yardstick, and the
  * kernel the profiler's FETCH_SIZE / WRITE_SIZE counters are calibrated against). */

@@ -20,7 +20,7 @@ _STATUS = {0: "SABER_OK", -1: "SABER_EINVAL", -2: "SABER_ENOMEM", -3: "SABER_EDE
 EXPORTS = ["saber_options_default", "saber_init_ex", "saber_init", "saber_iterate", "saber_counts_nnz",
            "saber_counts", "saber_loglik", "saber_holdout_loglik", "saber_free", "saber_last_error", "saber_get_z", "saber_set_z",
            "saber_get_iteration", "saber_token_probs", "saber_get_phi", "saber_get_stats", "saber_reset_stats",
-           "saber_get_stream", "saber_bandwidth_probe"]
+           "saber_get_stream", "saber_bandwidth_probe", "saber_alias_build_probe"]
 
 
 class SaberError(RuntimeError):
@@ -89,6 +89,7 @@ def load_library():
         "saber_reset_stats": (ctypes.c_int, [vp]),
         "saber_get_stream": (ctypes.c_int, [vp, vp]),
         "saber_bandwidth_probe": (ctypes.c_int, [i64, i32, vp]),
+        "saber_alias_build_probe": (ctypes.c_int, [vp, vp, i32, vp, vp, vp, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -202,6 +203,17 @@ class Saber:
                                                    None if z_init is None else _ptr(z_init), _ptr(z_out),
                                                    ctypes.addressof(ll), ctypes.addressof(scored)))
         return ll.value, scored.value, z_out[:n_obs]
+
+    def alias_build_probe(self, words=()):
+        """Builds alias tables for all dense rows; returns (ms, rows built, prob[m][K], alias[m][K]) for `words`."""
+        words = np.ascontiguousarray(words, dtype=np.int32)
+        m = int(words.size)
+        prob = np.zeros((max(m, 1), self.K), dtype=np.float32)
+        alias = np.zeros((max(m, 1), self.K), dtype=np.int32)
+        ms = ctypes.c_double(); rows = ctypes.c_int32()
+        _check(load_library().saber_alias_build_probe(self._h, _ptr(words) if m else None, m, _ptr(prob), _ptr(alias),
+                                                      ctypes.addressof(ms), ctypes.addressof(rows)))
+        return ms.value, rows.value, prob[:m], alias[:m]
 
     def get_z(self):
         z = np.zeros(self.T, dtype=np.int32)

@@ -1406,6 +1406,66 @@ extern "C" int saber_get_phi(saber_ctx *c, const int32_t *words, int32_t m, floa
     return SABER_OK;
 }
 
+// ------------------------------------------------------------------------------------------------
+// alias-table construction (measurement aid)
+// ------------------------------------------------------------------------------------------------
+extern "C" int saber_alias_build_probe(saber_ctx *c, const int32_t *words, int32_t m, float *prob, int32_t *alias,
+                                       double *ms_build, int32_t *rows_built) {
+    if (!c || m < 0 || (m > 0 && (!words || !prob || !alias)) || !ms_build)
+        return fail(SABER_EINVAL, "saber_alias_build_probe: bad argument");
+    if (c->parent) return fail(SABER_EINVAL, "saber_alias_build_probe: needs a context made by saber_init");
+    std::vector<int32_t> rows((size_t)std::max(m, 1));
+    for (int32_t i = 0; i < m; i++) {
+        if (words[i] < 0 || words[i] >= c->V) return fail(SABER_EINVAL, "saber_alias_build_probe: word %d is outside [0,%d)", words[i], c->V);
+        rows[(size_t)i] = c->h_word_row[(size_t)words[i]];
+        if (rows[(size_t)i] < 0) return fail(SABER_EINVAL, "saber_alias_build_probe: word %d keeps a sparse row (no dense Bhat row to build from)", words[i]);
+    }
+    const int nrows = c->V_dense, K = c->K;
+    if (rows_built) *rows_built = nrows;
+    *ms_build = 0.0;
+    if (nrows == 0) return m ? fail(SABER_EINVAL, "saber_alias_build_probe: no dense rows") : (int)SABER_OK;
+    const size_t cells = (size_t)nrows * (size_t)K;
+    if (cells * 20 > ((size_t)64 << 30)) return fail(SABER_ERANGE, "saber_alias_build_probe: tables of %zu bytes exceed 64 GB", cells * 20);
+    double *scaled = nullptr; int32_t *stack = nullptr, *d_alias = nullptr, *d_rows = nullptr, *o_alias = nullptr;
+    float *d_prob = nullptr, *o_prob = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    auto cleanup = [&]() {
+        dev_free(scaled); dev_free(stack); dev_free(d_alias); dev_free(d_rows); dev_free(o_alias); dev_free(d_prob); dev_free(o_prob);
+        if (e0) (void)hipEventDestroy(e0);
+        if (e1) (void)hipEventDestroy(e1);
+    };
+    int rc;
+    if ((rc = dev_alloc(&scaled, cells)) || (rc = dev_alloc(&stack, cells)) || (rc = dev_alloc(&d_alias, cells)) ||
+        (rc = dev_alloc(&d_prob, cells)) || (rc = dev_alloc(&d_rows, (size_t)std::max(m, 1))) ||
+        (rc = dev_alloc(&o_prob, (size_t)std::max(m, 1) * (size_t)K)) || (rc = dev_alloc(&o_alias, (size_t)std::max(m, 1) * (size_t)K))) {
+        cleanup(); return rc;
+    }
+    hipError_t e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    if (e == hipSuccess) e = hipEventRecord(e0, c->stream);
+    if (e == hipSuccess) {
+        hipLaunchKernelGGL(alias_build_kernel, dim3((unsigned)((nrows + 255) / 256)), dim3(256), 0, c->stream, c->phi, nrows, K,
+                           c->Kpad, scaled, stack, d_prob, d_alias);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipEventRecord(e1, c->stream);
+    if (e == hipSuccess && m) e = hipMemcpyAsync(d_rows, rows.data(), sizeof(int32_t) * (size_t)m, hipMemcpyHostToDevice, c->stream);
+    if (e == hipSuccess && m) {
+        hipLaunchKernelGGL(alias_export_kernel, dim3(grid_for((int64_t)m * K, 256, 4096)), dim3(256), 0, c->stream, d_rows, m,
+                           nrows, K, d_prob, d_alias, o_prob, o_alias);
+        e = hipGetLastError();
+    }
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e == hipSuccess && m) e = hipMemcpy(prob, o_prob, sizeof(float) * (size_t)m * (size_t)K, hipMemcpyDeviceToHost);
+    if (e == hipSuccess && m) e = hipMemcpy(alias, o_alias, sizeof(int32_t) * (size_t)m * (size_t)K, hipMemcpyDeviceToHost);
+    cleanup();
+    if (e != hipSuccess) return fail(SABER_EDEVICE, "saber_alias_build_probe: %s", hipGetErrorString(e));
+    *ms_build = (double)ms;
+    return SABER_OK;
+}
+
 extern "C" int saber_get_stats(saber_ctx *c, saber_stats *out) {
     if (!c || !out) return fail(SABER_EINVAL, "saber_get_stats: null argument");
     *out = c->stats;

@@ -194,4 +194,56 @@ __global__ void __launch_bounds__(256) sort_count_kernel(const int64_t *doc_ptr,
     for (int64_t t = begin + lane; t < end; t += kWave) atomicAdd(&row[rank_of[t]], 1u << topic_bits);
 }
 
+// ---- alias tables (the alternative to the tree that Sec. 3.2.3 weighs) ----
+// Vose's construction for the Bhat rows of the words with dense rows, one thread per row: the pairing of an
+// under-full with an over-full bucket is a chain in which every step needs the previous one's remainder, which is
+// what keeps it from using a wavefront's lanes.  Bucket k keeps topic k with probability prob[k] and hands the
+// rest to alias[k].  Arrays are laid out [K][nrows] so that the lanes of a wavefront (neighbouring rows) touch
+// neighbouring addresses as long as they walk in step.  scaled: K * p_k in binary64 while the row is worked on;
+// stack: under-full buckets from the bottom, over-full ones from the top.
+__global__ void __launch_bounds__(256) alias_build_kernel(const float *__restrict__ phi, int nrows, int K, int Kpad,
+                                                          double *scaled, int32_t *stack, float *prob, int32_t *alias) {
+    const int r = (int)(blockIdx.x * blockDim.x + threadIdx.x);
+    if (r >= nrows) return;
+    const float *row = phi + (size_t)r * (size_t)Kpad;
+    const size_t n = (size_t)nrows;
+    double tot = 0.0;
+    for (int k = 0; k < K; k++) tot += (double)row[k];
+    const double scale = (double)K / tot;
+    int ns = 0, nl = 0;                           // stack[ns-1] .. under-full, stack[K-nl] .. over-full
+    for (int k = 0; k < K; k++) {
+        const double q = (double)row[k] * scale;
+        scaled[(size_t)k * n + r] = q;
+        if (q < 1.0) stack[(size_t)(ns++) * n + r] = k;
+        else stack[(size_t)(K - 1 - nl++) * n + r] = k;
+    }
+    while (ns > 0 && nl > 0) {
+        const int s = stack[(size_t)(--ns) * n + r];
+        const int l = stack[(size_t)(K - nl) * n + r];        // top of the over-full stack
+        const double qs = scaled[(size_t)s * n + r];
+        prob[(size_t)s * n + r] = (float)qs;
+        alias[(size_t)s * n + r] = l;
+        const double ql = scaled[(size_t)l * n + r] + qs - 1.0;
+        scaled[(size_t)l * n + r] = ql;
+        if (ql < 1.0) {                                       // the over-full bucket became under-full: move it
+            nl--;
+            stack[(size_t)(ns++) * n + r] = l;
+        }
+    }
+    // what is left is full up to rounding
+    while (ns > 0) { const int s = stack[(size_t)(--ns) * n + r]; prob[(size_t)s * n + r] = 1.f; alias[(size_t)s * n + r] = s; }
+    while (nl > 0) { const int l = stack[(size_t)(K - nl) * n + r]; nl--; prob[(size_t)l * n + r] = 1.f; alias[(size_t)l * n + r] = l; }
+}
+
+// the tables of the rows listed, as [m][K]
+__global__ void alias_export_kernel(const int32_t *rows, int m, int nrows, int K, const float *prob, const int32_t *alias,
+                                    float *out_prob, int32_t *out_alias) {
+    const int64_t total = (int64_t)m * K;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (int64_t)gridDim.x * blockDim.x) {
+        const int w = (int)(i / K), k = (int)(i % K);
+        out_prob[i] = prob[(size_t)k * (size_t)nrows + (size_t)rows[w]];
+        out_alias[i] = alias[(size_t)k * (size_t)nrows + (size_t)rows[w]];
+    }
+}
+
 }  // namespace saber

@@ -354,6 +354,34 @@ def test_ablation_variants_match_oracle_and_default_path(ablation):
         pk.Saber(dp, w, 5, 7, 0.3, 0.01, 11, ablation=ablation, stream_workers=2)
 
 
+def test_alias_tables_encode_the_word_distributions():
+    """The alias-table build (measurement aid for Sec. 3.2.3): any valid table is accepted, what is checked is the
+    distribution it encodes, bucket by bucket in binary64, against the oracle's Bhat rows: p_k = Bhat_vk / sum."""
+    pk = saber()
+    for c, K in [(corpusgen.tiny(58, 300, 500, 15, 80.0), 300), (corpusgen.tiny(59, 200, 90, 8, 120.0), 3000)]:
+        g, o = make_pair(c, K, 50.0 / K, 0.01, 31, light_word_tokens=-1)
+        g.iterate(2); o.set_z(g.get_z(), 2)
+        words = np.unique(np.r_[0, c.spec.V - 1, np.random.default_rng(1).integers(0, c.spec.V, 24)]).astype(np.int32)
+        ms, rows, prob, alias = g.alias_build_probe(words)
+        assert rows == c.spec.V and ms > 0.0
+        assert prob.min() >= 0.0 and prob.max() <= 1.0 and alias.min() >= 0 and alias.max() < K
+        for i, w in enumerate(words):
+            phi = o.phi[w].astype(np.float64)
+            want = phi / phi.sum()
+            got = prob[i].astype(np.float64)
+            np.add.at(got, alias[i], 1.0 - prob[i].astype(np.float64))
+            assert np.allclose(got / K, want, rtol=1e-5, atol=1e-12), w
+        g.close(); o.close()
+    # words that keep a sparse row have no dense Bhat row to build from
+    c = corpusgen.tiny(58, 300, 500, 15, 80.0)
+    g = pk.Saber(c.doc_ptr, c.word_ids, c.spec.V, 300, 0.2, 0.01, 31)
+    light = int(np.argmin(np.bincount(c.word_ids, minlength=c.spec.V)))
+    with pytest.raises(pk.SaberError):
+        g.alias_build_probe([light])
+    ms, rows, _, _ = g.alias_build_probe([])
+    assert rows < c.spec.V
+
+
 def test_set_z_roundtrip_and_determinism():
     c = corpusgen.tiny(52, 200, 300, 10, 50.0)
     pk = saber()
