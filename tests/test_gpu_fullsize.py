@@ -111,3 +111,30 @@ def test_full_size_parity(name, K):
     assert np.isfinite(ll) and -12.0 < ll < -3.0
     say("[fullsize] K=%d invariants and A after iteration 1 ok, loglik %.4f (%.1fs)" % (K, ll, time.time() - t))
     g.close(); o.close()
+
+
+def test_full_size_streaming_and_variants_equal_default():
+    """At the benchmark's size: host streaming (the configuration bench.py times: 3 workers, 4 chunks) and the two
+    ablation variants give the assignments of the default path bit for bit, which the test above holds against the
+    oracle; the chains are compared after two iterations."""
+    import paper_1610_02496_amd as pk
+    c = corpus_for("C3")
+    s = c.spec
+    K = 10000
+    args = (c.doc_ptr, c.word_ids, s.V, K, 50.0 / K, s.beta, s.seed)
+    g = pk.Saber(*args)
+    g.iterate(2)
+    z_ref, ll_ref = g.get_z(), g.loglik()
+    ck_ref = g.counts(want_cd=False, want_cwk=False)[4]
+    g.close()
+    for label, opts in [("streaming 3x4", {"stream_workers": 3, "n_chunks": 4}), ("streaming 2x7", {"stream_workers": 2, "n_chunks": 7}),
+                        ("A by sorting", {"ablation": 2}), ("document order", {"ablation": 1})]:
+        t = time.time()
+        g = pk.Saber(*args, **opts)
+        g.iterate(2)
+        z = g.get_z()
+        assert np.array_equal(z, z_ref), label
+        assert np.array_equal(g.counts(want_cd=False, want_cwk=False)[4], ck_ref), label
+        assert abs(g.loglik() - ll_ref) <= 1e-9 * abs(ll_ref), label
+        say("[fullsize] %s: z, topic totals and log-likelihood equal to the default path (%.1fs)" % (label, time.time() - t))
+        g.close()
