@@ -89,6 +89,36 @@ def run_holdout(g, corpus, docs, n_foldin):
                     "observed, odd positions scored; seconds include layout build, upload, fold-in and scoring"}
 
 
+def run_curve(corpus, K, iters, every, held_docs):
+    """Convergence over time, in the manner of the paper's Fig. 9/10 (on synthetic data): the model is trained on
+    all documents but the first ``held_docs``, which are really held out and scored by document completion (even
+    positions observed, 10 fold-in iterations) every ``every`` iterations; the clock counts training only."""
+    import paper_1610_02496_amd as pk
+    s = corpus.spec
+    t_held = int(corpus.doc_ptr[held_docs])
+    h_ptr = np.ascontiguousarray(corpus.doc_ptr[: held_docs + 1])
+    h_words = np.ascontiguousarray(corpus.word_ids[:t_held])
+    pos = np.arange(t_held) - np.repeat(h_ptr[:-1], np.diff(h_ptr))
+    observed = (pos % 2 == 0).astype(np.uint8)
+    tr_ptr = np.ascontiguousarray(corpus.doc_ptr[held_docs:] - t_held)
+    tr_words = np.ascontiguousarray(corpus.word_ids[t_held:])
+    g = pk.Saber(tr_ptr, tr_words, s.V, K, 50.0 / K, s.beta, s.seed)
+    points, train_s, it = [], 0.0, 0
+    while True:
+        ll_h, scored, _ = g.holdout_loglik(h_ptr, h_words, observed, 10, 777)
+        points.append({"iteration": it, "train_seconds": train_s, "loglik_train": g.loglik(), "loglik_holdout": ll_h})
+        log("[bench] curve K=%d %s" % (K, json.dumps(points[-1])))
+        if it >= iters:
+            break
+        n = min(every, iters - it)
+        t0 = time.perf_counter()
+        g.iterate(n)
+        train_s += time.perf_counter() - t0
+        it += n
+    g.close()
+    return {"K": K, "train_tokens": int(tr_ptr[-1]), "held_out_documents": held_docs, "scored_tokens": scored, "points": points}
+
+
 def run_gpu(corpus, K, steps, warmup, opts, holdout_docs=0):
     import torch
     import paper_1610_02496_amd as pk
@@ -189,6 +219,12 @@ def main():
                     help="any other field of saber_options, for experiments (e.g. --opt dz_lds_entries=2048)")
     ap.add_argument("--streaming", default="3:4", metavar="WORKERS:CHUNKS",
                     help="also time the iterations with host streaming in this configuration ('' = skip)")
+    ap.add_argument("--topic-conc", type=float, default=0.0,
+                    help="override the mean per-word Dirichlet concentration of the planted topics (the workloads use "
+                         "0.01; smaller values give topics that differ more); the workload name then says so")
+    ap.add_argument("--curve", type=int, default=0, metavar="ITERATIONS",
+                    help="also record log-likelihood over training time for this many iterations (a point every 10), "
+                         "with the first 30,000 documents really held out; 0 = skip")
     ap.add_argument("--holdout-docs", type=int, default=30000,
                     help="documents scored by the holdout log-likelihood after the timed region (0 = skip)")
     args = ap.parse_args()
@@ -205,6 +241,9 @@ def main():
     spec = corpusgen.SPECS[args.workload]
     if args.docs:
         spec = corpusgen.scaled(spec, args.docs)
+    if args.topic_conc > 0:
+        import dataclasses
+        spec = dataclasses.replace(spec, topic_conc=args.topic_conc, name="%s(topic concentration %g)" % (spec.name, args.topic_conc))
     t0 = time.time()
     corpus = corpusgen.generate(spec, with_topics=False)
     log("[bench] corpus %s: D=%d V=%d T=%d generated in %.1fs" % (spec.name, spec.D, spec.V, corpus.T, time.time() - t0))
@@ -225,7 +264,7 @@ def main():
         log("[bench] plain copy kernel: %.0f GB/s (read+write)" % copy_gbs)
     main_res = run_gpu(corpus, spec.K, args.steps, args.warmup, opts, args.holdout_docs)
     main_res["roofline"]["copy_kernel_gbs"] = copy_gbs
-    if not opts and not args.docs:
+    if not opts and not args.docs and not args.topic_conc:
         main_res["roofline"]["traffic"] = profiled_traffic(args.workload, args.steps, args.warmup)
     log("[bench] K=%d: %s" % (spec.K, json.dumps(main_res)))
     also = None
@@ -258,6 +297,8 @@ def main():
         out["holdout"] = main_res["holdout"]
     if streaming is not None:
         out["streaming"] = streaming
+    if args.curve:
+        out["curve"] = [run_curve(corpus, k, args.curve, 10, min(30000, spec.D // 2)) for k in sorted({spec.K, 1000})]
     if also is not None:
         out["also"] = also
     print(json.dumps(out), flush=True)
