@@ -208,7 +208,7 @@ def main():
     ap.add_argument("--docs", type=int, default=0, help="use only a document prefix (experiments; 0 = full corpus)")
     ap.add_argument("--no-also", action="store_true", help="skip the secondary K")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-docs", type=int, default=6000)
+    ap.add_argument("--cpu-docs", type=int, default=24000)
     ap.add_argument("--block-threads", type=int, default=0)
     ap.add_argument("--tile-tokens", type=int, default=0)
     ap.add_argument("--chunks", type=int, default=0)
