@@ -33,6 +33,31 @@ def test_struct_layouts_match_header():
     assert (o.n_chunks, o.block_threads, o.tile_tokens, o.stage_phi, o.profile) == (0, 0, 8192, 1, 0)
 
 
+def header_struct_fields(name):
+    text = open(os.path.join(ROOT, "include", "saber.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    body = re.search(r"typedef struct %s \{(.*?)\} %s;" % (name, name), text, flags=re.S).group(1)
+    fields = []
+    for decl in body.split(";"):
+        m = re.match(r"\s*(int32_t|int64_t|double|float|uint32_t|uint64_t)\s+(\w+)(\[(\d+)\])?\s*$", decl)
+        if m:
+            fields.append((m.group(2), m.group(1), int(m.group(4)) if m.group(4) else 1))
+    return fields
+
+
+def test_binding_structs_mirror_the_header_field_by_field():
+    import ctypes
+    ctype_of = {"int32_t": ctypes.c_int32, "int64_t": ctypes.c_int64, "double": ctypes.c_double, "float": ctypes.c_float,
+                "uint32_t": ctypes.c_uint32, "uint64_t": ctypes.c_uint64}
+    for cname, cls in (("saber_options", pk.Options), ("saber_stats", pk.Stats)):
+        want = header_struct_fields(cname)
+        assert len(want) >= 10
+        got = [(n, t) for n, t in cls._fields_]
+        assert [n for n, _ in got] == [n for n, _, _ in want], cname
+        for (n, t), (_, ct, cnt) in zip(got, want):
+            assert t == (ctype_of[ct] * cnt if cnt > 1 else ctype_of[ct]), (cname, n)
+
+
 def test_validation_happens_before_any_device_work():
     """Bad arguments are rejected on the host, GPU or not."""
     dp = np.array([0, 2], dtype=np.int64)
