@@ -382,6 +382,55 @@ def test_alias_tables_encode_the_word_distributions():
     assert rows < c.spec.V
 
 
+@pytest.mark.parametrize("test_seed", [20240607, 7, 99])
+def test_random_shapes_and_options(test_seed):
+    """Sixty corpora per seed of random shape (documents of 0 to a few hundred tokens, vocabularies of 1 to 400 words, K from
+    2 to 4,000 including values next to multiples of 64 and of 256) under random hyper-parameters and random
+    layout options, each checked against the oracle for two E-steps and the counts that follow."""
+    rng = np.random.default_rng(test_seed)
+    pk = saber()
+    k_pool = [2, 3, 5, 63, 64, 65, 100, 255, 256, 257, 300, 511, 512, 513, 1000, 1023, 1025, 2000, 4000]
+    for case in range(60):
+        D = int(rng.integers(1, 120))
+        V = int(rng.choice([1, 2, 7, 50, 400]))
+        K = int(rng.choice(k_pool))
+        mean_len = float(rng.choice([0.5, 3.0, 40.0, 300.0]))
+        lens = rng.poisson(mean_len, D) * (rng.random(D) > 0.1)
+        if rng.random() < 0.3:
+            lens[int(rng.integers(0, D))] += int(rng.integers(600, 3000))      # one long document
+        doc_ptr = np.r_[0, np.cumsum(lens)].astype(np.int64)
+        T = int(doc_ptr[-1])
+        # Zipf-like word choice so that frequent and rare words meet
+        w = np.minimum((V * rng.random(T) ** 2.5).astype(np.int32), V - 1)
+        alpha = float(rng.choice([0.01, 0.1, 1.0, 50.0 / K]))
+        beta = float(rng.choice([0.001, 0.01, 0.5]))
+        seed = int(rng.integers(0, 2 ** 63))
+        opts = {}
+        if rng.random() < 0.5: opts["n_chunks"] = int(rng.integers(1, 6))
+        if rng.random() < 0.4: opts["tile_tokens"] = int(rng.choice([64, 100, 1000]))
+        if rng.random() < 0.4: opts["block_threads"] = int(rng.choice([64, 128, 256, 512, 1024]))
+        if rng.random() < 0.4: opts["light_word_tokens"] = int(rng.choice([-1, 1, 5, 1 << 20]))
+        if rng.random() < 0.3: opts["long_doc_tokens"] = int(rng.choice([8, 64]))
+        if rng.random() < 0.3: opts["dz_lds_entries"] = int(rng.choice([4, 64]))
+        if rng.random() < 0.2: opts["stage_phi"] = 0
+        mode = rng.random()
+        if mode < 0.25: opts["stream_workers"] = int(rng.integers(1, 5))
+        elif mode < 0.45: opts["ablation"] = int(rng.integers(1, 4))
+        label = (case, D, V, K, T, alpha, beta, opts)
+        g = pk.Saber(doc_ptr, w, V, K, alpha, beta, seed, **opts)
+        o = oracle.Model(doc_ptr, w, V, K, alpha, beta, seed)
+        try:
+            assert np.array_equal(g.get_z(), o.z), label
+            assert_counts_equal(g, o)
+            for _ in range(2):
+                assert_estep_parity(g, o, min_agree=0.999 if T >= 5000 else 0.0)
+            # a binary32 S + Q carries a relative error of 1e-6 at most: the same absolute error in its logarithm
+            assert abs(g.loglik() - o.loglik()) <= 1e-6 * abs(o.loglik()) + 1e-6, label
+        except AssertionError as e:
+            raise AssertionError("%s: %s" % (label, e))
+        g.close(); o.close()
+
+
 def test_set_z_roundtrip_and_determinism():
     c = corpusgen.tiny(52, 200, 300, 10, 50.0)
     pk = saber()
