@@ -67,22 +67,26 @@ typedef struct saber_options {
     int32_t light_word_tokens;  /* words with fewer tokens than this keep their row of B sparse (rebuilt by a segmented
                                    count, like a row of A) and their Bhat row is formed in LDS from a base vector and
                                    the non-zeros; default K/2; negative: every word keeps a dense row */
-    int32_t stream_workers;     /* 0 (default): the token arrays of every chunk stay in device memory.  1..8: host
-                                   streaming (Sec. 3.1.2) with this many workers: the chunks' token lists stay in
-                                   pinned host memory (4 bytes per token) and each chunk is copied into one of this
+    int32_t stream_workers;     /* 1..8: host streaming (Sec. 3.1.2) with this many workers: the chunks' token lists stay
+                                   in pinned host memory (4 bytes per token) and each chunk is copied into one of this
                                    many device buffers for its pass, so that with two or more the copy of one chunk
                                    overlaps the sampling of another (three hide it reliably).  The chunk's rows of A
                                    are rebuilt right after its sampling, while its new assignments are in the
                                    buffer; resident are the rows of A and 2 bytes per token (the word-major
                                    assignments), which is what lets a corpus several times the device memory run.
-                                   Results are the same.  With profile=1, ms_sample then covers the whole chunk loop
-                                   (copies waited for, sampling, CountByDZ) and ms_count_dz is zero. */
+                                   0 (default): everything stays in device memory if the estimate of what that takes
+                                   fits what is free, else host streaming with three workers (saber_stats says which;
+                                   SABER_ENOMEM if that does not fit either).  -1: never stream.  Results are the
+                                   same.  With profile=1 and streaming, ms_sample covers the whole chunk loop (copies
+                                   waited for, sampling, CountByDZ) and ms_count_dz is zero. */
     int32_t ablation;           /* measurement aid, default 0: bit 0 samples the tokens in document order instead of
                                    word order (the layout before Sec. 3.1.3: the row of A is fetched once per document,
                                    Bhat is gathered from global memory; every word then keeps a dense row and
                                    stream_workers must be 0); bit 1 rebuilds A by a radix sort of all (document, topic)
                                    pairs instead of the segmented count of Sec. 3.3.  Results are the same. */
-    int32_t reserved[4];
+    int32_t device_mem_limit_mb;/* device memory the automatic choice above may plan with, in MB; 0 (default): what
+                                   hipMemGetInfo reports as free */
+    int32_t reserved[3];
 } saber_options;
 
 /* Sums over the iterations run since the last saber_reset_stats.  The ms_* fields need profile=1. */
@@ -112,7 +116,8 @@ typedef struct saber_stats {
     int64_t light_tokens;        /* tokens of light words (layout constant) */
     int64_t sum_light_entries;   /* non-zeros of the sparse rows the counted E-steps staged, once per word */
     int64_t next_light_entries;  /* non-zeros of the sparse rows after the last M-step */
-    int64_t reserved[2];
+    int64_t stream_workers;      /* device buffers of host streaming in use; 0: everything is resident */
+    int64_t reserved[1];
 } saber_stats;
 
 /* Fill *opt with the defaults. */

@@ -34,7 +34,7 @@ class Options(ctypes.Structure):
                 ("stage_phi", ctypes.c_int32), ("profile", ctypes.c_int32), ("long_doc_tokens", ctypes.c_int32),
                 ("dz_lds_entries", ctypes.c_int32), ("stage_min_tokens", ctypes.c_int32),
                 ("light_block_threads", ctypes.c_int32), ("light_word_tokens", ctypes.c_int32),
-                ("stream_workers", ctypes.c_int32), ("ablation", ctypes.c_int32), ("reserved", ctypes.c_int32 * 4)]
+                ("stream_workers", ctypes.c_int32), ("ablation", ctypes.c_int32), ("device_mem_limit_mb", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
 
 
 class Stats(ctypes.Structure):
@@ -46,7 +46,7 @@ class Stats(ctypes.Structure):
                 ("words_present", ctypes.c_int64), ("tiles", ctypes.c_int64), ("sum_row_fetch", ctypes.c_int64),
                 ("next_row_fetch", ctypes.c_int64), ("light_words_present", ctypes.c_int64),
                 ("light_tokens", ctypes.c_int64), ("sum_light_entries", ctypes.c_int64),
-                ("next_light_entries", ctypes.c_int64), ("reserved", ctypes.c_int64 * 2)]
+                ("next_light_entries", ctypes.c_int64), ("stream_workers", ctypes.c_int64), ("reserved", ctypes.c_int64 * 1)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_ if n != "reserved"}

@@ -639,6 +639,38 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
         c->T_light = h_light_tok_ptr.back(); c->lw_cap = lunits * 32;
         c->n_light_short = (int64_t)h_light_short.size(); c->n_light_long = (int64_t)h_light_long.size();
     }
+    // ---- resident or streamed?  stream_workers = 0 keeps everything on the device when it fits and falls back to
+    // host streaming with three buffers when it does not ----
+    if (!par && c->opt.stream_workers == 0 && c->opt.ablation == 0 && T > 0) {
+        const size_t zs = c->z16 ? 2 : 4;
+        size_t row_units = 0, slot_tokens = 0, tiles_bound = (size_t)(T / std::max(1, c->opt.tile_tokens));
+        for (int64_t d = 0; d < D; d++) row_units += (size_t)((std::min<int64_t>(doc_ptr[d + 1] - doc_ptr[d], K) + 31) / 32);
+        for (const Chunk &ch : c->chunks) {
+            slot_tokens = std::max(slot_tokens, (size_t)ch.ntok);
+            tiles_bound += (size_t)std::min<int64_t>(V, ch.ntok);
+        }
+        const size_t common = row_units * 128 + (size_t)D * 32 + tiles_bound * sizeof(Tile) +
+                              ((size_t)c->V_dense + 1) * (size_t)c->Kpad * 8 +
+                              ((size_t)V + 1) * ((size_t)c->n3pad * 4 + (size_t)c->n3 * 8 + 4) + (size_t)c->lw_cap * 8 +
+                              (size_t)T * zs + ((size_t)32 << 20);
+        const size_t resident = common + (size_t)T * (8 + zs);
+        const size_t streamed = common + 3 * slot_tokens * (8 + zs) + (size_t)T / 16;
+        size_t limit = (size_t)std::max(0, c->opt.device_mem_limit_mb) << 20;
+        if (limit == 0) {
+            size_t free_b = 0, total_b = 0;
+            HIP_TRY(hipMemGetInfo(&free_b, &total_b));
+            limit = free_b;
+        }
+        if (resident > limit - limit / 16) {
+            if (streamed > limit - limit / 16)
+                return fail(SABER_ENOMEM, "saber_init: the corpus needs about %.1f GB of device memory (%.1f GB with the token "
+                            "lists streamed from the host) and %.1f GB are available; more chunks shrink the streaming buffers",
+                            resident / 1e9, streamed / 1e9, limit / 1e9);
+            c->n_slots = 3;
+        }
+    }
+    c->stats.stream_workers = c->n_slots;
+
     // ---- word-major token arrays and tiles per chunk (host counting sort; layout only) ----
     // position of every word's segment in the word-major order (light words first, then dense rows) and the
     // slabs CountByVZ cuts the dense rows' segments into
@@ -890,6 +922,7 @@ static int create_ctx(saber_ctx **out, const int64_t *doc_ptr, const int32_t *wo
         opt.light_word_tokens = opt_in->light_word_tokens;
         opt.stream_workers = opt_in->stream_workers;
         opt.ablation = opt_in->ablation;
+        opt.device_mem_limit_mb = opt_in->device_mem_limit_mb;
         opt.stage_phi = opt_in->stage_phi; opt.profile = opt_in->profile;
         if (opt_in->stage_phi < 0) opt.stage_phi = 1;
     }
@@ -899,8 +932,8 @@ static int create_ctx(saber_ctx **out, const int64_t *doc_ptr, const int32_t *wo
     if (opt.light_block_threads > 0 && (opt.light_block_threads % 64 || opt.light_block_threads > 1024))
         return fail(SABER_EINVAL, "saber_init: light_block_threads must be a multiple of 64 in [64,1024]");
     if (opt.stage_min_tokens <= 0) opt.stage_min_tokens = 1;
-    if (opt.stream_workers < 0 || opt.stream_workers > kMaxSlots)
-        return fail(SABER_EINVAL, "saber_init: stream_workers must be in [0,%d]", kMaxSlots);
+    if (opt.stream_workers < -1 || opt.stream_workers > kMaxSlots)
+        return fail(SABER_EINVAL, "saber_init: stream_workers must be in [-1,%d]", kMaxSlots);
     if (parent) { opt.stream_workers = 0; opt.ablation = 0; }   // held-out documents are few: always resident, regular kernels
     if (opt.ablation < 0 || opt.ablation > 3) return fail(SABER_EINVAL, "saber_init: ablation must be in [0,3]");
     if (opt.ablation && opt.stream_workers) return fail(SABER_EINVAL, "saber_init: the ablation variants need stream_workers = 0");
@@ -923,7 +956,7 @@ static int create_ctx(saber_ctx **out, const int64_t *doc_ptr, const int32_t *wo
     if (!c) return fail(SABER_ENOMEM, "saber_init: out of host memory");
     c->D = D; c->T = T; c->V = V; c->K = K; c->alpha = alpha; c->beta = beta; c->seed = seed; c->opt = opt;
     c->parent = parent; c->no_state = no_state;
-    c->n_slots = opt.stream_workers;
+    c->n_slots = std::max(0, opt.stream_workers);
     c->Kpad = (K + 63) / 64 * 64;
     c->n3 = c->Kpad / 64;
     c->n3pad = (c->n3 + 63) / 64 * 64;

@@ -41,7 +41,7 @@ def header_struct_fields(name):
     for decl in body.split(";"):
         m = re.match(r"\s*(int32_t|int64_t|double|float|uint32_t|uint64_t)\s+(\w+)(\[(\d+)\])?\s*$", decl)
         if m:
-            fields.append((m.group(2), m.group(1), int(m.group(4)) if m.group(4) else 1))
+            fields.append((m.group(2), m.group(1), int(m.group(4)) if m.group(4) else 0))
     return fields
 
 
@@ -55,7 +55,7 @@ def test_binding_structs_mirror_the_header_field_by_field():
         got = [(n, t) for n, t in cls._fields_]
         assert [n for n, _ in got] == [n for n, _, _ in want], cname
         for (n, t), (_, ct, cnt) in zip(got, want):
-            assert t == (ctype_of[ct] * cnt if cnt > 1 else ctype_of[ct]), (cname, n)
+            assert t == (ctype_of[ct] * cnt if cnt else ctype_of[ct]), (cname, n)
 
 
 def test_validation_happens_before_any_device_work():

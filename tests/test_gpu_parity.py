@@ -431,6 +431,28 @@ def test_random_shapes_and_options(test_seed):
         g.close(); o.close()
 
 
+def test_streaming_is_chosen_when_the_device_memory_does_not_suffice():
+    """stream_workers = 0 plans with the free device memory (here: with a stated limit): resident when the estimate
+    fits, three streaming buffers when only that fits, an error when neither does; results do not depend on it."""
+    rng = np.random.default_rng(3)
+    lens = rng.integers(50, 150, 5000)
+    doc_ptr = np.r_[0, np.cumsum(lens)].astype(np.int64)
+    w = rng.integers(0, 50, int(doc_ptr[-1])).astype(np.int32)
+    pk = saber()
+    res = pk.Saber(doc_ptr, w, 50, 16, 0.5, 0.01, 8, n_chunks=8, device_mem_limit_mb=1000)
+    assert res.get_stats()["stream_workers"] == 0
+    auto = pk.Saber(doc_ptr, w, 50, 16, 0.5, 0.01, 8, n_chunks=8, device_mem_limit_mb=40)
+    assert auto.get_stats()["stream_workers"] == 3
+    never = pk.Saber(doc_ptr, w, 50, 16, 0.5, 0.01, 8, n_chunks=8, device_mem_limit_mb=40, stream_workers=-1)
+    assert never.get_stats()["stream_workers"] == 0
+    for g in (res, auto, never):
+        g.iterate(3)
+    assert np.array_equal(res.get_z(), auto.get_z()) and np.array_equal(res.get_z(), never.get_z())
+    with pytest.raises(pk.SaberError) as e:
+        pk.Saber(doc_ptr, w, 50, 16, 0.5, 0.01, 8, n_chunks=8, device_mem_limit_mb=33)
+    assert e.value.code == pk.binding.SABER_ENOMEM and "streamed" in str(e.value)
+
+
 def test_set_z_roundtrip_and_determinism():
     c = corpusgen.tiny(52, 200, 300, 10, 50.0)
     pk = saber()
