@@ -23,8 +23,9 @@
  *     chunk count.
  *   - Limits: 1 <= K <= 262144 (three searched tree levels of width 64), D < 2^31, T < 2^40 (the corpus is cut
  *     into document chunks of fewer than 2^30 tokens when it is larger), and the longest document must be
- *     shorter than 2^(32 - ceil(log2 K)).  Everything stays resident in device memory: about 10 bytes per
- *     token plus 8*V*K bytes.
+ *     shorter than 2^(32 - ceil(log2 K)).  Device memory: about 16 bytes per token plus 8*K bytes per frequent
+ *     word and 8 bytes per non-zero count of the others when everything is resident; about 6 bytes per token
+ *     and 4 bytes per token of pinned host memory with host streaming (saber_options.stream_workers).
  */
 #ifndef SABER_H
 #define SABER_H
