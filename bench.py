@@ -168,7 +168,8 @@ def run_streaming(corpus, K, steps, warmup, workers, chunks):
     import torch
     import paper_1610_02496_amd as pk
     s = corpus.spec
-    g = pk.Saber(corpus.doc_ptr, corpus.word_ids, s.V, K, 50.0 / K, s.beta, s.seed, stream_workers=workers, n_chunks=chunks)
+    g = pk.Saber(corpus.doc_ptr, corpus.word_ids, s.V, K, 50.0 / K, s.beta, s.seed, stream_workers=workers,
+                 **({"n_chunks": chunks} if chunks else {}))
     g.iterate(warmup)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -204,7 +205,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=48)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3"])
+    ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"],
+                    help="C3 (default) is the benchmark line; C4 (738 M tokens) and C5 (7.1 G tokens: 6 minutes of corpus "
+                         "generation, 30 GB of host memory for the token list) are the large workloads")
     ap.add_argument("--docs", type=int, default=0, help="use only a document prefix (experiments; 0 = full corpus)")
     ap.add_argument("--no-also", action="store_true", help="skip the secondary K")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -239,6 +242,10 @@ def main():
 
     import corpusgen
     spec = corpusgen.SPECS[args.workload]
+    if args.workload in ("C4", "C5"):
+        os.environ.setdefault("LDA_CORPUS_PROGRESS", "2000000")   # the generator reports on stderr while it works
+        if args.streaming == "3:4":
+            args.streaming = "3:0"                                 # chunks as the library cuts them
     if args.docs:
         spec = corpusgen.scaled(spec, args.docs)
     if args.topic_conc > 0:
@@ -287,9 +294,11 @@ def main():
         "value": main_res["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": main_res["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "%s: seeded LDA corpus D=%d V=%d T=%d (NYTimes-shaped), fitted K=%d, alpha=50/K, beta=0.01, "
+        "config": {"workload": "%s: seeded LDA corpus D=%d V=%d T=%d (%s-shaped), fitted K=%d, alpha=50/K, beta=0.01, "
                                "iterations %d..%d from the Philox initial assignment"
-                               % (spec.name, spec.D, spec.V, corpus.T, spec.K, args.warmup + 1, args.warmup + args.steps)},
+                               % (spec.name, spec.D, spec.V, corpus.T,
+                                  {"C4": "PubMed", "C5": "ClueWeb12-subset"}.get(args.workload, "NYTimes"), spec.K,
+                                  args.warmup + 1, args.warmup + args.steps)},
         "roofline": main_res["roofline"], "cpu_baseline": cpu,
         "detail": {k: v for k, v in main_res.items() if k not in ("roofline", "holdout")},
     }

@@ -643,22 +643,22 @@ __global__ void scatter_zwm_kernel(const Tile *tiles, const uint32_t *tok_t, con
         z_chunk[tok_t[tile.begin + i]] = z_wm[tile.wm_begin + i];
 }
 
-// Host streaming: the document of every token of a chunk, from the canonical token numbers.  The document of
-// token t is the last d with doc_ptr[d] <= t; coarse[j] is that document for t = 64 j, so the search runs over
-// the few documents between two neighbouring entries.
+// Host streaming: the document of every token of a chunk, from the canonical token numbers, with one 16-byte
+// look-up per token.  blocks[b] describes the canonical tokens 64 b .. 64 b + 63: .x = ordinal (among the non-empty
+// documents) of the document that holds token 64 b, .y/.z = 64-bit mask whose bit j > 0 says that token 64 b + j is
+// the first of its document.  The ordinal of token t's document is .x plus the mask bits up to t's own; ne_doc
+// maps ordinals to document numbers when the corpus has empty documents (null: they are the same).
 __global__ void expand_tok_doc_kernel(const uint32_t *__restrict__ tok_t, int64_t n, int64_t t0,
-                                      const int32_t *__restrict__ coarse, const int64_t *__restrict__ doc_ptr,
+                                      const uint4 *__restrict__ blocks, const int32_t *__restrict__ ne_doc,
                                       int32_t *__restrict__ tok_doc) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (; i < n; i += stride) {
         const int64_t t = t0 + (int64_t)tok_t[i];
-        int32_t lo = coarse[t >> 6], hi = coarse[(t >> 6) + 1];
-        while (lo < hi) {
-            const int32_t mid = lo + ((hi - lo + 1) >> 1);
-            if (doc_ptr[mid] <= t) lo = mid; else hi = mid - 1;
-        }
-        tok_doc[i] = lo;
+        const uint4 q = blocks[t >> 6];
+        const unsigned long long mask = (((unsigned long long)q.z << 32) | (unsigned long long)q.y) & (~0ull >> (63 - (int)(t & 63)));
+        const int32_t ord = (int32_t)q.x + (int32_t)__popcll(mask);
+        tok_doc[i] = ne_doc ? ne_doc[ord] : ord;
     }
 }
 
