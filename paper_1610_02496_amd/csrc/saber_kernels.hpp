@@ -273,6 +273,14 @@ __device__ __forceinline__ uint4 load_block(uint32_t addr_lo, uint32_t addr_hi, 
     return make_uint4(v[0], v[1], v[2], v[3]);
 }
 
+// The second 256-entry block of the same row (same descriptor, 1 KB further on).
+__device__ __forceinline__ uint4 load_block2(uint32_t addr_lo, uint32_t addr_hi, uint32_t row_bytes, int lane) {
+    void *row = reinterpret_cast<void *>(((uint64_t)addr_hi << 32) | (uint64_t)addr_lo);
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(row, (short)0, (int)row_bytes, 0x00020000);
+    const auto v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane * 16, 16 * kWave, 0);
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
 // clear bit `bit` of a wave-uniform mask (one scalar instruction)
 __device__ __forceinline__ unsigned long long clear_bit(unsigned long long m, int bit) {
     asm("s_bitset0_b64 %0, %1" : "+s"(m) : "s"(bit));
@@ -411,13 +419,15 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
         // `cur` holds the first block of the run's row (fetched during the previous run) and cur_bytes the row's
         // padded length; the first block of the next run's row is fetched into `nxt` before this run's
         // arithmetic starts.
-        auto do_run = [&](const uint4 &cur, const uint32_t cur_bytes, uint4 &nxt, uint32_t &nxt_bytes) {
+        auto do_run = [&](const uint4 &cur, const uint4 &cur2, const uint32_t cur_bytes, uint4 &nxt, uint4 &nxt2, uint32_t &nxt_bytes) {
             const bool more = rest != 0ull;       // run starts are marked on active lanes only
             const int s_end = more ? (int)__builtin_ctzll(rest) : n;
             if (more) {
                 rest = clear_bit(rest, s_end);
                 nxt_bytes = readlane_u32(ra_bytes, s_end);
                 nxt = load_block(readlane_u32(ra_lo, s_end), readlane_u32(ra_hi, s_end), nxt_bytes, lane);
+                if (nxt_bytes > 16u * kWave)   // a second block: requested now as well, not when the run gets there
+                    nxt2 = load_block2(readlane_u32(ra_lo, s_end), readlane_u32(ra_hi, s_end), nxt_bytes, lane);
             }
             const unsigned long long below_end = ~0ull >> (kWave - s_end);   // 1 <= s_end <= 64
             const unsigned long long in_run = below_end & ~below_s;
@@ -460,7 +470,7 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
             const int kd = (int)readlane_u32(rec.y, s);
             const uint32_t *row = p.cd_ent + (size_t)readlane_u32(rec.x, s) * 32u;
             const int nblk = (kd + 4 * kWave - 1) / (4 * kWave);
-            const uint4 e1 = load_block(row + 4 * kWave, kd - 4 * kWave, lane);
+            const uint4 e1 = cur2;
             RowBlock b1;
             block_products<STAGED, B16>(e1, bits, tmask, lds_phi, phi_row, b1);
             const float t1 = readlane_f32(b1.incl, 63);
@@ -506,11 +516,12 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
 
         uint32_t bytes_a = readlane_u32(ra_bytes, 0), bytes_b = 0u;
         uint4 blk_a = load_block(readlane_u32(ra_lo, 0), readlane_u32(ra_hi, 0), bytes_a, lane);
-        uint4 blk_b = make_uint4(0u, 0u, 0u, 0u);
+        uint4 blk_b = make_uint4(0u, 0u, 0u, 0u), blk_a2 = blk_b, blk_b2 = blk_b;
+        if (bytes_a > 16u * kWave) blk_a2 = load_block2(readlane_u32(ra_lo, 0), readlane_u32(ra_hi, 0), bytes_a, lane);
         while (s < n) {
-            do_run(blk_a, bytes_a, blk_b, bytes_b);
+            do_run(blk_a, blk_a2, bytes_a, blk_b, blk_b2, bytes_b);
             if (s >= n) break;
-            do_run(blk_b, bytes_b, blk_a, bytes_a);
+            do_run(blk_b, blk_b2, bytes_b, blk_a, blk_a2, bytes_a);
         }
 
         if (MODE == MODE_SAMPLE && dense_mask) {
