@@ -422,12 +422,18 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
         auto do_run = [&](const uint4 &cur, const uint4 &cur2, const uint32_t cur_bytes, uint4 &nxt, uint4 &nxt2, uint32_t &nxt_bytes) {
             const bool more = rest != 0ull;       // run starts are marked on active lanes only
             const int s_end = more ? (int)__builtin_ctzll(rest) : n;
-            if (more) {
-                rest = clear_bit(rest, s_end);
-                nxt_bytes = readlane_u32(ra_bytes, s_end);
-                nxt = load_block(readlane_u32(ra_lo, s_end), readlane_u32(ra_hi, s_end), nxt_bytes, lane);
-                if (nxt_bytes > 16u * kWave)   // a second block: requested now as well, not when the run gets there
-                    nxt2 = load_block2(readlane_u32(ra_lo, s_end), readlane_u32(ra_hi, s_end), nxt_bytes, lane);
+            // The next run's row is requested here, without any branch around the two loads: after the last run
+            // (and for the second block of a short row) the descriptor's length makes every lane fall outside the
+            // row, which returns zeros and moves no data.  A load inside a branch would make the compiler wait for
+            // ALL outstanding loads where the branches meet, i.e. for the row just requested, before this run's
+            // arithmetic - the request has to be unconditional for its latency to pass under the arithmetic.
+            {
+                const int src = more ? s_end : 0;
+                rest = clear_bit(rest, src);      // bit 0 is never set in `rest`
+                nxt_bytes = more ? readlane_u32(ra_bytes, src) : 0u;
+                const uint32_t lo = readlane_u32(ra_lo, src), hi = readlane_u32(ra_hi, src);
+                nxt = load_block(lo, hi, nxt_bytes, lane);
+                nxt2 = load_block2(lo, hi, nxt_bytes, lane);
             }
             const unsigned long long below_end = ~0ull >> (kWave - s_end);   // 1 <= s_end <= 64
             const unsigned long long in_run = below_end & ~below_s;
@@ -517,7 +523,7 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
         uint32_t bytes_a = readlane_u32(ra_bytes, 0), bytes_b = 0u;
         uint4 blk_a = load_block(readlane_u32(ra_lo, 0), readlane_u32(ra_hi, 0), bytes_a, lane);
         uint4 blk_b = make_uint4(0u, 0u, 0u, 0u), blk_a2 = blk_b, blk_b2 = blk_b;
-        if (bytes_a > 16u * kWave) blk_a2 = load_block2(readlane_u32(ra_lo, 0), readlane_u32(ra_hi, 0), bytes_a, lane);
+        blk_a2 = load_block2(readlane_u32(ra_lo, 0), readlane_u32(ra_hi, 0), bytes_a, lane);
         while (s < n) {
             do_run(blk_a, blk_a2, bytes_a, blk_b, blk_b2, bytes_b);
             if (s >= n) break;
