@@ -618,14 +618,22 @@ __device__ __forceinline__ void block_for_each_z(const ZT *__restrict__ zs, int6
     for (int64_t i = threadIdx.x; i < head; i += blockDim.x) f((uint32_t)zs[i]);
     const int64_t nvec = (n - head) / kPer;
     const uint4 *__restrict__ v = reinterpret_cast<const uint4 *>(zs + head);
-    for (int64_t j = threadIdx.x; j < nvec; j += blockDim.x) {
-        const uint4 q = v[j];
+    // the next 16 bytes are requested before the current ones are handed to f: f's work (LDS atomics, as a rule)
+    // does not depend on them, so their latency passes under it
+    int64_t j = threadIdx.x;
+    uint4 q = make_uint4(0u, 0u, 0u, 0u);
+    if (j < nvec) q = v[j];
+    while (j < nvec) {
+        const int64_t jn = j + blockDim.x;
+        uint4 qn = make_uint4(0u, 0u, 0u, 0u);
+        if (jn < nvec) qn = v[jn];
         if (sizeof(ZT) == 2) {
             f(q.x & 0xffffu); f(q.x >> 16); f(q.y & 0xffffu); f(q.y >> 16);
             f(q.z & 0xffffu); f(q.z >> 16); f(q.w & 0xffffu); f(q.w >> 16);
         } else {
             f(q.x); f(q.y); f(q.z); f(q.w);
         }
+        q = qn; j = jn;
     }
     for (int64_t i = head + nvec * kPer + threadIdx.x; i < n; i += blockDim.x) f((uint32_t)zs[i]);
 }
