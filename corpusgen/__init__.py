@@ -23,8 +23,9 @@ _lib = None
 
 
 def build(force: bool = False) -> str:
-    """Compile the generator with gcc (about a second).  Without ``force`` an existing library is used as it is."""
-    if force or not os.path.exists(_LIB):
+    """Compile the generator with gcc (about a second).  Without ``force`` the library is rebuilt only when it is
+    missing or older than the C source."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp%d" % os.getpid()
         subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)

@@ -30,6 +30,7 @@
 #ifndef SABER_H
 #define SABER_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -118,8 +119,23 @@ typedef struct saber_stats {
     int64_t sum_light_entries;   /* non-zeros of the sparse rows the counted E-steps staged, once per word */
     int64_t next_light_entries;  /* non-zeros of the sparse rows after the last M-step */
     int64_t stream_workers;      /* device buffers of host streaming in use; 0: everything is resident */
-    int64_t reserved[1];
+    int64_t chunks;              /* document chunks the corpus is cut into (Sec. 3.1.2; layout constant) */
 } saber_stats;
+
+/*
+ * Where device memory and the compute stream come from (Sec. 2.1's problem statement leaves both to the host
+ * program; a caller that runs PyTorch hands over its caching allocator and its current stream).
+ *   alloc(bytes)   returns DEVICE memory of at least `bytes` bytes, 256-byte aligned, on the current device, or NULL
+ *   dealloc(ptr)   takes back what alloc returned
+ *   hip_stream     a hipStream_t on which every kernel and every ordered copy of the library then runs; NULL: each
+ *                  context creates (and destroys) a stream of its own
+ * alloc and dealloc are given together; both NULL restores hipMalloc / hipFree.  The setting is process-wide and
+ * applies to contexts created afterwards (and to saber_bandwidth_probe); a context keeps the hooks it was created
+ * with until saber_free, so they must stay callable until then, and the stream must outlive the context.  With a
+ * caller's stream the library still synchronises that stream before it returns from a call that promises completed
+ * work.  Pinned host memory of host streaming is always the library's own.  Errors: EINVAL (only one of alloc/dealloc).
+ */
+int saber_set_hooks(void *(*alloc)(size_t bytes), void (*dealloc)(void *ptr), void *hip_stream);
 
 /* Fill *opt with the defaults. */
 void saber_options_default(saber_options *opt);
@@ -142,14 +158,20 @@ int saber_init(saber_ctx **out, const int64_t *doc_ptr, const int32_t *word_ids,
  * Synchronous: all work has finished when it returns.  n = 0 is a no-op.  Errors: EINVAL (n<0), EDEVICE. */
 int saber_iterate(saber_ctx *ctx, int32_t n);
 
-/* Number of non-zeros of A (size of cd_topic / cd_count for saber_counts). */
+/* Number of non-zeros of the document-topic count matrix A of Sec. 2.1 (A_dk = tokens of document d assigned
+ * to topic k), i.e. the size of cd_topic / cd_count for saber_counts.  Errors: EINVAL, ENOMEM, EDEVICE. */
 int saber_counts_nnz(saber_ctx *ctx, int64_t *nnz_cd);
 
 /*
- * Copy out the count matrices of the last completed M-step.
- *   cd_row_ptr [D+1], cd_topic [nnz], cd_count [nnz]: A in CSR, topics ascending within a row
- *   cwk [V*K] row-major by word (B);  ck [K] topic totals sum_v B_vk
- * Any of the five may be NULL to skip it (cd_topic and cd_count need cd_row_ptr).
+ * Copy out the count matrices of Sec. 2.1 as the last completed M-step of Alg. 1 (CountByDZ, CountByVZ) left them:
+ * A (D x K, sparse: A_dk = tokens of document d with topic k) and B (V x K, dense: B_vk = tokens of word v with
+ * topic k).
+ *   cd_row_ptr [D+1], cd_topic [nnz], cd_count [nnz]: A in CSR, topics ascending within a row (the order the
+ *                                                     segmented count of Sec. 3.3 produces; the sparse draw of
+ *                                                     Alg. 2 depends on it)
+ *   cwk [V*K] row-major by word (B);  ck [K] topic totals sum_v B_vk (the denominators of Eq. 2 without V beta)
+ * Any of the five may be NULL to skip it (cd_topic and cd_count need cd_row_ptr).  All are host buffers owned by
+ * the caller.  Errors: EINVAL, ENOMEM, EDEVICE.
  */
 int saber_counts(saber_ctx *ctx, int64_t *cd_row_ptr, int32_t *cd_topic, int32_t *cd_count, int32_t *cwk,
                  int64_t *ck);
@@ -159,6 +181,8 @@ int saber_counts(saber_ctx *ctx, int64_t *cd_row_ptr, int32_t *cd_topic, int32_t
  *   (1/T) sum_t [ ln(S_t + Q_w) - ln(L_d + K alpha) ]  =  (1/T) sum_t ln sum_k theta_dk Bhat_wk
  * (the paper names per-token log-likelihood as its quality metric in Sec. 4 and gives no formula;
  * this is the predictive likelihood of the training tokens, a by-product of the sampler's normaliser).
+ * Both sums are reduced on the device in binary64 and in a fixed order (the result is the same in every run); one
+ * double comes back.  per_token_ll is a host pointer.  T = 0 gives 0.  Errors: EINVAL, EDEVICE.
  */
 int saber_loglik(saber_ctx *ctx, double *per_token_ll);
 
@@ -192,12 +216,16 @@ const char *saber_last_error(void);
 
 /* ---- state exchange (checkpointing, and the hooks the parity tests need) ---- */
 
-/* Current assignments, z[T] in canonical token order. */
+/* The state of Alg. 1 between iterations is the topic assignment k of every token of the list L (Sec. 2.1: tokens
+ * are triplets (d, v, k)); everything else (A, B, Bhat, the trees) is rebuilt from it by the M-step.
+ * saber_get_z: current assignments, z[T] (host) in canonical token order.  Errors: EINVAL, ENOMEM, EDEVICE. */
 int saber_get_z(saber_ctx *ctx, int32_t *z);
-/* Replace the assignments (each in [0,K)), set the iteration counter to iter and redo the M-step.
- * The next E-step then uses Philox counter word 2 = iter + 1. */
+/* Replace the assignments (z[T], host, each in [0,K)), set the iteration counter to iter and redo the M-step of
+ * Alg. 1 (CountByDZ, CountByVZ, Preprocess, BuildTree) on them.  The next E-step then uses Philox counter word
+ * 2 = iter + 1.  Errors: EINVAL (a topic out of range), ENOMEM, EDEVICE. */
 int saber_set_z(saber_ctx *ctx, const int32_t *z, uint32_t iter);
-/* Iteration counter (0 after init). */
+/* Number of iterations of Alg. 1's outer loop completed so far (0 after init, or the value given to
+ * saber_set_z); it is the third word of the Philox counter of the last E-step. */
 int saber_get_iteration(saber_ctx *ctx, uint32_t *iter);
 
 /*
@@ -216,21 +244,6 @@ int saber_get_stats(saber_ctx *ctx, saber_stats *out);
 int saber_reset_stats(saber_ctx *ctx);
 /* HIP stream the library launches on (a hipStream_t), for callers that want to order work against it. */
 int saber_get_stream(saber_ctx *ctx, void **hip_stream);
-
-/* Measurement aid for the choice between the alias table and the tree (Sec. 3.2.3): builds an alias table (Vose's
- * construction, one thread per row) from the current Bhat row of every word that keeps a dense row, and reports
- * the device time of that build in *ms_build and the number of rows in *rows_built (may be null); the sampler
- * does not use the tables.  For the m words listed (host array; each must keep a dense row, see
- * light_word_tokens) the table is returned in prob[m][K] and alias[m][K] (host): bucket k yields topic k with
- * probability prob, else topic alias.  All memory the call needs is allocated and freed inside it (20 bytes per
- * row and topic; more than 64 GB is refused with SABER_ERANGE). */
-int saber_alias_build_probe(saber_ctx *ctx, const int32_t *words, int32_t m, float *prob, int32_t *alias,
-                            double *ms_build, int32_t *rows_built);
-
-/* Measurement aid, independent of any context: copies `bytes` bytes device-to-device `reps` times with a
- * plain streaming kernel and reports read+write bandwidth in GB/s (the achievable-HBM yardstick, and the
- * kernel the profiler's FETCH_SIZE / WRITE_SIZE counters are calibrated against). */
-int saber_bandwidth_probe(int64_t bytes, int32_t reps, double *gb_per_s);
 
 #ifdef __cplusplus
 }

@@ -22,9 +22,9 @@ c_f32, c_f64, c_int = ctypes.c_float, ctypes.c_double, ctypes.c_int
 
 
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc.  Without ``force`` an existing library is used as it is: rebuild
-    (``python __graft_entry__.py``) after editing the C source."""
-    if force or not os.path.exists(_LIB):
+    """Compile the oracle with gcc (about a second).  Without ``force`` the library is rebuilt only when it is
+    missing or older than the C source, so that an edited oracle is never judged through a stale binary."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp%d" % os.getpid()
         subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-Wall", "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)

@@ -17,7 +17,7 @@ _STATUS = {0: "SABER_OK", -1: "SABER_EINVAL", -2: "SABER_ENOMEM", -3: "SABER_EDE
            -5: "SABER_ERANGE"}
 
 # every symbol include/saber.h declares
-EXPORTS = ["saber_options_default", "saber_init_ex", "saber_init", "saber_iterate", "saber_counts_nnz",
+EXPORTS = ["saber_set_hooks", "saber_options_default", "saber_init_ex", "saber_init", "saber_iterate", "saber_counts_nnz",
            "saber_counts", "saber_loglik", "saber_holdout_loglik", "saber_free", "saber_last_error", "saber_get_z", "saber_set_z",
            "saber_get_iteration", "saber_token_probs", "saber_get_phi", "saber_get_stats", "saber_reset_stats",
            "saber_get_stream", "saber_bandwidth_probe", "saber_alias_build_probe"]
@@ -46,7 +46,7 @@ class Stats(ctypes.Structure):
                 ("words_present", ctypes.c_int64), ("tiles", ctypes.c_int64), ("sum_row_fetch", ctypes.c_int64),
                 ("next_row_fetch", ctypes.c_int64), ("light_words_present", ctypes.c_int64),
                 ("light_tokens", ctypes.c_int64), ("sum_light_entries", ctypes.c_int64),
-                ("next_light_entries", ctypes.c_int64), ("stream_workers", ctypes.c_int64), ("reserved", ctypes.c_int64 * 1)]
+                ("next_light_entries", ctypes.c_int64), ("stream_workers", ctypes.c_int64), ("chunks", ctypes.c_int64)]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_ if n != "reserved"}
@@ -70,6 +70,7 @@ def load_library():
     vp, i32, i64, u32, u64, f32 = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32,
                                    ctypes.c_uint64, ctypes.c_float)
     sig = {
+        "saber_set_hooks": (ctypes.c_int, [vp, vp, vp]),
         "saber_options_default": (None, [vp]),
         "saber_init_ex": (ctypes.c_int, [vp, vp, vp, i64, i32, i32, f32, f32, u64, vp]),
         "saber_init": (ctypes.c_int, [vp, vp, vp, i64, i32, i32, f32, f32, u64]),
@@ -105,6 +106,48 @@ def _check(rc):
 
 def _ptr(a):
     return None if a is None else a.ctypes.data
+
+
+ALLOC_FN = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t)
+DEALLOC_FN = ctypes.CFUNCTYPE(None, ctypes.c_void_p)
+_hook_refs = None   # the callbacks in force: ctypes function objects must outlive their use by the library
+
+
+def set_hooks(alloc=None, dealloc=None, hip_stream=0):
+    """saber_set_hooks: ``alloc(bytes) -> device address`` / ``dealloc(address)`` (Python callables or None for
+    hipMalloc / hipFree) and the hipStream_t (an integer; 0: every context creates its own) used by contexts created
+    from now on."""
+    global _hook_refs
+    a = ALLOC_FN(alloc) if alloc is not None else None
+    d = DEALLOC_FN(dealloc) if dealloc is not None else None
+    _check(load_library().saber_set_hooks(ctypes.cast(a, ctypes.c_void_p) if a else None,
+                                          ctypes.cast(d, ctypes.c_void_p) if d else None,
+                                          ctypes.c_void_p(int(hip_stream)) if hip_stream else None))
+    _hook_refs = (_hook_refs or []) + [(a, d)]   # earlier contexts may still hold earlier callbacks
+
+
+def set_torch_hooks(stream=None):
+    """Device memory from PyTorch's caching allocator and kernels on a torch stream (default: the current one).
+    PyTorch serves as plumbing only: it hands out device memory and the stream."""
+    import torch
+    st = stream if stream is not None else torch.cuda.current_stream()
+    dev = torch.cuda.current_device()
+
+    def alloc(nbytes):
+        try:
+            return torch.cuda.caching_allocator_alloc(int(nbytes), dev, st)
+        except Exception:   # out of memory: the library reports SABER_ENOMEM
+            return None
+
+    def dealloc(ptr):
+        torch.cuda.caching_allocator_delete(ptr)
+
+    set_hooks(alloc, dealloc, st.cuda_stream)
+
+
+def clear_hooks():
+    """Back to hipMalloc / hipFree and a library-owned stream per context."""
+    set_hooks(None, None, 0)
 
 
 def options_default() -> Options:

@@ -1,6 +1,7 @@
 """Build the HIP library (libsaber.so) for gfx950 with hipcc, in-tree."""
 from __future__ import annotations
 
+import glob
 import os
 import subprocess
 
@@ -8,8 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsaber.so")
 SOURCES = [os.path.join(CSRC, "saber.hip")]
-DEPS = SOURCES + [os.path.join(CSRC, "saber_kernels.hpp"),
-                  os.path.join(os.path.dirname(HERE), "include", "saber.h")]
+# every header saber.hip includes: an edit to any of them marks the library stale
+DEPS = SOURCES + sorted(glob.glob(os.path.join(CSRC, "*.hpp"))) + sorted(glob.glob(os.path.join(os.path.dirname(HERE), "include", "*.h")))
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

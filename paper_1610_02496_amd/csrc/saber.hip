@@ -4,6 +4,7 @@
 #include "saber_kernels.hpp"
 #include "saber_ablation.hpp"
 #include "../../include/saber.h"
+#include "../../include/saber_measure.h"
 
 #include <algorithm>
 #include <cmath>
@@ -38,6 +39,54 @@ static int fail(int code, const char *fmt, ...) {
 extern "C" const char *saber_last_error(void) { return g_err; }
 
 // ------------------------------------------------------------------------------------------------
+// device memory
+// ------------------------------------------------------------------------------------------------
+// Work space of the log-likelihood reduction: the per-tile sums of one chunk, then kLlTail doubles - the workgroup sums
+// of one reduction pass, the running total over chunks, the normaliser and the result.
+constexpr size_t kLlTail = (size_t)kReduceBlocks + 3;
+struct LlScratch { double *tile_part, *block_part, *acc, *norm, *result; };
+static LlScratch ll_scratch(double *base, size_t max_tiles) {
+    LlScratch w;
+    w.tile_part = base; w.block_part = base + max_tiles; w.acc = w.block_part + kReduceBlocks; w.norm = w.acc + 1; w.result = w.norm + 1;
+    return w;
+}
+
+// Where device memory and the compute stream come from (saber_set_hooks).  A context keeps the hooks it was created
+// with, so its memory goes back through the deallocator that matches its allocator.
+struct Hooks {
+    void *(*alloc)(size_t) = nullptr;
+    void (*dealloc)(void *) = nullptr;
+    hipStream_t stream = nullptr;
+    bool have_stream = false;
+};
+static Hooks g_hooks;
+
+static int hook_alloc(const Hooks &h, void **p, size_t bytes) {
+    *p = nullptr;
+    bytes = std::max<size_t>(bytes, 1);
+    if (h.alloc) {
+        *p = h.alloc(bytes);
+        if (!*p) return fail(SABER_ENOMEM, "the caller's allocator returned no memory for %zu bytes", bytes);
+        if (reinterpret_cast<uintptr_t>(*p) & 255u) {
+            void *q = *p; *p = nullptr;
+            if (h.dealloc) h.dealloc(q);
+            return fail(SABER_EINVAL, "the caller's allocator returned memory that is not 256-byte aligned");
+        }
+        return SABER_OK;
+    }
+    HIP_TRY(hipMalloc(p, bytes));
+    return SABER_OK;
+}
+static void hook_free(const Hooks &h, void *p) {
+    if (!p) return;
+    if (h.alloc) { if (h.dealloc) h.dealloc(p); }
+    else (void)hipFree(p);
+}
+template <typename T>
+static int dev_alloc(const Hooks &h, T **p, size_t n) { return hook_alloc(h, (void **)p, std::max<size_t>(n, 1) * sizeof(T)); }
+static void dev_free(const Hooks &h, void *p) { hook_free(h, p); }
+
+// ------------------------------------------------------------------------------------------------
 // context
 // ------------------------------------------------------------------------------------------------
 struct Chunk {
@@ -58,6 +107,9 @@ constexpr int kCtr = 8;   // device counters per timed iteration
 enum { EV_BEGIN = 0, EV_SAMPLE, EV_DZ, EV_CK, EV_PHI, EV_PER_ITER };
 
 struct saber_ctx {
+    Hooks hooks;                      // allocator and stream in force when the context was created
+    bool own_stream = false;
+    int device = 0;                   // the HIP device the context lives on
     int64_t D = 0, T = 0;
     int32_t V = 0, K = 0, Kpad = 0, n3 = 0, n3pad = 0, nwords = 0;
     float alpha = 0, beta = 0, vbeta = 0;
@@ -65,7 +117,6 @@ struct saber_ctx {
     uint32_t iter = 0, topic_bits = 0, topic_mask = 0;
     bool z16 = false, staged = false, b16 = false;
     saber_options opt{};
-    double ll_const = 0.0;            // sum_d L_d ln(L_d + K alpha)
     int64_t max_doc_len = 0;
     hipStream_t stream = nullptr;
     // device arrays
@@ -108,7 +159,8 @@ struct saber_ctx {
     unsigned long long *dense_slots = nullptr; // [kMaxTimedIters][kDenseSlots] dense-branch tokens, spread over slots
     unsigned long long *counters = nullptr; // [kMaxTimedIters][kCtr]: dense-branch tokens, nnz(A), sum K_d L_d, sum K_d U_d,
                                             // non-zeros of the sparse rows of B
-    double *ll_partial = nullptr;     // [max tiles per chunk]
+    // log-likelihood reduction: [max tiles per chunk] per-tile sums, then kLlTail doubles (LlScratch below)
+    double *ll_partial = nullptr;
     std::vector<Chunk> chunks;
     int64_t total_tiles = 0, max_chunk_tiles = 0;
     // measurement
@@ -143,17 +195,17 @@ struct saber_ctx {
     unsigned sort_end_bit = 0;
 };
 
-template <typename T>
-static int dev_alloc(T **p, size_t n) {
-    *p = nullptr;
-    HIP_TRY(hipMalloc((void **)p, std::max<size_t>(n, 1) * sizeof(T)));
-    return SABER_OK;
-}
-static void dev_free(void *p) { if (p) (void)hipFree(p); }
-
 static inline int grid_for(int64_t n, int block, int cap = 65535 * 16) {
     int64_t g = (n + block - 1) / block;
     return (int)std::max<int64_t>(1, std::min<int64_t>(g, cap));
+}
+
+extern "C" int saber_set_hooks(void *(*alloc)(size_t), void (*dealloc)(void *), void *hip_stream) {
+    if ((alloc == nullptr) != (dealloc == nullptr))
+        return fail(SABER_EINVAL, "saber_set_hooks: alloc and dealloc must be given together");
+    g_hooks.alloc = alloc; g_hooks.dealloc = dealloc;
+    g_hooks.stream = reinterpret_cast<hipStream_t>(hip_stream); g_hooks.have_stream = hip_stream != nullptr;
+    return SABER_OK;
 }
 
 extern "C" void saber_options_default(saber_options *opt) {
@@ -166,39 +218,39 @@ extern "C" void saber_options_default(saber_options *opt) {
 extern "C" void saber_free(saber_ctx *c) {
     if (!c) return;
     if (c->stream) (void)hipStreamSynchronize(c->stream);
-    dev_free(c->z); dev_free(c->tok_doc); dev_free(c->tok_t); dev_free(c->tiles); dev_free(c->docrec);
-    dev_free(c->cd_ent); dev_free(c->doc_ptr); dev_free(c->short_docs); dev_free(c->long_docs);
-    dev_free(c->doc_words); dev_free(c->counters); dev_free(c->dense_slots); dev_free(c->ll_partial); dev_free(c->z_wm);
+    auto release = [c](void *p) { dev_free(c->hooks, p); };
+    release(c->z); release(c->tok_doc); release(c->tok_t); release(c->tiles); release(c->docrec);
+    release(c->cd_ent); release(c->doc_ptr); release(c->short_docs); release(c->long_docs);
+    release(c->doc_words); release(c->counters); release(c->dense_slots); release(c->ll_partial); release(c->z_wm);
     if (!c->parent) {   // the model's arrays belong to the model
-        dev_free(c->cwk); dev_free(c->ck); dev_free(c->denom); dev_free(c->phi); dev_free(c->l3_64); dev_free(c->l3);
-        dev_free(c->sumphi); dev_free(c->row_word); dev_free(c->light_words); dev_free(c->light_short);
-        dev_free(c->light_long); dev_free(c->light_tok_ptr); dev_free(c->wrec); dev_free(c->lw_ent); dev_free(c->lw_phi);
-        dev_free(c->vz_items);
+        release(c->cwk); release(c->ck); release(c->denom); release(c->phi); release(c->l3_64); release(c->l3);
+        release(c->sumphi); release(c->row_word); release(c->light_words); release(c->light_short);
+        release(c->light_long); release(c->light_tok_ptr); release(c->wrec); release(c->lw_ent); release(c->lw_phi);
+        release(c->vz_items);
     }
     if (c->have_events) for (auto &e : c->ev) if (e) (void)hipEventDestroy(e);
     if (c->s_in) { (void)hipStreamSynchronize(c->s_in); (void)hipStreamDestroy(c->s_in); }
     for (int s = 0; s < kMaxSlots; s++) {
-        dev_free(c->slot_tok_doc[s]); dev_free(c->slot_tok_t[s]); dev_free(c->slot_z[s]);
+        release(c->slot_tok_doc[s]); release(c->slot_tok_t[s]); release(c->slot_z[s]);
         if (c->ev_loaded[s]) (void)hipEventDestroy(c->ev_loaded[s]);
         if (c->ev_done[s]) (void)hipEventDestroy(c->ev_done[s]);
     }
-    dev_free(c->doc_blocks); dev_free(c->ne_doc);
-    dev_free(c->word_ids_d); dev_free(c->word_row_d); dev_free(c->sort_keys); dev_free(c->sort_keys_out);
-    dev_free(c->sort_rank); dev_free(c->sort_tmp);
+    release(c->doc_blocks); release(c->ne_doc);
+    release(c->word_ids_d); release(c->word_row_d); release(c->sort_keys); release(c->sort_keys_out);
+    release(c->sort_rank); release(c->sort_tmp);
     if (c->h_tok_t) (void)hipHostFree(c->h_tok_t);
-    if (c->stream) (void)hipStreamDestroy(c->stream);
+    if (c->stream && c->own_stream) (void)hipStreamDestroy(c->stream);
     delete c;
 }
 
 // ------------------------------------------------------------------------------------------------
 // launch helpers
 // ------------------------------------------------------------------------------------------------
-// The assignments as the kernels index them, by canonical token number: the resident array, or for a chunk held
-// in a buffer the address at which token t0 of the chunk is the buffer's first element.
-static void *z_view(const saber_ctx *c, const Chunk &ch, int slot) {
-    if (slot < 0) return c->z;
-    const uintptr_t zs = c->z16 ? 2 : 4;
-    return reinterpret_cast<void *>(reinterpret_cast<uintptr_t>(c->slot_z[slot]) - (uintptr_t)ch.t0 * zs);
+// The assignments of a chunk in canonical order: the resident array, which holds all tokens (`first` = 0: its first
+// element is token 0), or the streaming buffer that holds the chunk (`first` = the chunk's first token).
+struct ZView { void *z; int64_t first; };
+static ZView z_view(const saber_ctx *c, const Chunk &ch, int slot) {
+    return slot < 0 ? ZView{c->z, 0} : ZView{c->slot_z[slot], ch.t0};
 }
 
 static EStepParams make_params(saber_ctx *c, const Chunk &ch, int slot = -1) {
@@ -208,7 +260,8 @@ static EStepParams make_params(saber_ctx *c, const Chunk &ch, int slot = -1) {
     else { p.tok_doc = c->slot_tok_doc[slot]; p.tok_t = c->slot_tok_t[slot]; }
     p.docrec = c->docrec; p.cd_ent = c->cd_ent;
     p.phi = c->phi; p.l3 = c->l3; p.l3_64 = c->l3_64; p.sumphi = c->sumphi;
-    p.z = z_view(c, ch, slot);
+    const ZView zv = z_view(c, ch, slot);
+    p.z = zv.z; p.z_rel = ch.t0 - zv.first;
     p.base = c->phi + (size_t)c->V_dense * (size_t)c->Kpad;
     p.wrec = c->wrec; p.lw_ent = c->lw_ent; p.lw_phi = c->lw_phi; p.z_wm = c->z_wm;
     p.t_base = ch.t0; p.K = c->K; p.Kpad = c->Kpad; p.n3 = c->n3; p.n3pad = c->n3pad;
@@ -303,7 +356,8 @@ static int launch_estep(saber_ctx *c, const Chunk &ch, EStepParams &p0) {
 // over z_wm (CountByVZ -> sparse rows of B).  Two launches: short segments with one wavefront each, long ones
 // with 256 threads.
 static int launch_segmented_count(saber_ctx *c, const int32_t *short_list, int64_t n_short, const int32_t *long_list,
-                                  int64_t n_long, const int64_t *seg_ptr, const void *z, uint2 *rec, uint32_t *ent) {
+                                  int64_t n_long, const int64_t *seg_ptr, const void *z, int64_t z_first, uint2 *rec,
+                                  uint32_t *ent) {
     for (int pass = 0; pass < 2; pass++) {
         const int64_t n = pass == 0 ? n_short : n_long;
         const int32_t *list = pass == 0 ? short_list : long_list;
@@ -322,10 +376,10 @@ static int launch_segmented_count(saber_ctx *c, const int32_t *short_list, int64
         const dim3 grid((unsigned)n), blk((unsigned)block);
         if (c->z16)
             hipLaunchKernelGGL((count_dz_kernel<uint16_t>), grid, blk, lds, c->stream, list, seg_ptr,
-                               (const uint16_t *)z, rec, ent, c->K, c->topic_bits, c->nwords, entries);
+                               (const uint16_t *)z, z_first, rec, ent, c->K, c->topic_bits, c->nwords, entries);
         else
             hipLaunchKernelGGL((count_dz_kernel<int32_t>), grid, blk, lds, c->stream, list, seg_ptr,
-                               (const int32_t *)z, rec, ent, c->K, c->topic_bits, c->nwords, entries);
+                               (const int32_t *)z, z_first, rec, ent, c->K, c->topic_bits, c->nwords, entries);
         HIP_TRY(hipGetLastError());
     }
     return SABER_OK;
@@ -356,14 +410,15 @@ static int launch_sort_rebuild(saber_ctx *c) {
 
 static int launch_count_dz(saber_ctx *c) {
     if (c->opt.ablation & 2) return launch_sort_rebuild(c);
-    return launch_segmented_count(c, c->short_docs, c->n_short, c->long_docs, c->n_long, c->doc_ptr, c->z, c->docrec,
+    return launch_segmented_count(c, c->short_docs, c->n_short, c->long_docs, c->n_long, c->doc_ptr, c->z, 0, c->docrec,
                                   c->cd_ent);
 }
 
 // CountByDZ for the documents of one chunk whose assignments sit in a buffer
 static int launch_count_dz_chunk(saber_ctx *c, const Chunk &ch, int slot) {
+    const ZView zv = z_view(c, ch, slot);
     return launch_segmented_count(c, c->short_docs + ch.short0, ch.nshort, c->long_docs + ch.long0, ch.nlong, c->doc_ptr,
-                                  z_view(c, ch, slot), c->docrec, c->cd_ent);
+                                  zv.z, zv.first, c->docrec, c->cd_ent);
 }
 
 // ---- host streaming ----
@@ -404,7 +459,7 @@ static int sync_all(saber_ctx *c) {
 static int launch_light_words(saber_ctx *c) {
     if (c->V_light == 0) return SABER_OK;
     SABER_TRY(launch_segmented_count(c, c->light_short, c->n_light_short, c->light_long, c->n_light_long,
-                                     c->light_tok_ptr, c->z_wm, c->wrec, c->lw_ent));
+                                     c->light_tok_ptr, c->z_wm, 0, c->wrec, c->lw_ent));
     const size_t lds = (size_t)c->n3 * (sizeof(double) + sizeof(int));
     hipLaunchKernelGGL(light_tree_kernel, dim3((unsigned)c->V_light), dim3(64), lds, c->stream, c->light_words, c->wrec,
                        c->lw_ent, c->lw_phi, c->denom, c->phi + (size_t)c->V_dense * (size_t)c->Kpad,
@@ -463,13 +518,13 @@ static int launch_phi(saber_ctx *c) {
 static int launch_fill_zwm_chunk(saber_ctx *c, const Chunk &ch, int slot) {
     if (ch.ntiles == 0) return SABER_OK;
     const uint32_t *tok_t = slot < 0 ? c->tok_t + ch.t0 : c->slot_tok_t[slot];
-    const void *z = z_view(c, ch, slot);
+    const ZView zv = z_view(c, ch, slot);
     if (c->z16)
         hipLaunchKernelGGL((fill_zwm_kernel<uint16_t>), dim3((unsigned)ch.ntiles), dim3(256), 0, c->stream,
-                           c->tiles + ch.tile0, tok_t, (const uint16_t *)z, ch.t0, (uint16_t *)c->z_wm);
+                           c->tiles + ch.tile0, tok_t, (const uint16_t *)zv.z, ch.t0 - zv.first, (uint16_t *)c->z_wm);
     else
         hipLaunchKernelGGL((fill_zwm_kernel<int32_t>), dim3((unsigned)ch.ntiles), dim3(256), 0, c->stream,
-                           c->tiles + ch.tile0, tok_t, (const int32_t *)z, ch.t0, (int32_t *)c->z_wm);
+                           c->tiles + ch.tile0, tok_t, (const int32_t *)zv.z, ch.t0 - zv.first, (int32_t *)c->z_wm);
     HIP_TRY(hipGetLastError());
     return SABER_OK;
 }
@@ -513,15 +568,15 @@ static int launch_count_vz(saber_ctx *c) {
     return SABER_OK;
 }
 
-// iteration 0: the Philox draw of Alg. 1's initialisation for the canonical tokens [t0, t1); z is indexed by token
-static int launch_init_z(saber_ctx *c, void *z, int64_t t0, int64_t t1) {
+// iteration 0: the Philox draw of Alg. 1's initialisation for the canonical tokens [t0, t1), stored from z[z_rel] on
+static int launch_init_z(saber_ctx *c, void *z, int64_t z_rel, int64_t t0, int64_t t1) {
     if (t1 <= t0) return SABER_OK;
     if (c->z16)
         hipLaunchKernelGGL((init_z_kernel<uint16_t>), dim3(grid_for(t1 - t0, 256, 8192)), dim3(256), 0, c->stream,
-                           (uint16_t *)z, t0, t1, (uint32_t)c->K, (uint32_t)c->seed, (uint32_t)(c->seed >> 32));
+                           (uint16_t *)z, z_rel, t0, t1, (uint32_t)c->K, (uint32_t)c->seed, (uint32_t)(c->seed >> 32));
     else
         hipLaunchKernelGGL((init_z_kernel<int32_t>), dim3(grid_for(t1 - t0, 256, 8192)), dim3(256), 0, c->stream,
-                           (int32_t *)z, t0, t1, (uint32_t)c->K, (uint32_t)c->seed, (uint32_t)(c->seed >> 32));
+                           (int32_t *)z, z_rel, t0, t1, (uint32_t)c->K, (uint32_t)c->seed, (uint32_t)(c->seed >> 32));
     HIP_TRY(hipGetLastError());
     return SABER_OK;
 }
@@ -545,7 +600,7 @@ static int full_mstep(saber_ctx *c, const int32_t *user_z = nullptr) {
                 }
                 HIP_TRY(hipMemcpy(c->slot_z[s], src, (size_t)ch.ntok * (c->z16 ? 2 : 4), hipMemcpyHostToDevice));
             } else {
-                SABER_TRY(launch_init_z(c, z_view(c, ch, s), ch.t0, ch.t0 + ch.ntok));
+                SABER_TRY(launch_init_z(c, c->slot_z[s], 0, ch.t0, ch.t0 + ch.ntok));
             }
             SABER_TRY(launch_count_dz_chunk(c, ch, s));
             SABER_TRY(launch_fill_zwm_chunk(c, ch, s));
@@ -585,7 +640,8 @@ static int refresh_workload_stats(saber_ctx *c) {
 // ------------------------------------------------------------------------------------------------
 static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) {
     const int64_t D = c->D, T = c->T; const int32_t V = c->V, K = c->K;
-    HIP_TRY(hipStreamCreate(&c->stream));
+    if (c->hooks.have_stream) { c->stream = c->hooks.stream; c->own_stream = false; }
+    else { HIP_TRY(hipStreamCreate(&c->stream)); c->own_stream = true; }
     if (c->opt.profile) {
         for (auto &e : c->ev) HIP_TRY(hipEventCreate(&e));
         c->have_events = true;
@@ -759,7 +815,7 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
         }
     }
     c->doc_len.resize((size_t)D);
-    int64_t units = 0; double llc = 0.0;
+    int64_t units = 0;
     for (int64_t d = 0; d < D; d++) {
         const int64_t len = doc_ptr[d + 1] - doc_ptr[d];
         c->doc_len[(size_t)d] = len;
@@ -767,9 +823,8 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
         h_rec[(size_t)d] = make_uint2((uint32_t)units, 0u);
         units += (std::min<int64_t>(len, K) + 31) / 32;
         (len > c->opt.long_doc_tokens ? h_long : h_short).push_back((int32_t)d);
-        if (len > 0) llc += (double)len * std::log((double)len + (double)K * (double)c->alpha);
     }
-    c->ll_const = llc; c->cd_cap = units * 32;
+    c->cd_cap = units * 32;
     c->n_short = (int64_t)h_short.size(); c->n_long = (int64_t)h_long.size();
     for (Chunk &ch : c->chunks) {   // both lists ascend by document: a chunk's documents are a contiguous part of each
         ch.short0 = std::lower_bound(h_short.begin(), h_short.end(), (int32_t)ch.d0) - h_short.begin();
@@ -784,9 +839,9 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     if (c->n_slots) {
         HIP_TRY(hipStreamCreateWithFlags(&c->s_in, hipStreamNonBlocking));
         for (int s = 0; s < c->n_slots; s++) {
-            SABER_TRY(dev_alloc(&c->slot_tok_doc[s], (size_t)c->slot_tokens)); SABER_TRY(dev_alloc(&c->slot_tok_t[s], (size_t)c->slot_tokens));
-            if (c->z16) SABER_TRY(dev_alloc((uint16_t **)&c->slot_z[s], (size_t)c->slot_tokens));
-            else SABER_TRY(dev_alloc((int32_t **)&c->slot_z[s], (size_t)c->slot_tokens));
+            SABER_TRY(dev_alloc(c->hooks, &c->slot_tok_doc[s], (size_t)c->slot_tokens)); SABER_TRY(dev_alloc(c->hooks, &c->slot_tok_t[s], (size_t)c->slot_tokens));
+            if (c->z16) SABER_TRY(dev_alloc(c->hooks, (uint16_t **)&c->slot_z[s], (size_t)c->slot_tokens));
+            else SABER_TRY(dev_alloc(c->hooks, (int32_t **)&c->slot_z[s], (size_t)c->slot_tokens));
             HIP_TRY(hipEventCreateWithFlags(&c->ev_loaded[s], hipEventDisableTiming));
             HIP_TRY(hipEventCreateWithFlags(&c->ev_done[s], hipEventDisableTiming));
         }
@@ -801,34 +856,34 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
             if (j) { uint4 &q = blocks[(size_t)(t >> 6)]; if (j < 32) q.y |= 1u << j; else q.z |= 1u << (j - 32); }
             for (int64_t b = (t + 63) >> 6; b <= (end - 1) >> 6; b++) blocks[(size_t)b].x = r;   // blocks that begin inside d
         }
-        SABER_TRY(dev_alloc(&c->doc_blocks, blocks.size()));
+        SABER_TRY(dev_alloc(c->hooks, &c->doc_blocks, blocks.size()));
         HIP_TRY(hipMemcpy(c->doc_blocks, blocks.data(), sizeof(uint4) * blocks.size(), hipMemcpyHostToDevice));
         if ((int64_t)ne.size() != D) {   // some document is empty: ordinals are not document numbers
-            SABER_TRY(dev_alloc(&c->ne_doc, ne.size()));
+            SABER_TRY(dev_alloc(c->hooks, &c->ne_doc, ne.size()));
             if (!ne.empty()) HIP_TRY(hipMemcpy(c->ne_doc, ne.data(), sizeof(int32_t) * ne.size(), hipMemcpyHostToDevice));
         }
     } else {
-        if (c->z16) SABER_TRY(dev_alloc((uint16_t **)&c->z, (size_t)T)); else SABER_TRY(dev_alloc((int32_t **)&c->z, (size_t)T));
-        SABER_TRY(dev_alloc(&c->tok_doc, (size_t)T)); SABER_TRY(dev_alloc(&c->tok_t, (size_t)T));
+        if (c->z16) SABER_TRY(dev_alloc(c->hooks, (uint16_t **)&c->z, (size_t)T)); else SABER_TRY(dev_alloc(c->hooks, (int32_t **)&c->z, (size_t)T));
+        SABER_TRY(dev_alloc(c->hooks, &c->tok_doc, (size_t)T)); SABER_TRY(dev_alloc(c->hooks, &c->tok_t, (size_t)T));
     }
-    SABER_TRY(dev_alloc(&c->tiles, h_tiles.size())); SABER_TRY(dev_alloc(&c->docrec, (size_t)D));
-    SABER_TRY(dev_alloc(&c->cd_ent, (size_t)c->cd_cap)); SABER_TRY(dev_alloc(&c->doc_ptr, (size_t)D + 1));
-    SABER_TRY(dev_alloc(&c->short_docs, h_short.size())); SABER_TRY(dev_alloc(&c->long_docs, h_long.size()));
+    SABER_TRY(dev_alloc(c->hooks, &c->tiles, h_tiles.size())); SABER_TRY(dev_alloc(c->hooks, &c->docrec, (size_t)D));
+    SABER_TRY(dev_alloc(c->hooks, &c->cd_ent, (size_t)c->cd_cap)); SABER_TRY(dev_alloc(c->hooks, &c->doc_ptr, (size_t)D + 1));
+    SABER_TRY(dev_alloc(c->hooks, &c->short_docs, h_short.size())); SABER_TRY(dev_alloc(c->hooks, &c->long_docs, h_long.size()));
     if (par) {
         // borrowed from the model: everything the sampler reads about words
         c->phi = par->phi; c->l3 = par->l3; c->l3_64 = par->l3_64; c->sumphi = par->sumphi;
         c->wrec = par->wrec; c->lw_ent = par->lw_ent; c->lw_phi = par->lw_phi;
     } else {
-    SABER_TRY(dev_alloc(&c->cwk, vk)); SABER_TRY(dev_alloc(&c->ck, (size_t)K)); SABER_TRY(dev_alloc(&c->denom, (size_t)K));
-    SABER_TRY(dev_alloc(&c->phi, vk)); SABER_TRY(dev_alloc(&c->l3_64, ((size_t)V + 1) * (size_t)c->n3));
-    SABER_TRY(dev_alloc(&c->row_word, h_row_word.size())); SABER_TRY(dev_alloc(&c->light_words, h_light_words.size()));
-    SABER_TRY(dev_alloc(&c->light_short, h_light_short.size())); SABER_TRY(dev_alloc(&c->light_long, h_light_long.size()));
-    SABER_TRY(dev_alloc(&c->light_tok_ptr, h_light_tok_ptr.size())); SABER_TRY(dev_alloc(&c->wrec, h_wrec.size()));
-    SABER_TRY(dev_alloc(&c->lw_ent, (size_t)c->lw_cap)); SABER_TRY(dev_alloc(&c->lw_phi, (size_t)c->lw_cap));
+    SABER_TRY(dev_alloc(c->hooks, &c->cwk, vk)); SABER_TRY(dev_alloc(c->hooks, &c->ck, (size_t)K)); SABER_TRY(dev_alloc(c->hooks, &c->denom, (size_t)K));
+    SABER_TRY(dev_alloc(c->hooks, &c->phi, vk)); SABER_TRY(dev_alloc(c->hooks, &c->l3_64, ((size_t)V + 1) * (size_t)c->n3));
+    SABER_TRY(dev_alloc(c->hooks, &c->row_word, h_row_word.size())); SABER_TRY(dev_alloc(c->hooks, &c->light_words, h_light_words.size()));
+    SABER_TRY(dev_alloc(c->hooks, &c->light_short, h_light_short.size())); SABER_TRY(dev_alloc(c->hooks, &c->light_long, h_light_long.size()));
+    SABER_TRY(dev_alloc(c->hooks, &c->light_tok_ptr, h_light_tok_ptr.size())); SABER_TRY(dev_alloc(c->hooks, &c->wrec, h_wrec.size()));
+    SABER_TRY(dev_alloc(c->hooks, &c->lw_ent, (size_t)c->lw_cap)); SABER_TRY(dev_alloc(c->hooks, &c->lw_phi, (size_t)c->lw_cap));
     }
-    if (c->z16) SABER_TRY(dev_alloc((uint16_t **)&c->z_wm, (size_t)T)); else SABER_TRY(dev_alloc((int32_t **)&c->z_wm, (size_t)T));
+    if (c->z16) SABER_TRY(dev_alloc(c->hooks, (uint16_t **)&c->z_wm, (size_t)T)); else SABER_TRY(dev_alloc(c->hooks, (int32_t **)&c->z_wm, (size_t)T));
     if (!par) {
-    SABER_TRY(dev_alloc(&c->vz_items, h_vz_items.size()));
+    SABER_TRY(dev_alloc(c->hooks, &c->vz_items, h_vz_items.size()));
     if (!h_vz_items.empty())
         HIP_TRY(hipMemcpy(c->vz_items, h_vz_items.data(), sizeof(VzItem) * h_vz_items.size(), hipMemcpyHostToDevice));
     HIP_TRY(hipMemcpy(c->row_word, h_row_word.data(), sizeof(int32_t) * h_row_word.size(), hipMemcpyHostToDevice));
@@ -840,27 +895,27 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
         if (!h_light_short.empty()) HIP_TRY(hipMemcpy(c->light_short, h_light_short.data(), sizeof(int32_t) * h_light_short.size(), hipMemcpyHostToDevice));
         if (!h_light_long.empty()) HIP_TRY(hipMemcpy(c->light_long, h_light_long.data(), sizeof(int32_t) * h_light_long.size(), hipMemcpyHostToDevice));
     }
-    SABER_TRY(dev_alloc(&c->doc_words, (size_t)D));
+    SABER_TRY(dev_alloc(c->hooks, &c->doc_words, (size_t)D));
     if (c->opt.ablation & 1) {
-        SABER_TRY(dev_alloc(&c->word_ids_d, (size_t)T)); SABER_TRY(dev_alloc(&c->word_row_d, (size_t)V));
+        SABER_TRY(dev_alloc(c->hooks, &c->word_ids_d, (size_t)T)); SABER_TRY(dev_alloc(c->hooks, &c->word_row_d, (size_t)V));
         if (T) HIP_TRY(hipMemcpy(c->word_ids_d, word_ids, sizeof(int32_t) * (size_t)T, hipMemcpyHostToDevice));
         HIP_TRY(hipMemcpy(c->word_row_d, c->h_word_row.data(), sizeof(int32_t) * (size_t)V, hipMemcpyHostToDevice));
     }
     if (c->opt.ablation & 2) {
         unsigned dbits = 1; while (dbits < 32 && (1ll << dbits) < std::max<int64_t>(D, 1)) dbits++;
         c->sort_end_bit = c->topic_bits + dbits;
-        SABER_TRY(dev_alloc(&c->sort_keys, (size_t)T)); SABER_TRY(dev_alloc(&c->sort_keys_out, (size_t)T));
-        SABER_TRY(dev_alloc(&c->sort_rank, (size_t)T));
+        SABER_TRY(dev_alloc(c->hooks, &c->sort_keys, (size_t)T)); SABER_TRY(dev_alloc(c->hooks, &c->sort_keys_out, (size_t)T));
+        SABER_TRY(dev_alloc(c->hooks, &c->sort_rank, (size_t)T));
         size_t bytes = 0;
         HIP_TRY(rocprim::radix_sort_keys(nullptr, bytes, c->sort_keys, c->sort_keys_out, (size_t)std::max<int64_t>(T, 1), 0u,
                                          c->sort_end_bit, c->stream));
         c->sort_tmp_bytes = std::max<size_t>(bytes, 1);
-        HIP_TRY(hipMalloc(&c->sort_tmp, c->sort_tmp_bytes));
+        SABER_TRY(hook_alloc(c->hooks, &c->sort_tmp, c->sort_tmp_bytes));
     }
-    if (!par) { SABER_TRY(dev_alloc(&c->l3, ((size_t)V + 1) * (size_t)c->n3pad)); SABER_TRY(dev_alloc(&c->sumphi, (size_t)V + 1)); }
-    SABER_TRY(dev_alloc(&c->counters, (size_t)kMaxTimedIters * kCtr));
-    SABER_TRY(dev_alloc(&c->dense_slots, (size_t)kMaxTimedIters * kDenseSlots));
-    SABER_TRY(dev_alloc(&c->ll_partial, (size_t)std::max<int64_t>(c->max_chunk_tiles, 1)));
+    if (!par) { SABER_TRY(dev_alloc(c->hooks, &c->l3, ((size_t)V + 1) * (size_t)c->n3pad)); SABER_TRY(dev_alloc(c->hooks, &c->sumphi, (size_t)V + 1)); }
+    SABER_TRY(dev_alloc(c->hooks, &c->counters, (size_t)kMaxTimedIters * kCtr));
+    SABER_TRY(dev_alloc(c->hooks, &c->dense_slots, (size_t)kMaxTimedIters * kDenseSlots));
+    SABER_TRY(dev_alloc(c->hooks, &c->ll_partial, (size_t)std::max<int64_t>(c->max_chunk_tiles, 1) + kLlTail));
     if (T && !c->n_slots) {
         HIP_TRY(hipMemcpy(c->tok_doc, h_tok_doc, sizeof(int32_t) * (size_t)T, hipMemcpyHostToDevice));
         HIP_TRY(hipMemcpy(c->tok_t, h_tok_t, sizeof(uint32_t) * (size_t)T, hipMemcpyHostToDevice));
@@ -875,11 +930,11 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
         hipLaunchKernelGGL(fill_u32_kernel, dim3(grid_for((int64_t)vk, 256, 8192)), dim3(256), 0, c->stream, (uint32_t *)c->cwk, 0u, vk);
         HIP_TRY(hipGetLastError());
     }
-    c->stats.tokens = T; c->stats.tiles = c->total_tiles;
+    c->stats.tokens = T; c->stats.tiles = c->total_tiles; c->stats.chunks = (int64_t)c->chunks.size();
     if (c->no_state) { HIP_TRY(hipStreamSynchronize(c->stream)); return SABER_OK; }
 
     // ---- iteration 0: Philox assignment, then the M-step ----
-    if (!c->n_slots) SABER_TRY(launch_init_z(c, c->z, 0, T));   // with host streaming: chunk by chunk, in full_mstep
+    if (!c->n_slots) SABER_TRY(launch_init_z(c, c->z, 0, 0, T));   // with host streaming: chunk by chunk, in full_mstep
     SABER_TRY(full_mstep(c));
     if (par) return SABER_OK;
     SABER_TRY(refresh_workload_stats(c));
@@ -964,6 +1019,8 @@ static int create_ctx(saber_ctx **out, const int64_t *doc_ptr, const int32_t *wo
 
     saber_ctx *c = new (std::nothrow) saber_ctx();
     if (!c) return fail(SABER_ENOMEM, "saber_init: out of host memory");
+    c->hooks = parent ? parent->hooks : g_hooks;
+    if (hipGetDevice(&c->device) != hipSuccess) { delete c; return fail(SABER_EDEVICE, "saber_init: hipGetDevice failed"); }
     c->D = D; c->T = T; c->V = V; c->K = K; c->alpha = alpha; c->beta = beta; c->seed = seed; c->opt = opt;
     c->parent = parent; c->no_state = no_state;
     c->n_slots = std::max(0, opt.stream_workers);
@@ -1103,10 +1160,12 @@ extern "C" int saber_iterate(saber_ctx *c, int32_t n) {
 // ------------------------------------------------------------------------------------------------
 extern "C" int saber_counts_nnz(saber_ctx *c, int64_t *nnz) {
     if (!c || !nnz) return fail(SABER_EINVAL, "saber_counts_nnz: null argument");
-    std::vector<uint2> rec((size_t)c->D);
-    if (c->D) HIP_TRY(hipMemcpy(rec.data(), c->docrec, sizeof(uint2) * (size_t)c->D, hipMemcpyDeviceToHost));
-    int64_t s = 0; for (auto &r : rec) s += r.y;
-    *nnz = s;
+    try {
+        std::vector<uint2> rec((size_t)c->D);
+        if (c->D) HIP_TRY(hipMemcpy(rec.data(), c->docrec, sizeof(uint2) * (size_t)c->D, hipMemcpyDeviceToHost));
+        int64_t s = 0; for (auto &r : rec) s += r.y;
+        *nnz = s;
+    } catch (const std::bad_alloc &) { return fail(SABER_ENOMEM, "saber_counts_nnz: out of host memory"); }
     return SABER_OK;
 }
 
@@ -1187,27 +1246,45 @@ extern "C" int saber_counts(saber_ctx *c, int64_t *cd_row_ptr, int32_t *cd_topic
     return SABER_OK;
 }
 
+// *result (device memory) = [ sum over the tokens of c of ln(S_t + Q_w)  -  sum_d w_d ln(len_d + K alpha) ] / T on the device, all
+// sums in binary64 and in a fixed order.  `theta` holds the rows of A that S is formed with (c itself for the training
+// log-likelihood; the observed part of the documents for the holdout score, whose document lengths then also give
+// len_d while w_d counts the scored tokens).  Everything is queued on c's stream; nothing is waited for.
+static int launch_loglik(saber_ctx *c, const saber_ctx *theta, const LlScratch &ws, double *result) {
+    bool first = true;
+    for (const Chunk &ch : c->chunks) {
+        if (ch.ntiles == 0) continue;
+        int s = -1;
+        if (c->n_slots) SABER_TRY(stream_acquire(c, ch, &s));
+        EStepParams p = make_params(c, ch, s);
+        p.docrec = theta->docrec; p.cd_ent = theta->cd_ent;
+        p.out_ll = ws.tile_part;
+        SABER_TRY(launch_estep<MODE_LOGLIK>(c, ch, p));
+        if (c->n_slots) SABER_TRY(stream_release(c, s));
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3(kReduceBlocks), dim3(kReduceThreads), 0, c->stream, ws.tile_part,
+                           ch.ntiles, ws.block_part);
+        HIP_TRY(hipGetLastError());
+        hipLaunchKernelGGL(reduce_final_kernel, dim3(1), dim3(kReduceThreads), 0, c->stream, ws.block_part, ws.acc, first ? 0 : 1);
+        HIP_TRY(hipGetLastError());
+        first = false;
+    }
+    hipLaunchKernelGGL(doc_norm_kernel, dim3(kReduceBlocks), dim3(kReduceThreads), 0, c->stream, c->doc_ptr, theta->doc_ptr,
+                       c->D, (double)c->K * (double)c->alpha, ws.block_part);
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(reduce_final_kernel, dim3(1), dim3(kReduceThreads), 0, c->stream, ws.block_part, ws.norm, 0);
+    HIP_TRY(hipGetLastError());
+    hipLaunchKernelGGL(loglik_finish_kernel, dim3(1), dim3(64), 0, c->stream, ws.acc, ws.norm, (double)c->T, result);
+    HIP_TRY(hipGetLastError());
+    return SABER_OK;
+}
+
 extern "C" int saber_loglik(saber_ctx *c, double *out) {
     if (!c || !out) return fail(SABER_EINVAL, "saber_loglik: null argument");
     if (c->T == 0) { *out = 0.0; return SABER_OK; }
-    double total = 0.0;
-    try {
-        std::vector<double> part;
-        for (const Chunk &ch : c->chunks) {
-            if (ch.ntiles == 0) continue;
-            int s = -1;
-            if (c->n_slots) SABER_TRY(stream_acquire(c, ch, &s));
-            EStepParams p = make_params(c, ch, s);
-            p.out_ll = c->ll_partial;
-            SABER_TRY(launch_estep<MODE_LOGLIK>(c, ch, p));
-            if (c->n_slots) SABER_TRY(stream_release(c, s));
-            HIP_TRY(hipStreamSynchronize(c->stream));
-            part.resize((size_t)ch.ntiles);
-            HIP_TRY(hipMemcpy(part.data(), c->ll_partial, sizeof(double) * (size_t)ch.ntiles, hipMemcpyDeviceToHost));
-            for (double v : part) total += v;   // fixed order: the result is reproducible
-        }
-    } catch (const std::bad_alloc &) { return fail(SABER_ENOMEM, "saber_loglik: out of host memory"); }
-    *out = (total - c->ll_const) / (double)c->T;
+    const LlScratch ws = ll_scratch(c->ll_partial, (size_t)std::max<int64_t>(c->max_chunk_tiles, 1));
+    SABER_TRY(launch_loglik(c, c, ws, ws.result));
+    SABER_TRY(sync_all(c));
+    HIP_TRY(hipMemcpy(out, ws.result, sizeof(double), hipMemcpyDeviceToHost));
     return SABER_OK;
 }
 
@@ -1261,30 +1338,20 @@ extern "C" int saber_holdout_loglik(saber_ctx *m, const int64_t *doc_ptr, const 
         if (rc == SABER_OK) rc = foldin_iterate(obs, n_foldin);
         if (rc == SABER_OK && z_out) rc = saber_get_z(obs, z_out);
         if (rc == SABER_OK) rc = create_ctx(&scr, sptr.data(), sw.data(), D, m->V, m->K, m->alpha, m->beta, seed, &opt, m, true);
-        double total = 0.0;
+        double ll = 0.0;
         if (rc == SABER_OK && scr->T > 0) {
-            std::vector<double> part;
-            for (const Chunk &ch : scr->chunks) {
-                if (ch.ntiles == 0) continue;
-                EStepParams p = make_params(scr, ch);
-                p.docrec = obs->docrec; p.cd_ent = obs->cd_ent;   // theta comes from the observed part
-                p.out_ll = scr->ll_partial;
-                if ((rc = launch_estep<MODE_LOGLIK>(scr, ch, p)) != SABER_OK) break;
+            // theta comes from the observed part: its rows of A, and its document lengths in the normaliser
+            const LlScratch ws = ll_scratch(scr->ll_partial, (size_t)std::max<int64_t>(scr->max_chunk_tiles, 1));
+            rc = launch_loglik(scr, obs, ws, ws.result);
+            if (rc == SABER_OK) {
                 hipError_t e = hipStreamSynchronize(scr->stream);
-                part.resize((size_t)ch.ntiles);
-                if (e == hipSuccess) e = hipMemcpy(part.data(), scr->ll_partial, sizeof(double) * (size_t)ch.ntiles, hipMemcpyDeviceToHost);
-                if (e != hipSuccess) { rc = fail(SABER_EDEVICE, "saber_holdout_loglik: %s", hipGetErrorString(e)); break; }
-                for (double v : part) total += v;   // fixed order: the result is reproducible
-            }
-            // the normaliser ln(L'_d + K alpha) of theta, once per scored token
-            for (int64_t d = 0; d < D; d++) {
-                const int64_t ns = sptr[(size_t)d + 1] - sptr[(size_t)d];
-                if (ns) total -= (double)ns * std::log((double)(optr[(size_t)d + 1] - optr[(size_t)d]) + (double)m->K * (double)m->alpha);
+                if (e == hipSuccess) e = hipMemcpy(&ll, ws.result, sizeof(double), hipMemcpyDeviceToHost);
+                if (e != hipSuccess) rc = fail(SABER_EDEVICE, "saber_holdout_loglik: %s", hipGetErrorString(e));
             }
         }
         if (rc == SABER_OK) {
             *n_scored = scr->T;
-            *loglik = scr->T > 0 ? total / (double)scr->T : 0.0;
+            *loglik = ll;
         }
     } catch (const std::bad_alloc &) { rc = fail(SABER_ENOMEM, "saber_holdout_loglik: out of host memory"); }
     saber_free(scr); saber_free(obs);
@@ -1323,13 +1390,13 @@ extern "C" int saber_get_z(saber_ctx *c, int32_t *z) {
     }
     if (!c->z16) { HIP_TRY(hipMemcpy(z, c->z, sizeof(int32_t) * (size_t)c->T, hipMemcpyDeviceToHost)); return SABER_OK; }
     int32_t *tmp = nullptr;
-    SABER_TRY(dev_alloc(&tmp, (size_t)c->T));
+    SABER_TRY(dev_alloc(c->hooks, &tmp, (size_t)c->T));
     hipLaunchKernelGGL((z_to_i32_kernel<uint16_t>), dim3(grid_for(c->T, 256, 8192)), dim3(256), 0, c->stream,
                        (const uint16_t *)c->z, tmp, c->T);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
     if (e == hipSuccess) e = hipMemcpy(z, tmp, sizeof(int32_t) * (size_t)c->T, hipMemcpyDeviceToHost);
-    dev_free(tmp);
+    dev_free(c->hooks, tmp);
     if (e != hipSuccess) return fail(SABER_EDEVICE, "saber_get_z: %s", hipGetErrorString(e));
     return SABER_OK;
 }
@@ -1340,7 +1407,7 @@ extern "C" int saber_set_z(saber_ctx *c, const int32_t *z, uint32_t iter) {
         if (z[t] < 0 || z[t] >= c->K) return fail(SABER_EINVAL, "saber_set_z: topic %d at token %lld is outside [0,%d)", z[t], (long long)t, c->K);
     if (c->T && !c->n_slots) {
         int32_t *tmp = nullptr;
-        SABER_TRY(dev_alloc(&tmp, (size_t)c->T));
+        SABER_TRY(dev_alloc(c->hooks, &tmp, (size_t)c->T));
         hipError_t e = hipMemcpy(tmp, z, sizeof(int32_t) * (size_t)c->T, hipMemcpyHostToDevice);
         if (e == hipSuccess) {
             if (c->z16)
@@ -1350,7 +1417,7 @@ extern "C" int saber_set_z(saber_ctx *c, const int32_t *z, uint32_t iter) {
             e = hipGetLastError();
         }
         if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
-        dev_free(tmp);
+        dev_free(c->hooks, tmp);
         if (e != hipSuccess) return fail(SABER_EDEVICE, "saber_set_z: %s", hipGetErrorString(e));
     }
     c->iter = iter;
@@ -1371,36 +1438,35 @@ extern "C" int saber_token_probs(saber_ctx *c, const int64_t *tok, int64_t m, fl
     for (int64_t i = 0; i < m; i++)
         if (tok[i] < 0 || tok[i] >= c->T) return fail(SABER_EINVAL, "saber_token_probs: token index %lld is outside [0,%lld)", (long long)tok[i], (long long)c->T);
     if (m == 0) return SABER_OK;
-    float *dS = nullptr, *dQ = nullptr, *gS = nullptr, *gQ = nullptr; int64_t *dtok = nullptr;
+    // S and Q of every token of a chunk (inspection mode of the sampling kernel), then the requested tokens of that
+    // chunk are picked out and S / (S + Q) is formed, all on the device; the work space is sized for one chunk
+    int64_t max_tok = 1;
+    for (const Chunk &ch : c->chunks) max_tok = std::max(max_tok, ch.ntok);
+    float *dS = nullptr, *dQ = nullptr, *g3 = nullptr; int64_t *dtok = nullptr;
     int rc = SABER_OK;
-    auto cleanup = [&]() { dev_free(dS); dev_free(dQ); dev_free(gS); dev_free(gQ); dev_free(dtok); };
-    if ((rc = dev_alloc(&dS, (size_t)c->T)) || (rc = dev_alloc(&dQ, (size_t)c->T)) || (rc = dev_alloc(&gS, (size_t)m)) ||
-        (rc = dev_alloc(&gQ, (size_t)m)) || (rc = dev_alloc(&dtok, (size_t)m))) { cleanup(); return rc; }
+    auto cleanup = [&]() { dev_free(c->hooks, dS); dev_free(c->hooks, dQ); dev_free(c->hooks, g3); dev_free(c->hooks, dtok); };
+    if ((rc = dev_alloc(c->hooks, &dS, (size_t)max_tok)) || (rc = dev_alloc(c->hooks, &dQ, (size_t)max_tok)) ||
+        (rc = dev_alloc(c->hooks, &g3, 3 * (size_t)m)) || (rc = dev_alloc(c->hooks, &dtok, (size_t)m))) { cleanup(); return rc; }
+    hipError_t e = hipMemcpy(dtok, tok, sizeof(int64_t) * (size_t)m, hipMemcpyHostToDevice);
     for (const Chunk &ch : c->chunks) {
+        if (e != hipSuccess) break;
+        if (ch.ntiles == 0) continue;
         int s = -1;
         if (c->n_slots && (rc = stream_acquire(c, ch, &s))) { cleanup(); return rc; }
         EStepParams p = make_params(c, ch, s);
         p.out_S = dS; p.out_Q = dQ;
         if ((rc = launch_estep<MODE_PROBS>(c, ch, p))) { cleanup(); return rc; }
         if (c->n_slots && (rc = stream_release(c, s))) { cleanup(); return rc; }
-    }
-    std::vector<float> hS((size_t)m), hQ((size_t)m);
-    hipError_t e = hipMemcpyAsync(dtok, tok, sizeof(int64_t) * (size_t)m, hipMemcpyHostToDevice, c->stream);
-    if (e == hipSuccess) {
-        hipLaunchKernelGGL(gather_f32_kernel, dim3(grid_for(m, 256)), dim3(256), 0, c->stream, dS, dtok, m, gS);
-        hipLaunchKernelGGL(gather_f32_kernel, dim3(grid_for(m, 256)), dim3(256), 0, c->stream, dQ, dtok, m, gQ);
+        hipLaunchKernelGGL(gather_probs_kernel, dim3(grid_for(m, 256)), dim3(256), 0, c->stream, dS, dQ, dtok, m, ch.t0, ch.ntok,
+                           g3, g3 + m, g3 + 2 * m);
         e = hipGetLastError();
     }
     if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
-    if (e == hipSuccess) e = hipMemcpy(hS.data(), gS, sizeof(float) * (size_t)m, hipMemcpyDeviceToHost);
-    if (e == hipSuccess) e = hipMemcpy(hQ.data(), gQ, sizeof(float) * (size_t)m, hipMemcpyDeviceToHost);
+    if (e == hipSuccess && S) e = hipMemcpy(S, g3, sizeof(float) * (size_t)m, hipMemcpyDeviceToHost);
+    if (e == hipSuccess && Q) e = hipMemcpy(Q, g3 + m, sizeof(float) * (size_t)m, hipMemcpyDeviceToHost);
+    if (e == hipSuccess && p_sparse) e = hipMemcpy(p_sparse, g3 + 2 * m, sizeof(float) * (size_t)m, hipMemcpyDeviceToHost);
     cleanup();
     if (e != hipSuccess) return fail(SABER_EDEVICE, "saber_token_probs: %s", hipGetErrorString(e));
-    for (int64_t i = 0; i < m; i++) {
-        if (S) S[i] = hS[(size_t)i];
-        if (Q) Q[i] = hQ[(size_t)i];
-        if (p_sparse) p_sparse[i] = hS[(size_t)i] / (hS[(size_t)i] + hQ[(size_t)i]);
-    }
     return SABER_OK;
 }
 
@@ -1412,10 +1478,10 @@ extern "C" int saber_get_phi(saber_ctx *c, const int32_t *words, int32_t m, floa
     // assemble the requested Bhat rows on the device: dense rows are copied, light rows are the base vector
     // overwritten at the word's non-zeros; the prefix rows are then rebuilt the way the dense branch does
     float *drows = nullptr, *dout = nullptr; int32_t *dw = nullptr, *dlight = nullptr;
-    auto cleanup = [&]() { dev_free(drows); dev_free(dout); dev_free(dw); dev_free(dlight); };
+    auto cleanup = [&]() { dev_free(c->hooks, drows); dev_free(c->hooks, dout); dev_free(c->hooks, dw); dev_free(c->hooks, dlight); };
     int rc;
-    if ((rc = dev_alloc(&drows, (size_t)m * (size_t)c->K)) || (rc = dev_alloc(&dout, (size_t)m * (size_t)c->K)) ||
-        (rc = dev_alloc(&dw, (size_t)m)) || (rc = dev_alloc(&dlight, (size_t)m))) { cleanup(); return rc; }
+    if ((rc = dev_alloc(c->hooks, &drows, (size_t)m * (size_t)c->K)) || (rc = dev_alloc(c->hooks, &dout, (size_t)m * (size_t)c->K)) ||
+        (rc = dev_alloc(c->hooks, &dw, (size_t)m)) || (rc = dev_alloc(c->hooks, &dlight, (size_t)m))) { cleanup(); return rc; }
     hipError_t e = hipMemcpy(dw, words, sizeof(int32_t) * (size_t)m, hipMemcpyHostToDevice);
     for (int32_t i = 0; i < m && e == hipSuccess; i++) {
         const int32_t row = c->h_word_row[(size_t)words[i]];
@@ -1473,14 +1539,14 @@ extern "C" int saber_alias_build_probe(saber_ctx *c, const int32_t *words, int32
     float *d_prob = nullptr, *o_prob = nullptr;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     auto cleanup = [&]() {
-        dev_free(scaled); dev_free(stack); dev_free(d_alias); dev_free(d_rows); dev_free(o_alias); dev_free(d_prob); dev_free(o_prob);
+        dev_free(c->hooks, scaled); dev_free(c->hooks, stack); dev_free(c->hooks, d_alias); dev_free(c->hooks, d_rows); dev_free(c->hooks, o_alias); dev_free(c->hooks, d_prob); dev_free(c->hooks, o_prob);
         if (e0) (void)hipEventDestroy(e0);
         if (e1) (void)hipEventDestroy(e1);
     };
     int rc;
-    if ((rc = dev_alloc(&scaled, cells)) || (rc = dev_alloc(&stack, cells)) || (rc = dev_alloc(&d_alias, cells)) ||
-        (rc = dev_alloc(&d_prob, cells)) || (rc = dev_alloc(&d_rows, (size_t)std::max(m, 1))) ||
-        (rc = dev_alloc(&o_prob, (size_t)std::max(m, 1) * (size_t)K)) || (rc = dev_alloc(&o_alias, (size_t)std::max(m, 1) * (size_t)K))) {
+    if ((rc = dev_alloc(c->hooks, &scaled, cells)) || (rc = dev_alloc(c->hooks, &stack, cells)) || (rc = dev_alloc(c->hooks, &d_alias, cells)) ||
+        (rc = dev_alloc(c->hooks, &d_prob, cells)) || (rc = dev_alloc(c->hooks, &d_rows, (size_t)std::max(m, 1))) ||
+        (rc = dev_alloc(c->hooks, &o_prob, (size_t)std::max(m, 1) * (size_t)K)) || (rc = dev_alloc(c->hooks, &o_alias, (size_t)std::max(m, 1) * (size_t)K))) {
         cleanup(); return rc;
     }
     hipError_t e = hipEventCreate(&e0);
@@ -1537,8 +1603,8 @@ extern "C" int saber_bandwidth_probe(int64_t bytes, int32_t reps, double *gb_per
     uint4 *src = nullptr, *dst = nullptr;
     hipEvent_t e0 = nullptr, e1 = nullptr;
     int rc = SABER_OK;
-    auto cleanup = [&]() { dev_free(src); dev_free(dst); if (e0) (void)hipEventDestroy(e0); if (e1) (void)hipEventDestroy(e1); };
-    if ((rc = dev_alloc(&src, n16)) || (rc = dev_alloc(&dst, n16))) { cleanup(); return rc; }
+    auto cleanup = [&]() { dev_free(g_hooks, src); dev_free(g_hooks, dst); if (e0) (void)hipEventDestroy(e0); if (e1) (void)hipEventDestroy(e1); };
+    if ((rc = dev_alloc(g_hooks, &src, n16)) || (rc = dev_alloc(g_hooks, &dst, n16))) { cleanup(); return rc; }
     hipError_t e = hipEventCreate(&e0);
     if (e == hipSuccess) e = hipEventCreate(&e1);
     if (e == hipSuccess) {

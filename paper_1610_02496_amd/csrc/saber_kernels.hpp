@@ -45,8 +45,13 @@ __device__ __forceinline__ double wave_incl_scan(double v) { SABER_SCAN_BODY(dou
 #undef SABER_SCAN_BODY
 
 // binary32 scan used in the sampler's inner loop: the two row-broadcast steps as single fused DPP adds (rows
-// outside the row mask keep their value, which is exactly what the scan wants).  s_nop 1 covers the two wait
-// states a DPP read needs after the VALU write of its source.
+// outside the row mask keep their value, which is exactly what the scan wants; the compiler fuses a masked DPP
+// move into an integer add but not into a float add, hence the two lines of assembly).  s_nop 1 covers the two
+// wait states a DPP read needs after the VALU write of its source.  The compiler's hazard recogniser does not see
+// inside the assembly, so the one other hazard of a DPP instruction is the caller's to exclude: no VALU write of
+// EXEC (v_cmpx, v_readlane into EXEC) within five instructions before the call.  Every call site sits in
+// wave-uniform control flow, where EXEC is only ever written by scalar instructions (on gfx9 the compiler forms
+// no v_cmpx), which need no wait.
 __device__ __forceinline__ float wave_incl_scan_fast(float v) {
     v += dpp_f32<0x111, 0xf>(v);
     v += dpp_f32<0x112, 0xf>(v);
@@ -125,12 +130,13 @@ __global__ void fill_u32_kernel(uint32_t *p, uint32_t value, size_t n) {
     for (; i < n; i += stride) p[i] = value;
 }
 
+// z[z_rel + i] belongs to the canonical token t0 + i
 template <typename ZT>
-__global__ void init_z_kernel(ZT *z, int64_t t0, int64_t t1, uint32_t K, uint32_t seed_lo, uint32_t seed_hi) {
+__global__ void init_z_kernel(ZT *z, int64_t z_rel, int64_t t0, int64_t t1, uint32_t K, uint32_t seed_lo, uint32_t seed_hi) {
     int64_t t = t0 + (int64_t)blockIdx.x * blockDim.x + threadIdx.x, stride = (int64_t)gridDim.x * blockDim.x;
     for (; t < t1; t += stride) {
         Rand2 r = philox_token(seed_lo, seed_hi, (uint64_t)t, 0u);
-        z[t] = (ZT)__umulhi(r.r0, K);   // floor(word0 * K / 2^32)
+        z[z_rel + (t - t0)] = (ZT)__umulhi(r.r0, K);   // floor(word0 * K / 2^32)
     }
 }
 
@@ -145,9 +151,17 @@ __global__ void z_to_i32_kernel(const ZT *z, int32_t *dst, int64_t T) {
     for (; t < T; t += stride) dst[t] = (int32_t)z[t];
 }
 
-__global__ void gather_f32_kernel(const float *src, const int64_t *idx, int64_t m, float *dst) {
+// Normalisers of Alg. 2 for the requested tokens that lie in the chunk [t0, t0 + n): S and Q as the sampling
+// kernel's inspection mode left them (indexed by the token's position in the chunk) and the probability of the
+// sparse branch, S / (S + Q).
+__global__ void gather_probs_kernel(const float *S, const float *Q, const int64_t *idx, int64_t m, int64_t t0, int64_t n,
+                                    float *out_S, float *out_Q, float *out_p) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < m) dst[i] = src[idx[i]];
+    if (i >= m) return;
+    const int64_t r = idx[i] - t0;
+    if (r < 0 || r >= n) return;
+    const float s = S[r], q = Q[r];
+    out_S[i] = s; out_Q[i] = q; out_p[i] = s / (s + q);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -169,19 +183,21 @@ struct EStepParams {
                                 //            padded with the row total (tree level above the bottom)
     const double *l3_64;        // [V][n3]    the same running sums before rounding (base of each bottom block)
     const float *sumphi;        // [V]        prefix sum at topic K-1 = l3[n3-1]
-    void *z;                    // [T] assignments, canonical order (uint16 or int32)
+    void *z;                    // assignments in canonical order (uint16 or int32): the chunk's token t_base + i is
+                                // element z_rel + i (the resident array holds all tokens, a streaming buffer one chunk)
     // light words (few tokens): B is kept sparse, Bhat = base + the word's non-zeros
     const float *base;          // [Kpad] Bhat of a zero count, beta / denom_k (pad columns 0)
     const uint2 *wrec;          // [light words] {row start in units of 32 entries, non-zeros}
     const uint32_t *lw_ent;     // packed (topic, count) rows of B for the light words, ascending topic
     const float *lw_phi;        // Bhat value of every such entry
     void *z_wm;                 // [T] new assignments in word-major order (light words first): input of CountByVZ
-    float *out_S;               // probs mode: S per canonical token
-    float *out_Q;               // probs mode: Q per canonical token
+    float *out_S;               // probs mode: S per token of the chunk, indexed by the token's position in the chunk
+    float *out_Q;               // probs mode: Q likewise
     double *out_ll;             // loglik mode: one partial sum per tile
     unsigned long long *n_dense;// sample mode: kDenseSlots dense-branch token counters (workgroup b adds to slot b mod
                                 // kDenseSlots: one hot address would serialise the atomics of the whole launch)
     int64_t t_base;             // canonical index of the chunk's first token
+    int64_t z_rel;              // position of that token in z
     int32_t K, Kpad, n3, n3pad;
     uint32_t topic_bits, topic_mask;
     float alpha;
@@ -553,13 +569,12 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
         }
 
         if (act) {
-            const int64_t tc = p.t_base + (int64_t)t;
             if (MODE == MODE_SAMPLE) {
-                reinterpret_cast<ZT *>(p.z)[tc] = (ZT)my_z;
+                reinterpret_cast<ZT *>(p.z)[p.z_rel + (int64_t)t] = (ZT)my_z;
                 // the second copy, in word-major order, is what CountByVZ reads (coalesced here and there)
                 reinterpret_cast<ZT *>(p.z_wm)[tile.wm_begin + (int64_t)(i - tile.begin)] = (ZT)my_z;
             } else if (MODE == MODE_PROBS) {
-                p.out_S[tc] = my_S; p.out_Q[tc] = Q;
+                p.out_S[t] = my_S; p.out_Q[t] = Q;
             } else {
                 ll_acc += log((double)(my_S + Q));
             }
@@ -689,10 +704,10 @@ __global__ void expand_tok_doc_kernel(const uint32_t *__restrict__ tok_t, int64_
 
 // word-major copy of the assignments (after init / set_z; during iterations the E-step writes it)
 template <typename ZT>
-__global__ void fill_zwm_kernel(const Tile *tiles, const uint32_t *tok_t, const ZT *z, int64_t t_base, ZT *z_wm) {
+__global__ void fill_zwm_kernel(const Tile *tiles, const uint32_t *tok_t, const ZT *z, int64_t z_rel, ZT *z_wm) {
     const Tile tile = tiles[blockIdx.x];
     for (int i = threadIdx.x; i < tile.count; i += blockDim.x)
-        z_wm[tile.wm_begin + i] = z[t_base + (int64_t)tok_t[tile.begin + i]];
+        z_wm[tile.wm_begin + i] = z[z_rel + (int64_t)tok_t[tile.begin + i]];
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -723,9 +738,10 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *scratc
 // slot in the ascending row; counts are accumulated per slot with LDS atomics.
 // Rows whose K_d exceeds lds_entries are accumulated directly in the global row.
 // ---------------------------------------------------------------------------------------------
+// z[0] is the assignment at position z_first of the segment numbering (a streaming buffer holds one chunk only).
 template <typename ZT>
 __global__ void __launch_bounds__(1024) count_dz_kernel(const int32_t *doc_list, const int64_t *doc_ptr,
-                                                        const ZT *z, uint2 *docrec, uint32_t *cd_ent, int K,
+                                                        const ZT *z, int64_t z_first, uint2 *docrec, uint32_t *cd_ent, int K,
                                                         uint32_t topic_bits, int nwords, int lds_entries) {
     extern __shared__ uint32_t lds_u32[];
     __shared__ uint32_t scan_scratch[20];
@@ -736,7 +752,7 @@ __global__ void __launch_bounds__(1024) count_dz_kernel(const int32_t *doc_list,
     const int64_t begin = doc_ptr[d];
     const int len = (int)(doc_ptr[d + 1] - begin);
     if (len == 0) { if (threadIdx.x == 0) docrec[d].y = 0u; return; }
-    const ZT *__restrict__ zd = z + begin;
+    const ZT *__restrict__ zd = z + (begin - z_first);
 
     for (int w = threadIdx.x; w < nwords; w += blockDim.x) bitmap[w] = 0u;
     __syncthreads();
@@ -987,6 +1003,59 @@ __global__ void light_stats_kernel(const uint2 *wrec, int n, unsigned long long 
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) nnz += wrec[i].y;
     nnz = wave_sum(nnz);
     if (lane_id() == 0 && nnz) atomicAdd(out, (unsigned long long)nnz);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Log-likelihood reduction (the per-token log-likelihood is the quality metric of Sec. 4): binary64 sums in a
+// fixed order, so the result is the same in every run.  kReduceBlocks workgroups of kReduceThreads threads: thread
+// i of workgroup b adds the elements b * kReduceThreads + i, + kReduceBlocks * kReduceThreads, ...; lanes are
+// combined by a DPP scan, wavefronts and workgroups in index order.
+// ---------------------------------------------------------------------------------------------
+constexpr int kReduceBlocks = 256, kReduceThreads = 256;
+
+__device__ __forceinline__ double block_sum_f64(double v, double *wave_part) {
+    const double w = readlane_f64(wave_incl_scan(v), 63);
+    if (lane_id() == 0) wave_part[threadIdx.x / kWave] = w;
+    __syncthreads();
+    double sum = 0.0;
+    for (int i = 0; i < (int)(blockDim.x / kWave); i++) sum += wave_part[i];
+    __syncthreads();
+    return sum;
+}
+
+// block_part[b] = sum of workgroup b's share of in[0..n)
+__global__ void __launch_bounds__(kReduceThreads) reduce_partials_kernel(const double *in, int64_t n, double *block_part) {
+    __shared__ double wave_part[kReduceThreads / kWave];
+    double v = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * kReduceThreads + threadIdx.x; i < n; i += (int64_t)kReduceBlocks * kReduceThreads) v += in[i];
+    const double sum = block_sum_f64(v, wave_part);
+    if (threadIdx.x == 0) block_part[blockIdx.x] = sum;
+}
+
+// block_part[b] = workgroup b's share of sum_d w_d ln(len_d + K alpha), w_d = wptr[d+1] - wptr[d] and
+// len_d = lptr[d+1] - lptr[d]: the normaliser of theta_d, once per token that is scored in document d.
+__global__ void __launch_bounds__(kReduceThreads) doc_norm_kernel(const int64_t *wptr, const int64_t *lptr, int64_t D,
+                                                                   double k_alpha, double *block_part) {
+    __shared__ double wave_part[kReduceThreads / kWave];
+    double v = 0.0;
+    for (int64_t d = (int64_t)blockIdx.x * kReduceThreads + threadIdx.x; d < D; d += (int64_t)kReduceBlocks * kReduceThreads) {
+        const int64_t w = wptr[d + 1] - wptr[d];
+        if (w > 0) v += (double)w * log((double)(lptr[d + 1] - lptr[d]) + k_alpha);
+    }
+    const double sum = block_sum_f64(v, wave_part);
+    if (threadIdx.x == 0) block_part[blockIdx.x] = sum;
+}
+
+// *acc = (add ? *acc : 0) + sum of block_part[0..kReduceBlocks); one workgroup
+__global__ void __launch_bounds__(kReduceThreads) reduce_final_kernel(const double *block_part, double *acc, int add) {
+    __shared__ double wave_part[kReduceThreads / kWave];
+    const double sum = block_sum_f64(threadIdx.x < kReduceBlocks ? block_part[threadIdx.x] : 0.0, wave_part);
+    if (threadIdx.x == 0) *acc = (add ? *acc : 0.0) + sum;
+}
+
+// *out = (*sum_ln - *norm) / tokens: the per-token log-likelihood
+__global__ void loglik_finish_kernel(const double *sum_ln, const double *norm, double tokens, double *out) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) *out = (*sum_ln - *norm) / tokens;
 }
 
 // Plain streaming copy (16 bytes per lane per step): the yardstick for achievable HBM bandwidth and the

@@ -1,4 +1,5 @@
-"""The C-ABI library loads without a GPU and exports every symbol include/saber.h declares."""
+"""The C-ABI library loads without a GPU and exports every symbol the headers under include/ declare."""
+import glob
 import os
 import re
 
@@ -11,9 +12,11 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "saber.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(saber_[a-z0-9_]+)\s*\(", text)))
+    names = set()
+    for path in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))):
+        text = re.sub(r"/\*.*?\*/", "", open(path).read(), flags=re.S)
+        names.update(re.findall(r"\b(saber_[a-z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_symbol():

@@ -27,11 +27,14 @@ _CORPORA = {}
 
 def corpus_for(name):
     """C3: the benchmark corpus (100M tokens).  C4p: the first million documents of the PubMed-shaped
-    workload (short documents, 90M tokens, V=141K), fitted with its K=5,000."""
+    workload (short documents, 90M tokens, V=141K), fitted with its K=5,000.  C5p: the first 820,000 documents of
+    the ClueWeb12-subset-shaped workload (long, heavy-tailed documents, 300M tokens), fitted with its K=10,000:
+    the library cuts it into three document chunks by itself (Sec. 3.1.2), as it cuts the full workload into 53."""
     if name not in _CORPORA:
         _CORPORA.clear()                       # one large corpus in memory at a time
         t = time.time()
-        spec = corpusgen.SPECS["C3"] if name == "C3" else corpusgen.scaled(corpusgen.SPECS["C4"], 1_000_000)
+        spec = {"C3": corpusgen.SPECS["C3"], "C4p": corpusgen.scaled(corpusgen.SPECS["C4"], 1_000_000),
+                "C5p": corpusgen.scaled(corpusgen.SPECS["C5"], 820_000)}[name]
         c = corpusgen.generate(spec, with_topics=False)
         say("[fullsize] corpus %s T=%d generated in %.1fs" % (spec.name, c.T, time.time() - t))
         if name == "C3":
@@ -40,7 +43,7 @@ def corpus_for(name):
     return _CORPORA[name]
 
 
-@pytest.mark.parametrize("name,K", [("C3", 1000), ("C3", 10000), ("C4p", 5000)])
+@pytest.mark.parametrize("name,K", [("C4p", 5000), ("C5p", 10000), ("C3", 1000), ("C3", 10000)])
 def test_full_size_parity(name, K):
     import paper_1610_02496_amd as pk
     c = corpus_for(name)
@@ -48,7 +51,9 @@ def test_full_size_parity(name, K):
     alpha, beta, seed = 50.0 / K, s.beta, s.seed
     t = time.time()
     g = pk.Saber(c.doc_ptr, c.word_ids, s.V, K, alpha, beta, seed)       # default options = bench configuration
-    say("[fullsize] K=%d gpu init %.1fs" % (K, time.time() - t)); t = time.time()
+    say("[fullsize] %s K=%d gpu init %.1fs, %d chunks" % (name, K, time.time() - t, g.get_stats()["chunks"])); t = time.time()
+    if name == "C5p":
+        assert g.get_stats()["chunks"] >= 3 and g.get_stats()["stream_workers"] == 0   # the automatic, resident layout
     o = oracle.Model(c.doc_ptr, c.word_ids, s.V, K, alpha, beta, seed)
     say("[fullsize] K=%d oracle init + M-step %.1fs" % (K, time.time() - t)); t = time.time()
 
@@ -111,6 +116,17 @@ def test_full_size_parity(name, K):
     assert np.isfinite(ll) and -12.0 < ll < -3.0
     say("[fullsize] K=%d invariants and A after iteration 1 ok, loglik %.4f (%.1fs)" % (K, ll, time.time() - t))
     g.close(); o.close()
+    if name == "C5p":
+        # the same corpus with its token lists streamed from pinned host memory (the billion-token workload's
+        # configuration: three workers, chunks as the library cuts them): assignments equal bit for bit
+        t = time.time()
+        g = pk.Saber(c.doc_ptr, c.word_ids, s.V, K, alpha, beta, seed, stream_workers=3)
+        assert g.get_stats()["chunks"] >= 3 and g.get_stats()["stream_workers"] == 3
+        g.iterate(1)
+        assert np.array_equal(g.get_z(), z)
+        assert g.loglik() == ll
+        say("[fullsize] %s host streaming, 3 workers: z and log-likelihood equal to the resident path (%.1fs)" % (name, time.time() - t))
+        g.close()
 
 
 def test_full_size_streaming_and_variants_equal_default():
