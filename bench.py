@@ -6,11 +6,15 @@
 A "step" is one full iteration of Alg. 1 over the synthetic corpus.  The corpus (seeded, generated on
 the host, resident in HBM before the timed region) has the shape of the NYTimes-like workload:
 D=300K, V=100K, T=100M.  The headline value is tokens/s at K=10,000 (the sparse regime the metric is
-quoted on); the same corpus fitted with K=1,000 is reported in "also".  Prints ONE JSON line.
+quoted on); the same corpus fitted with K=1,000 is reported in "also", and the PubMed-shaped workload
+(D=8.2M, V=141K, T=738M, K=5,000) in "also_c4", each with the roofline of its own sampling kernel.
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
 import argparse
+import glob
+import hashlib
 import json
 import os
 import sys
@@ -53,19 +57,33 @@ def algorithmic_bytes(st, K, z_bytes):
     return tok + stage
 
 
+def source_digest():
+    """Digest of the HIP sources the library is built from: the tag that ties a stored counter figure to the
+    kernels it was measured on."""
+    h = hashlib.sha256()
+    for path in sorted(glob.glob(os.path.join(ROOT, "paper_1610_02496_amd", "csrc", "*"))):
+        h.update(os.path.basename(path).encode())
+        h.update(open(path, "rb").read())
+    return h.hexdigest()[:16]
+
+
 def profiled_traffic(workload, steps, warmup):
-    """HBM bytes per launch of the sampling kernel measured with rocprofv3 --pmc on this same command
-    (summary under profiles/); None for any other command."""
-    if (workload, steps, warmup) != ("C3", 48, 2):
-        return None
-    path = os.path.join(ROOT, "profiles", "estep_kernel_C3_hbm_traffic.md")
+    """Bytes beyond L2 per pass of the sampling kernel as `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` counted them
+    on this same command (the summary under profiles/ states the command, the calibration and the digest of the
+    kernel sources it ran).  The counters cannot be read from inside the process, so the figure is a stored one:
+    it is returned only for the command line and the kernel sources it was measured with, otherwise None."""
+    path = os.path.join(ROOT, "profiles", "estep_kernel_%s_hbm_traffic.md" % workload)
     try:
-        for line in open(path):
-            if line.startswith("traffic_bytes_per_launch"):
-                return float(line.split("=")[1])
+        kv = dict(line.split("=", 1) for line in open(path) if "=" in line and line.split("=")[0].strip().isidentifier())
     except OSError:
-        pass
-    return None
+        return None
+    kv = {k.strip(): v.strip() for k, v in kv.items()}
+    if kv.get("bench_args") != "--steps %d --warmup %d" % (steps, warmup) or kv.get("source_digest") != source_digest():
+        return None
+    try:
+        return float(kv["traffic_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
 
 
 def run_holdout(g, corpus, docs, n_foldin):
@@ -87,36 +105,6 @@ def run_holdout(g, corpus, docs, n_foldin):
             "seconds": dt, "foldin_tokens_per_s": n_obs * n_foldin / dt, "loglik_per_scored_token": ll,
             "note": "documents are a prefix of the training corpus (stand-in for held-out documents); even positions "
                     "observed, odd positions scored; seconds include layout build, upload, fold-in and scoring"}
-
-
-def run_curve(corpus, K, iters, every, held_docs):
-    """Convergence over time, in the manner of the paper's Fig. 9/10 (on synthetic data): the model is trained on
-    all documents but the first ``held_docs``, which are really held out and scored by document completion (even
-    positions observed, 10 fold-in iterations) every ``every`` iterations; the clock counts training only."""
-    import paper_1610_02496_amd as pk
-    s = corpus.spec
-    t_held = int(corpus.doc_ptr[held_docs])
-    h_ptr = np.ascontiguousarray(corpus.doc_ptr[: held_docs + 1])
-    h_words = np.ascontiguousarray(corpus.word_ids[:t_held])
-    pos = np.arange(t_held) - np.repeat(h_ptr[:-1], np.diff(h_ptr))
-    observed = (pos % 2 == 0).astype(np.uint8)
-    tr_ptr = np.ascontiguousarray(corpus.doc_ptr[held_docs:] - t_held)
-    tr_words = np.ascontiguousarray(corpus.word_ids[t_held:])
-    g = pk.Saber(tr_ptr, tr_words, s.V, K, 50.0 / K, s.beta, s.seed)
-    points, train_s, it = [], 0.0, 0
-    while True:
-        ll_h, scored, _ = g.holdout_loglik(h_ptr, h_words, observed, 10, 777)
-        points.append({"iteration": it, "train_seconds": train_s, "loglik_train": g.loglik(), "loglik_holdout": ll_h})
-        log("[bench] curve K=%d %s" % (K, json.dumps(points[-1])))
-        if it >= iters:
-            break
-        n = min(every, iters - it)
-        t0 = time.perf_counter()
-        g.iterate(n)
-        train_s += time.perf_counter() - t0
-        it += n
-    g.close()
-    return {"K": K, "train_tokens": int(tr_ptr[-1]), "held_out_documents": held_docs, "scored_tokens": scored, "points": points}
 
 
 def run_gpu(corpus, K, steps, warmup, opts, holdout_docs=0):
@@ -154,7 +142,10 @@ def run_gpu(corpus, K, steps, warmup, opts, holdout_docs=0):
         "nnz_cd": st["nnz_cd"], "loglik": ll, "iterations_run": warmup + steps,
         "roofline": {"bound": "hbm", "kernel": "estep_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "bytes_per_launch": bytes_total / launches, "ms_per_launch": ms_sample / launches},
+                     "bytes_per_launch": bytes_total / launches, "ms_per_launch": ms_sample / launches,
+                     "achieved_is": "algorithmic (model) bytes of a pass / its duration between HIP events on the library's "
+                                    "stream; most of them are rows of A that the 256 MB Infinity Cache serves, so this is a "
+                                    "fraction of the HBM peak figure, not a count of HBM transactions"},
     }
     if holdout_docs:
         res["holdout"] = run_holdout(g, corpus, holdout_docs, 10)
@@ -182,34 +173,79 @@ def run_streaming(corpus, K, steps, warmup, workers, chunks):
     return res
 
 
-def run_cpu_baseline(corpus, K, docs, threads):
-    """The oracle, as it stands, on a document prefix of the same corpus: one full iteration (E-step + M-step)."""
+def cpu_model_name():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def run_cpu_baseline(corpus, K, docs):
+    """The oracle, as it stands, on a document prefix of the same corpus: one full iteration (E-step + M-step), first
+    on one thread (the canonical oracle: `value`), then on all the cores this process may use (`value_all_cores`; the
+    oracle's E-step is an OpenMP loop over tokens that read frozen counts and draw from a counter-based generator,
+    its M-step is serial).  The multi-threaded assignments must equal the single-threaded ones before either figure
+    is reported."""
     import oracle
     s = corpus.spec
     docs = min(docs, s.D)
     doc_ptr = np.ascontiguousarray(corpus.doc_ptr[: docs + 1])
     T = int(doc_ptr[-1])
     word_ids = np.ascontiguousarray(corpus.word_ids[:T])
-    m = oracle.Model(doc_ptr, word_ids, s.V, K, 50.0 / K, s.beta, s.seed)
-    t0 = time.perf_counter()
-    m.iterate(1, nthreads=threads)
-    dt = time.perf_counter() - t0
-    m.close()
-    return {"value": T / dt, "unit": "tokens/s", "cores": threads, "kind": "oracle",
-            "sample": "first %d documents (%d tokens) of the same corpus, K=%d, V=%d, iteration 1 (E-step + M-step), %.1fs"
-                      % (docs, T, K, s.V, dt)}
+    nproc = os.cpu_count() or 1
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = nproc
+    cores = max(1, min(usable, int(os.environ.get("OMP_NUM_THREADS", usable))))
+    seconds, z = {}, {}
+    for threads in (1, cores):
+        m = oracle.Model(doc_ptr, word_ids, s.V, K, 50.0 / K, s.beta, s.seed)
+        t0 = time.perf_counter()
+        m.iterate(1, nthreads=threads)
+        seconds[threads] = time.perf_counter() - t0
+        z[threads] = m.z.copy()
+        m.close()
+    assert np.array_equal(z[1], z[cores]), "the oracle's assignments depend on its thread count"
+    return {"value": T / seconds[1], "unit": "tokens/s", "cores": 1, "kind": "oracle",
+            "value_all_cores": T / seconds[cores], "cores_all": cores, "nproc": nproc, "cpu_model": cpu_model_name(),
+            "threads_bit_identical": True,
+            "sample": "first %d documents (%d tokens) of the same corpus, K=%d, V=%d, iteration 1 (E-step + M-step): %.1fs on "
+                      "1 thread, %.1fs on %d threads" % (docs, T, K, s.V, seconds[1], seconds[cores], cores)}
+
+
+def run_c4(steps, warmup, copy_gbs):
+    """The PubMed-shaped workload (D=8.2M, V=141K, T=738M, fitted K=5,000) under the same clock: short documents, a
+    third of the tokens on the dense branch; library defaults (six document chunks)."""
+    import corpusgen
+    os.environ.setdefault("LDA_CORPUS_PROGRESS", "2000000")
+    spec = corpusgen.SPECS["C4"]
+    t0 = time.time()
+    corpus = corpusgen.generate(spec, with_topics=False)
+    log("[bench] corpus %s: D=%d V=%d T=%d generated in %.1fs" % (spec.name, spec.D, spec.V, corpus.T, time.time() - t0))
+    res = run_gpu(corpus, spec.K, steps, warmup, {})
+    res["workload"] = ("C4: seeded LDA corpus D=%d V=%d T=%d (PubMed-shaped), fitted K=%d, alpha=50/K, beta=0.01, iterations "
+                       "%d..%d from the Philox initial assignment" % (spec.D, spec.V, corpus.T, spec.K, warmup + 1, warmup + steps))
+    if copy_gbs:
+        res["roofline"]["frac_of_copy_kernel"] = res["roofline"]["achieved"] / copy_gbs
+    res["roofline"]["traffic"] = profiled_traffic("C4", steps, warmup)
+    return res
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=48)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C3", choices=["C1", "C2", "C3", "C4", "C5"],
                     help="C3 (default) is the benchmark line; C4 (738 M tokens) and C5 (7.1 G tokens: 6 minutes of corpus "
                          "generation, 30 GB of host memory for the token list) are the large workloads")
     ap.add_argument("--docs", type=int, default=0, help="use only a document prefix (experiments; 0 = full corpus)")
     ap.add_argument("--no-also", action="store_true", help="skip the secondary K")
+    ap.add_argument("--no-c4", action="store_true", help="skip the PubMed-shaped workload (about 80 s: 738 M tokens to generate)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-docs", type=int, default=24000)
     ap.add_argument("--block-threads", type=int, default=0)
@@ -225,9 +261,6 @@ def main():
     ap.add_argument("--topic-conc", type=float, default=0.0,
                     help="override the mean per-word Dirichlet concentration of the planted topics (the workloads use "
                          "0.01; smaller values give topics that differ more); the workload name then says so")
-    ap.add_argument("--curve", type=int, default=0, metavar="ITERATIONS",
-                    help="also record log-likelihood over training time for this many iterations (a point every 10), "
-                         "with the first 30,000 documents really held out; 0 = skip")
     ap.add_argument("--holdout-docs", type=int, default=30000,
                     help="documents scored by the holdout log-likelihood after the timed region (0 = skip)")
     args = ap.parse_args()
@@ -254,6 +287,7 @@ def main():
     t0 = time.time()
     corpus = corpusgen.generate(spec, with_topics=False)
     log("[bench] corpus %s: D=%d V=%d T=%d generated in %.1fs" % (spec.name, spec.D, spec.V, corpus.T, time.time() - t0))
+    T_main = corpus.T
     opts = {}
     if args.block_threads: opts["block_threads"] = args.block_threads
     if args.tile_tokens: opts["tile_tokens"] = args.tile_tokens
@@ -271,8 +305,13 @@ def main():
         log("[bench] plain copy kernel: %.0f GB/s (read+write)" % copy_gbs)
     main_res = run_gpu(corpus, spec.K, args.steps, args.warmup, opts, args.holdout_docs)
     main_res["roofline"]["copy_kernel_gbs"] = copy_gbs
+    if copy_gbs:
+        main_res["roofline"]["frac_of_copy_kernel"] = main_res["roofline"]["achieved"] / copy_gbs
     if not opts and not args.docs and not args.topic_conc:
         main_res["roofline"]["traffic"] = profiled_traffic(args.workload, args.steps, args.warmup)
+        if main_res["roofline"]["traffic"] is None:
+            main_res["roofline"]["traffic_note"] = ("no counter figure stored for this command line and these kernel sources "
+                                                    "(digest %s)" % source_digest())
     log("[bench] K=%d: %s" % (spec.K, json.dumps(main_res)))
     also = None
     if args.workload == "C3" and not args.no_also:
@@ -286,8 +325,13 @@ def main():
         log("[bench] host streaming: %s" % json.dumps(streaming))
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = run_cpu_baseline(corpus, spec.K, args.cpu_docs, 1)
+        cpu = run_cpu_baseline(corpus, spec.K, args.cpu_docs)
         log("[bench] cpu baseline: %s" % json.dumps(cpu))
+    also_c4 = None
+    if args.workload == "C3" and not args.no_c4 and not opts and not args.docs and not args.topic_conc:
+        corpus = None                                # 0.4 GB; the next corpus takes 3 GB
+        also_c4 = run_c4(args.steps, args.warmup, copy_gbs)
+        log("[bench] C4: %s" % json.dumps(also_c4))
 
     out = {
         "metric": "Gibbs tokens sampled/sec/iteration (whole ESCA iteration: E-step + M-step) at K=%d" % spec.K,
@@ -296,7 +340,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": "%s: seeded LDA corpus D=%d V=%d T=%d (%s-shaped), fitted K=%d, alpha=50/K, beta=0.01, "
                                "iterations %d..%d from the Philox initial assignment"
-                               % (spec.name, spec.D, spec.V, corpus.T,
+                               % (spec.name, spec.D, spec.V, T_main,
                                   {"C4": "PubMed", "C5": "ClueWeb12-subset"}.get(args.workload, "NYTimes"), spec.K,
                                   args.warmup + 1, args.warmup + args.steps)},
         "roofline": main_res["roofline"], "cpu_baseline": cpu,
@@ -306,10 +350,10 @@ def main():
         out["holdout"] = main_res["holdout"]
     if streaming is not None:
         out["streaming"] = streaming
-    if args.curve:
-        out["curve"] = [run_curve(corpus, k, args.curve, 10, min(30000, spec.D // 2)) for k in sorted({spec.K, 1000})]
     if also is not None:
         out["also"] = also
+    if also_c4 is not None:
+        out["also_c4"] = also_c4
     print(json.dumps(out), flush=True)
 
 

@@ -88,7 +88,11 @@ typedef struct saber_options {
                                    pairs instead of the segmented count of Sec. 3.3.  Results are the same. */
     int32_t device_mem_limit_mb;/* device memory the automatic choice above may plan with, in MB; 0 (default): what
                                    hipMemGetInfo reports as free */
-    int32_t reserved[3];
+    int32_t quarter_row_entries;/* rows of A of at most this many entries (default and at most 64) are sampled four at a time,
+                                   one (word, document) run per 16 lanes of a wavefront; negative: none */
+    int32_t half_row_entries;   /* longer rows of at most this many entries (default and at most 128) two at a time, one per 32
+                                   lanes; negative: none.  Rows beyond both get all 64 lanes, in blocks of 256 entries */
+    int32_t reserved[1];
 } saber_options;
 
 /* Sums over the iterations run since the last saber_reset_stats.  The ms_* fields need profile=1. */

@@ -34,7 +34,8 @@ class Options(ctypes.Structure):
                 ("stage_phi", ctypes.c_int32), ("profile", ctypes.c_int32), ("long_doc_tokens", ctypes.c_int32),
                 ("dz_lds_entries", ctypes.c_int32), ("stage_min_tokens", ctypes.c_int32),
                 ("light_block_threads", ctypes.c_int32), ("light_word_tokens", ctypes.c_int32),
-                ("stream_workers", ctypes.c_int32), ("ablation", ctypes.c_int32), ("device_mem_limit_mb", ctypes.c_int32), ("reserved", ctypes.c_int32 * 3)]
+                ("stream_workers", ctypes.c_int32), ("ablation", ctypes.c_int32), ("device_mem_limit_mb", ctypes.c_int32),
+                ("quarter_row_entries", ctypes.c_int32), ("half_row_entries", ctypes.c_int32), ("reserved", ctypes.c_int32 * 1)]
 
 
 class Stats(ctypes.Structure):

@@ -98,6 +98,8 @@ struct Chunk {
     int64_t n_heavy = 0, n_dense = 0;
     // the chunk's documents inside the (ascending) lists of short and of long documents
     int64_t short0 = 0, nshort = 0, long0 = 0, nlong = 0;
+    // the rows of A of the chunk's documents: first row and extent, in units of 32 entries (128 bytes)
+    int64_t row_unit0 = 0, row_units = 0;
 };
 
 constexpr int kMaxSlots = 8;
@@ -212,6 +214,7 @@ extern "C" void saber_options_default(saber_options *opt) {
     if (!opt) return;
     memset(opt, 0, sizeof(*opt));
     opt->n_chunks = 0; opt->block_threads = 0; opt->tile_tokens = 8192; opt->stage_phi = 1; opt->profile = 0;
+    opt->quarter_row_entries = 64; opt->half_row_entries = 128;
     opt->long_doc_tokens = 512; opt->dz_lds_entries = 2048; opt->stage_min_tokens = 0; opt->light_block_threads = 0; opt->light_word_tokens = 0;
 }
 
@@ -253,12 +256,22 @@ static ZView z_view(const saber_ctx *c, const Chunk &ch, int slot) {
     return slot < 0 ? ZView{c->z, 0} : ZView{c->slot_z[slot], ch.t0};
 }
 
+// The rows of A the sampling kernel reads for the documents of chunk `ch` of context `theta`: all of them sit behind
+// one buffer descriptor and are addressed by 32-bit byte offsets (build() keeps every chunk's rows below 4 GB).
+static void set_rows(EStepParams &p, const saber_ctx *theta, const Chunk &ch) {
+    p.docrec = theta->docrec;
+    p.cd_rows = theta->cd_ent + (size_t)ch.row_unit0 * 32u;
+    p.row_unit0 = (uint32_t)ch.row_unit0;
+    p.rows_bytes = (uint32_t)((uint64_t)ch.row_units * 128u);
+    p.quarter_row_bytes = 4u * (uint32_t)theta->opt.quarter_row_entries; p.half_row_bytes = 4u * (uint32_t)theta->opt.half_row_entries;
+}
+
 static EStepParams make_params(saber_ctx *c, const Chunk &ch, int slot = -1) {
     EStepParams p{};
     p.tiles = c->tiles + ch.tile0;
     if (slot < 0) { p.tok_doc = c->tok_doc + ch.t0; p.tok_t = c->tok_t + ch.t0; }
     else { p.tok_doc = c->slot_tok_doc[slot]; p.tok_t = c->slot_tok_t[slot]; }
-    p.docrec = c->docrec; p.cd_ent = c->cd_ent;
+    set_rows(p, c, ch);
     p.phi = c->phi; p.l3 = c->l3; p.l3_64 = c->l3_64; p.sumphi = c->sumphi;
     const ZView zv = z_view(c, ch, slot);
     p.z = zv.z; p.z_rel = ch.t0 - zv.first;
@@ -647,16 +660,21 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
         c->have_events = true;
     }
     // ---- chunks: contiguous document ranges of about equal token count (Sec. 3.1.2) ----
+    // A chunk also ends before its rows of A (128-byte aligned slots of capacity min(L_d, K)) would pass 4 GB: the
+    // sampling kernel addresses them by 32-bit byte offsets.  That only happens with far fewer chunks than the default.
     const int nch = std::max(1, c->opt.n_chunks);
+    const int64_t unit_limit = (int64_t)0xfff00000ll / 128;
     c->chunks.clear();
     {
         int64_t d = 0;
-        for (int i = 0; i < nch; i++) {
+        for (int i = 0; i < nch || d < D; i++) {
             Chunk ch; ch.d0 = d; ch.t0 = doc_ptr[d];
-            if (i == nch - 1) d = D;
-            else {
-                const int64_t target = (T * (int64_t)(i + 1)) / nch;
-                while (d < D && doc_ptr[d + 1] <= target) d++;
+            const int64_t target = i < nch - 1 ? (T * (int64_t)(i + 1)) / nch : T;
+            int64_t units = 0;
+            while (d < D && doc_ptr[d + 1] <= target) {
+                const int64_t u = (std::min<int64_t>(doc_ptr[d + 1] - doc_ptr[d], K) + 31) / 32;
+                if (units + u > unit_limit) break;
+                units += u; d++;
             }
             ch.d1 = d; ch.ntok = doc_ptr[d] - ch.t0;
             if (ch.ntok >= (1ll << 31)) return fail(SABER_ERANGE, "saber_init: a document chunk holds %lld tokens (limit 2^31)", (long long)ch.ntok);
@@ -827,6 +845,8 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     c->cd_cap = units * 32;
     c->n_short = (int64_t)h_short.size(); c->n_long = (int64_t)h_long.size();
     for (Chunk &ch : c->chunks) {   // both lists ascend by document: a chunk's documents are a contiguous part of each
+        ch.row_unit0 = (int64_t)h_rec[(size_t)ch.d0].x;
+        ch.row_units = (ch.d1 < D ? (int64_t)h_rec[(size_t)ch.d1].x : units) - ch.row_unit0;
         ch.short0 = std::lower_bound(h_short.begin(), h_short.end(), (int32_t)ch.d0) - h_short.begin();
         ch.nshort = (std::lower_bound(h_short.begin(), h_short.end(), (int32_t)std::min<int64_t>(ch.d1, 0x7fffffff)) - h_short.begin()) - ch.short0;
         ch.long0 = std::lower_bound(h_long.begin(), h_long.end(), (int32_t)ch.d0) - h_long.begin();
@@ -988,6 +1008,8 @@ static int create_ctx(saber_ctx **out, const int64_t *doc_ptr, const int32_t *wo
         opt.stream_workers = opt_in->stream_workers;
         opt.ablation = opt_in->ablation;
         opt.device_mem_limit_mb = opt_in->device_mem_limit_mb;
+        if (opt_in->quarter_row_entries != 0) opt.quarter_row_entries = std::max(0, opt_in->quarter_row_entries);
+        if (opt_in->half_row_entries != 0) opt.half_row_entries = std::max(0, opt_in->half_row_entries);
         opt.stage_phi = opt_in->stage_phi; opt.profile = opt_in->profile;
         if (opt_in->stage_phi < 0) opt.stage_phi = 1;
     }
@@ -1009,6 +1031,8 @@ static int create_ctx(saber_ctx **out, const int64_t *doc_ptr, const int32_t *wo
     // Infinity Cache, and a corpus of several hundred million tokens samples 20 % faster than in one chunk
     if (opt.n_chunks <= 0) opt.n_chunks = (int32_t)std::max<int64_t>(1, (T + (128ll << 20) - 1) / (128ll << 20));
     if (opt.n_chunks > 65536) return fail(SABER_EINVAL, "saber_init: n_chunks too large");
+    if (opt.quarter_row_entries > 64 || opt.half_row_entries > 128)
+        return fail(SABER_EINVAL, "saber_init: quarter_row_entries must not exceed 64 and half_row_entries 128");
     if (opt.dz_lds_entries > 12288) return fail(SABER_EINVAL, "saber_init: dz_lds_entries must not exceed 12288");
     // token positions inside a chunk are 32-bit: keep every chunk below 2^30 tokens (documents are far shorter)
     opt.n_chunks = (int32_t)std::max<int64_t>(opt.n_chunks, (T >> 30) + 1);
@@ -1257,7 +1281,8 @@ static int launch_loglik(saber_ctx *c, const saber_ctx *theta, const LlScratch &
         int s = -1;
         if (c->n_slots) SABER_TRY(stream_acquire(c, ch, &s));
         EStepParams p = make_params(c, ch, s);
-        p.docrec = theta->docrec; p.cd_ent = theta->cd_ent;
+        // theta's documents are c's documents (same D, same chunks: the held-out contexts have one chunk each)
+        set_rows(p, theta, theta->chunks[(size_t)(&ch - c->chunks.data())]);
         p.out_ll = ws.tile_part;
         SABER_TRY(launch_estep<MODE_LOGLIK>(c, ch, p));
         if (c->n_slots) SABER_TRY(stream_release(c, s));

@@ -3,6 +3,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace saber {
 
@@ -177,7 +178,13 @@ struct EStepParams {
     const int32_t *tok_doc;     // [chunk tokens] document of the token (global document id)
     const uint32_t *tok_t;      // [chunk tokens] canonical token index relative to t_base
     const uint2 *docrec;        // [D] {row start in units of 32 entries, K_d}
-    const uint32_t *cd_ent;     // packed rows of A: topic | count << topic_bits, ascending topic
+    const uint32_t *cd_rows;    // packed rows of A (topic | count << topic_bits, ascending topic) from the first row of
+                                // the chunk's documents on: the row of document d starts (docrec[d].x - row_unit0) * 32
+                                // entries into it
+    uint32_t row_unit0;         // row start of the chunk's first document
+    uint32_t rows_bytes;        // bytes from cd_rows to the end of the chunk's last row (below 2^32)
+    uint32_t quarter_row_bytes; // rows up to this padded length (at most 256 bytes) are sampled four at a time, one per 16 lanes
+    uint32_t half_row_bytes;    // longer rows up to this length (at most 512 bytes) two at a time, one per 32 lanes
     const float *phi;           // [dense rows][Kpad]  Bhat
     const float *l3;            // [V][n3pad] binary32 prefix sum of the Bhat row at the end of every 64-topic block,
                                 //            padded with the row total (tree level above the bottom)
@@ -258,14 +265,19 @@ __device__ __forceinline__ uint32_t dense_query4(const float *phi_row, int phi_l
 // ---------------------------------------------------------------------------------------------
 // E-step (Alg. 2).  One workgroup per tile; the word's Bhat row and the upper tree level are staged in
 // LDS (STAGED) or read from global memory.  Each wavefront takes a batch of up to 64 tokens: the
-// per-token scalars (document, row descriptor, Philox draws) are produced one token per lane, then the
-// wavefront walks the tokens one after another.  A row of A is consumed in blocks of 256 entries, lane l
-// holding entries 4l..4l+3 (one 16-byte load per lane, 1 KB per wavefront): the lane forms its four
-// running partial products, one DPP scan over the lane sums yields both S and every prefix sum, and the
-// draw is located with one ballot plus a four-way compare inside the winning lane.  The first block of
-// the next row is fetched while the current token is processed.  Tokens are ordered by (word, document),
-// so repeated occurrences of a word in a document are neighbours: they share A_d (.) Bhat_v and S, and only
-// the two draws are repeated.
+// per-token scalars (document, row descriptor, Philox draws) are produced one token per lane.  Tokens are
+// ordered by (word, document), so repeated occurrences of a word in a document are neighbours (a "run"): they
+// share A_d (.) Bhat_v and S, and only the two draws differ.
+//
+// A row of A is consumed in pieces of 4 entries per lane (one 16-byte load per lane): the lane forms its four
+// running partial products, a DPP scan over the lane sums yields both S and every prefix sum, and the draw is
+// located with one ballot plus a four-way compare inside the winning lane.  How many lanes a run gets depends
+// on the length of its row:
+//   * rows of at most 64 entries: four runs at a time, one per DPP row of 16 lanes;
+//   * rows of at most 128 entries: two runs at a time, one per half of the wavefront;
+//   * longer rows: one run at a time over all 64 lanes, in blocks of 256 entries.
+// A lane's 16 entries sit in the same order in all three layouts and a DPP scan never crosses the lanes of a
+// group, so the sums come out bit-identical whichever layout a row gets.
 // B16: entries are packed topic:16 | count:16 (compile-time shifts); otherwise topic_bits is a run-time value.
 // ---------------------------------------------------------------------------------------------
 struct RowBlock { float a0, a1, a2, a3, incl; };   // running sums inside the lane; inclusive scan of lane sums
@@ -280,20 +292,24 @@ __device__ __forceinline__ uint4 load_block(const uint32_t *row, int rel_kd, int
     return make_uint4(v[0], v[1], v[2], v[3]);
 }
 
-// The same for a row given by its address halves and padded length in bytes (wave-uniform values read from the
-// lane of the run's first token).
-__device__ __forceinline__ uint4 load_block(uint32_t addr_lo, uint32_t addr_hi, uint32_t row_bytes, int lane) {
-    void *row = reinterpret_cast<void *>(((uint64_t)addr_hi << 32) | (uint64_t)addr_lo);
-    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(row, (short)0, (int)row_bytes, 0x00020000);
+// The same for a row given by its address and padded length in bytes (wave-uniform values).
+__device__ __forceinline__ uint4 load_block(const void *row, uint32_t row_bytes, int lane) {
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(row), (short)0, (int)row_bytes, 0x00020000);
     const auto v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane * 16, 0, 0);
     return make_uint4(v[0], v[1], v[2], v[3]);
 }
 
 // The second 256-entry block of the same row (same descriptor, 1 KB further on).
-__device__ __forceinline__ uint4 load_block2(uint32_t addr_lo, uint32_t addr_hi, uint32_t row_bytes, int lane) {
-    void *row = reinterpret_cast<void *>(((uint64_t)addr_hi << 32) | (uint64_t)addr_lo);
-    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(row, (short)0, (int)row_bytes, 0x00020000);
+__device__ __forceinline__ uint4 load_block2(const void *row, uint32_t row_bytes, int lane) {
+    __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(row), (short)0, (int)row_bytes, 0x00020000);
     const auto v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lane * 16, 16 * kWave, 0);
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
+// 16 bytes at a per-lane byte offset into the rows of a chunk; an offset of 0xffffffff (any offset past the
+// descriptor's end) returns zeros and moves no data.
+__device__ __forceinline__ uint4 load_rows_at(__amdgpu_buffer_rsrc_t rows, uint32_t byte_off) {
+    const auto v = __builtin_amdgcn_raw_buffer_load_b128(rows, (int)byte_off, 0, 0);
     return make_uint4(v[0], v[1], v[2], v[3]);
 }
 
@@ -301,6 +317,36 @@ __device__ __forceinline__ uint4 load_block2(uint32_t addr_lo, uint32_t addr_hi,
 __device__ __forceinline__ unsigned long long clear_bit(unsigned long long m, int bit) {
     asm("s_bitset0_b64 %0, %1" : "+s"(m) : "s"(bit));
     return m;
+}
+
+// lane permutations through the LDS crossbar (no LDS memory is touched); lane numbers are passed times 4
+__device__ __forceinline__ uint32_t lane_pull(uint32_t v, uint32_t src_lane4) {
+    return (uint32_t)__builtin_amdgcn_ds_bpermute((int)src_lane4, (int)v);      // every lane reads lane src
+}
+__device__ __forceinline__ float lane_pull(float v, uint32_t src_lane4) {
+    return __int_as_float(__builtin_amdgcn_ds_bpermute((int)src_lane4, __float_as_int(v)));
+}
+__device__ __forceinline__ uint32_t lane_push(uint32_t v, uint32_t dst_lane4) {
+    return (uint32_t)__builtin_amdgcn_ds_permute((int)dst_lane4, (int)v);       // every lane writes lane dst; the
+}                                                                               // highest writer wins, unwritten lanes get 0
+
+// number of set bits of a wave-uniform mask at this lane or below it
+__device__ __forceinline__ uint32_t bits_up_to_lane(unsigned long long m) {
+    const unsigned long long h = m >> 1;
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(h >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)h, (uint32_t)(m & 1ull)));
+}
+
+// Inclusive scan over the lanes of each group of G lanes (G = 16: one DPP row; 32: half a wavefront; 64: all).
+template <int G>
+__device__ __forceinline__ float group_incl_scan(float v) {
+    v += dpp_f32<0x111, 0xf>(v);
+    v += dpp_f32<0x112, 0xf>(v);
+    v += dpp_f32<0x114, 0xf>(v);
+    v += dpp_f32<0x118, 0xf>(v);
+    // see wave_incl_scan_fast for the two lines of assembly and their precondition
+    if (G >= 32) asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf" : "+v"(v));
+    if (G >= 64) asm volatile("s_nop 1\n\tv_add_f32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf" : "+v"(v));
+    return v;
 }
 
 // Bhat value of the entry's topic.  With 16/16 packing and the row in LDS the byte offset (topic * 4) is formed
@@ -318,7 +364,8 @@ __device__ __forceinline__ float phi_of(uint32_t e, uint32_t tmask, const float 
     return STAGED ? lds_phi[e & tmask] : phi_row[e & tmask];
 }
 
-template <bool STAGED, bool B16>
+// element-wise product A_d (.) Bhat_v of the lane's four entries as running sums, and their scan over the group
+template <bool STAGED, bool B16, int G = kWave>
 __device__ __forceinline__ void block_products(const uint4 e, uint32_t bits, uint32_t tmask,
                                                const float *lds_phi, const float *__restrict__ phi_row, RowBlock &b) {
     const float f0 = phi_of<STAGED, B16>(e.x, tmask, lds_phi, phi_row);
@@ -329,7 +376,7 @@ __device__ __forceinline__ void block_products(const uint4 e, uint32_t bits, uin
     b.a1 = __builtin_fmaf((float)(e.y >> bits), f1, b.a0);
     b.a2 = __builtin_fmaf((float)(e.z >> bits), f2, b.a1);
     b.a3 = __builtin_fmaf((float)(e.w >> bits), f3, b.a2);
-    b.incl = wave_incl_scan_fast(b.a3);
+    b.incl = group_incl_scan<G>(b.a3);
 }
 
 // First entry of the block whose prefix sum (carry + sums inside the block) reaches x.  The lane is found
@@ -392,11 +439,13 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
     const int lane = lane_id(), nwaves = blockDim.x / kWave;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
     const uint32_t bits = B16 ? 16u : p.topic_bits, tmask = B16 ? 0xffffu : p.topic_mask;
+    // all rows of A of the chunk behind one buffer descriptor: a row is addressed by its 32-bit byte offset
+    const __amdgpu_buffer_rsrc_t rows = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(p.cd_rows), (short)0,
+                                                                          (int)p.rows_bytes, 0x00020000);
     double ll_acc = 0.0;
-    uint32_t dense_count = 0;
     // batch size: 64 tokens per wavefront, fewer when the tile is too small to keep every wavefront busy
     int bs = (tile.count + nwaves - 1) / nwaves;
-    bs = bs > kWave ? kWave : bs;
+    bs = __builtin_amdgcn_readfirstlane(bs > kWave ? kWave : bs);   // wave-uniform: keep it in a scalar register
 
     for (int round = 0;; round++) {
         int ticket = 0;
@@ -409,7 +458,7 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
         const int i = tile.begin + batch + lane;
         const int d = act ? p.tok_doc[i] : -1;
         const uint32_t t = act ? p.tok_t[i] : 0u;
-        uint2 rec = make_uint2(0u, 0u);
+        uint2 rec = make_uint2(p.row_unit0, 0u);
         if (act) rec = p.docrec[d];
         float u0 = 0.f, u1 = 0.f;
         if (MODE == MODE_SAMPLE) {
@@ -418,42 +467,163 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
         }
         uint32_t my_z = 0; float my_S = 0.f;
         unsigned long long dense_mask = 0ull;
-        int s = 0;
 
-        // Runs: tokens are ordered by (word, document), so the tokens of one document are neighbours.  Bit i of
-        // `rest` marks a lane i > s where a new document starts.
+        // Runs: bit i of `starts` marks a lane where the tokens of another document begin.
         const int d_prev = __builtin_amdgcn_update_dpp(-2, d, 0x138, 0xf, 0xf, false);   // wave_shr:1
-        unsigned long long rest = __builtin_amdgcn_ballot_w64(act && d != d_prev) & ~1ull;
-        // every lane prepares the buffer descriptor words of its document's row, so that a run needs three
-        // lane reads and no scalar address arithmetic: address halves and the padded row length in bytes
-        const uint64_t row_addr = (uint64_t)reinterpret_cast<uintptr_t>(p.cd_ent) + ((uint64_t)rec.x << 7);
-        const uint32_t ra_lo = (uint32_t)row_addr, ra_hi = (uint32_t)(row_addr >> 32);
-        const uint32_t ra_bytes = ((rec.y + 3u) & ~3u) << 2;
-        unsigned long long below_s = 0ull;   // lanes before the current run
+        const bool first_of_run = act && d != d_prev;
+        const unsigned long long starts = __builtin_amdgcn_ballot_w64(first_of_run) | 1ull;
+        // the row of the lane's document: byte offset inside the chunk's rows and padded length in bytes
+        const uint32_t row_off = (rec.x - p.row_unit0) << 7;
+        const uint32_t row_bytes = ((rec.y + 3u) & ~3u) << 2;
+        // position of the token inside its run
+        const uint32_t jpos = (uint32_t)(lane - wave_incl_scan_max(first_of_run || lane == 0 ? lane : -1));
+        // rows that fit a quarter or a half of the wavefront; runs are cut into pieces of at most G tokens there
+        unsigned long long m16 = __builtin_amdgcn_ballot_w64(act && row_bytes <= p.quarter_row_bytes);
+        unsigned long long m32 = __builtin_amdgcn_ballot_w64(act && row_bytes <= p.half_row_bytes) & ~m16;
+        const unsigned long long cuts16 = __builtin_amdgcn_ballot_w64(act && (jpos & 15u) == 0u);   // where pieces begin
+        const unsigned long long cuts32 = __builtin_amdgcn_ballot_w64(act && (jpos & 31u) == 0u);
+        // a pass serves four (two) runs at the cost of about one: a class that would not fill most of one pass goes
+        // with the next wider one
+        if (__builtin_popcountll(m16 & cuts16) < 3) { if (p.half_row_bytes >= p.quarter_row_bytes) m32 |= m16; m16 = 0ull; }
+        if (__builtin_popcountll(m32 & cuts32) < 2) m32 = 0ull;
+        const unsigned long long cm16 = m16 & cuts16, cm32 = m32 & cuts32;
+        unsigned long long wide_rest = starts & ~(m16 | m32);
 
-        // One run [s, s_end) of tokens of this word in one document: they share A_d (.) Bhat_v and S.
-        // `cur` holds the first block of the run's row (fetched during the previous run) and cur_bytes the row's
-        // padded length; the first block of the next run's row is fetched into `nxt` before this run's
-        // arithmetic starts.
-        auto do_run = [&](const uint4 &cur, const uint4 &cur2, const uint32_t cur_bytes, uint4 &nxt, uint4 &nxt2, uint32_t &nxt_bytes) {
-            const bool more = rest != 0ull;       // run starts are marked on active lanes only
-            const int s_end = more ? (int)__builtin_ctzll(rest) : n;
-            // The next run's row is requested here, without any branch around the two loads: after the last run
-            // (and for the second block of a short row) the descriptor's length makes every lane fall outside the
-            // row, which returns zeros and moves no data.  A load inside a branch would make the compiler wait for
-            // ALL outstanding loads where the branches meet, i.e. for the row just requested, before this run's
-            // arithmetic - the request has to be unconditional for its latency to pass under the arithmetic.
-            {
-                const int src = more ? s_end : 0;
-                rest = clear_bit(rest, src);      // bit 0 is never set in `rest`
-                nxt_bytes = more ? readlane_u32(ra_bytes, src) : 0u;
-                const uint32_t lo = readlane_u32(ra_lo, src), hi = readlane_u32(ra_hi, src);
-                nxt = load_block(lo, hi, nxt_bytes, lane);
-                nxt2 = load_block2(lo, hi, nxt_bytes, lane);
+        // ---- rows of at most 4 G entries: 64 / G runs at a time, one per group of G lanes ----
+        // Token side: lane i holds token i of the batch.  Group side: the G lanes of group g hold the row of the
+        // g-th run of the pass, 4 entries per lane.  Per class, the runs' row offsets and lengths are first packed
+        // into the low lanes (slot r = r-th run of the class); a pass then pulls four (two) slots.
+        auto run_class = [&](auto G_, const unsigned long long cm, const unsigned long long cuts, const bool in_class) {
+            constexpr int G = decltype(G_)::value, NG = kWave / G, LG = G == 16 ? 4 : 5;
+            const int nruns = (int)__builtin_popcountll(cm);   // wave-uniform
+            if (nruns == 0) return;
+            uint32_t zero = 0u;
+            asm volatile("" : "+s"(zero));   // (keeps the compiler from running the set-up below ahead of this test)
+            const int npass = (nruns + NG - 1) / NG;
+            const uint32_t gi = (uint32_t)lane >> LG, li = (uint32_t)lane & (uint32_t)(G - 1), li16 = li << 4;
+            const uint32_t rank = bits_up_to_lane(cm);          // pieces of the class that start at this lane or before
+            // slots: a piece's first lane writes to slot rank - 1; all other lanes write to lane 63, which is a slot
+            // only if every lane starts a piece
+            const uint32_t dst4 = __builtin_amdgcn_inverse_ballot_w64(cm) ? (rank - 1u) << 2 : 252u + zero;
+            const uint32_t slot_pk = lane_push(row_bytes | ((uint32_t)lane << 18), dst4);   // length | first token lane * 4 << 16
+            const uint32_t slot_off = lane_push(row_off, dst4);
+            const uint32_t my_piece = in_class ? rank - 1u : 0x80000000u;   // token side: piece of this token
+            const uint32_t jg4 = (jpos & (uint32_t)(G - 1)) << 2;           // and its place in it, times 4
+            constexpr unsigned long long ONES = G == 16 ? 0x0001000100010001ull : 0x0000000100000001ull;   // first lane of every group
+
+            // request the rows of pass `ps` (past the last pass: nothing is moved)
+            auto issue = [&](const int ps, uint4 &blk, uint32_t &pk) {
+                uint32_t idx = (uint32_t)(ps * NG) + gi;
+                idx = idx < (uint32_t)nruns ? idx : (uint32_t)(nruns - 1);   // spare groups repeat the last run
+                pk = lane_pull(slot_pk, idx << 2);
+                const uint32_t off = lane_pull(slot_off, idx << 2);
+                const uint32_t lim = ps < npass ? pk & 0xffffu : 0u;
+                blk = load_rows_at(rows, li16 < lim ? off + li16 : 0xffffffffu);
+            };
+            auto compute = [&](const int ps, const uint4 &cur, const uint32_t pk) {
+                RowBlock b;
+                block_products<STAGED, B16, G>(cur, bits, tmask, lds_phi, phi_row, b);
+                // S of the group's run in all its lanes
+                const float S = G == 16 ? dpp_f32<0x15f, 0xf>(b.incl)                    // row_newbcast:15
+                                        : lane_pull(b.incl, (uint32_t)(lane | (G - 1)) << 2);
+                // token side: is this token's piece part of the pass, and which lane will hold its result
+                const uint32_t gt = my_piece - (uint32_t)(ps * NG);
+                const bool in_pass = gt < (uint32_t)NG;
+                const uint32_t src4 = (gt << (LG + 2)) + jg4;
+                uint32_t zacc = 0u;
+                if (MODE == MODE_SAMPLE) {
+                    const float base = b.incl - b.a3;
+                    const float p0 = base + b.a0, p1 = base + b.a1, p2 = base + b.a2;
+                    // the last lane of every group's row: if rounding leaves no lane, the choice falls on it (its padding
+                    // repeats the row's last topic)
+                    const unsigned long long sent = __builtin_amdgcn_ballot_w64(li16 + 16u == (pk & 0xffffu));
+                    const unsigned long long pass_mask = __builtin_amdgcn_ballot_w64(in_pass);
+                    // Lane j of a group collects the result of the j-th token of the group's piece.  `todo` marks the
+                    // token lanes at position j of the pass's pieces: when it is empty, no piece is that long.
+                    unsigned long long todo = pass_mask & cuts, collect = ONES;
+                    uint32_t ua = pk >> 16;                           // lane * 4 of the token that is served next
+                    uint32_t da = (uint32_t)(lane & ~(G - 1)) << 2;   // lane * 4 of the group lane that collects its result
+                    float x = lane_pull(u1, ua) * S;
+                    while (todo) {
+                        // problem 1 for one token per group: position of x in the prefix sums of P.  (Whether the
+                        // token takes this branch is decided on the token side, once S has arrived there.)
+                        ua += 4u;
+                        const float x_next = lane_pull(u1, ua) * S;
+                        const unsigned long long ge = __builtin_amdgcn_ballot_w64(b.incl >= x) | sent;
+                        const unsigned long long win = ge & ~(ge - ONES);   // first such lane of every group
+                        uint32_t sel = cur.w;
+                        sel = p2 >= x ? cur.z : sel;
+                        sel = p1 >= x ? cur.y : sel;
+                        sel = p0 >= x ? cur.x : sel;
+                        // the winning lane writes to the collecting lane, every other lane to the collecting lane's
+                        // neighbour, whose own turn to collect is another one
+                        const uint32_t got = lane_push(sel, da + (__builtin_amdgcn_inverse_ballot_w64(win) ? 0u : 4u));
+                        zacc = __builtin_amdgcn_inverse_ballot_w64(collect) ? got : zacc;
+                        da += 4u; collect <<= 1;
+                        todo = (todo << 1) & pass_mask & ~cuts;
+                        x = x_next;
+                    }
+                }
+                const float St = lane_pull(S, src4);
+                my_S = in_pass ? St : my_S;
+                if (MODE == MODE_SAMPLE) {
+                    const uint32_t zt = lane_pull(zacc, src4);
+                    my_z = in_pass ? zt & tmask : my_z;
+                }
+            };
+            uint4 blk_a, blk_b; uint32_t pk_a, pk_b;
+            issue(0, blk_a, pk_a);
+            for (int ps = 0;; ps += 2) {
+                issue(ps + 1, blk_b, pk_b);
+                compute(ps, blk_a, pk_a);
+                if (ps + 1 >= npass) break;
+                issue(ps + 2, blk_a, pk_a);
+                compute(ps + 1, blk_b, pk_b);
+                if (ps + 2 >= npass) break;
             }
-            const unsigned long long below_end = ~0ull >> (kWave - s_end);   // 1 <= s_end <= 64
-            const unsigned long long in_run = below_end & ~below_s;
-            below_s = below_end;
+        };
+        // ---- longer rows: one run [s, s_end) at a time over the whole wavefront ----
+        // `cur` and `cur2` hold the first two blocks of the run's row (fetched during the previous run) and cur_bytes the
+        // row's padded length; the next run's row is fetched into `nxt`, `nxt2` before this run's arithmetic starts.
+        const char *rows_base = reinterpret_cast<const char *>(p.cd_rows);
+        auto fetch = [&](const int s, uint4 &blk, uint4 &blk2, uint32_t &bytes) {
+            // Requested without any branch around the two loads: for s < 0 (no further run), and for the second
+            // block of a short row, the descriptor's length makes every lane fall outside the row, which returns zeros
+            // and moves no data.  A load inside a branch would make the compiler wait for ALL outstanding loads where
+            // the branches meet, i.e. for the row just requested, before the current run's arithmetic.
+            const int src = s < 0 ? 0 : s;
+            bytes = s < 0 ? 0u : readlane_u32(row_bytes, src);
+            const void *row = rows_base + readlane_u32(row_off, src);
+            blk = load_block(row, bytes, lane);
+            blk2 = load_block2(row, bytes, lane);
+        };
+        auto next_wide = [&]() {
+            if (!wide_rest) return -1;
+            const int s = (int)__builtin_ctzll(wide_rest);
+            wide_rest = clear_bit(wide_rest, s);
+            return s;
+        };
+        // the first of the long rows is requested now, so that it arrives while the short rows are worked on
+        int s_a = next_wide(), s_b = -1;
+        uint32_t bytes_a, bytes_b;
+        uint4 blk_a, blk_a2, blk_b, blk_b2;
+        fetch(s_a, blk_a, blk_a2, bytes_a);
+
+        run_class(std::integral_constant<int, 16>{}, cm16, cuts16, __builtin_amdgcn_inverse_ballot_w64(m16));
+        run_class(std::integral_constant<int, 32>{}, cm32, cuts32, __builtin_amdgcn_inverse_ballot_w64(m32));
+        if (MODE == MODE_SAMPLE && (m16 | m32)) {
+            // the coin of the tokens served above, all at once
+            const unsigned long long sparse = __builtin_amdgcn_ballot_w64(u0 * (my_S + Q) < my_S);
+            dense_mask = (m16 | m32) & ~sparse;
+        }
+
+        // ---- longer rows: one run [s, s_end) at a time over the whole wavefront (its first fetch went out above) ----
+        auto do_run = [&](const int s, const uint4 &cur, const uint4 &cur2, const uint32_t cur_bytes, const int s_next, uint4 &nxt,
+                          uint4 &nxt2, uint32_t &nxt_bytes) {
+            fetch(s_next, nxt, nxt2, nxt_bytes);
+            const unsigned long long later = starts & (~1ull << s);           // run starts after lane s
+            const int s_end = later ? (int)__builtin_ctzll(later) : n;
+            const unsigned long long in_run = (~0ull >> (kWave - s_end)) & (~0ull << s);   // 0 <= s < s_end <= 64
             // element-wise product A_d (.) Bhat_v, its prefix sums and its sum S (Alg. 2, product loop)
             RowBlock b0;
             block_products<STAGED, B16>(cur, bits, tmask, lds_phi, phi_row, b0);
@@ -486,11 +656,10 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
                 } else {
                     if (lane >= s && lane < s_end) my_S = t0;
                 }
-                s = s_end;
                 return;
             }
-            const int kd = (int)readlane_u32(rec.y, s);
-            const uint32_t *row = p.cd_ent + (size_t)readlane_u32(rec.x, s) * 32u;
+            const int kd = (int)(cur_bytes >> 2);   // the row's length rounded up to 4 entries: the padding has count 0
+            const uint32_t *row = reinterpret_cast<const uint32_t *>(rows_base + readlane_u32(row_off, s));
             const int nblk = (kd + 4 * kWave - 1) / (4 * kWave);
             const uint4 e1 = cur2;
             RowBlock b1;
@@ -533,22 +702,32 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
             } else {
                 if (lane >= s && lane < s_end) my_S = S;
             }
-            s = s_end;
         };
 
-        uint32_t bytes_a = readlane_u32(ra_bytes, 0), bytes_b = 0u;
-        uint4 blk_a = load_block(readlane_u32(ra_lo, 0), readlane_u32(ra_hi, 0), bytes_a, lane);
-        uint4 blk_b = make_uint4(0u, 0u, 0u, 0u), blk_a2 = blk_b, blk_b2 = blk_b;
-        blk_a2 = load_block2(readlane_u32(ra_lo, 0), readlane_u32(ra_hi, 0), bytes_a, lane);
-        while (s < n) {
-            do_run(blk_a, blk_a2, bytes_a, blk_b, blk_b2, bytes_b);
-            if (s >= n) break;
-            do_run(blk_b, blk_b2, bytes_b, blk_a, blk_a2, bytes_a);
+        if (s_a >= 0) {
+            for (;;) {
+                s_b = next_wide();
+                do_run(s_a, blk_a, blk_a2, bytes_a, s_b, blk_b, blk_b2, bytes_b);
+                if (s_b < 0) break;
+                s_a = next_wide();
+                do_run(s_b, blk_b, blk_b2, bytes_b, s_a, blk_a, blk_a2, bytes_a);
+                if (s_a < 0) break;
+            }
+        }
+
+        // The token's number is read again rather than carried through the batch in a register (the kernel is at its
+        // register limit; the 4 bytes come from a cache line this wavefront loaded at the top of the batch).  Requested
+        // here, it arrives while the dense branch below is served.
+        uint32_t t_late = 0u;
+        if (MODE != MODE_LOGLIK) {
+            uint32_t pos_t = (uint32_t)(batch + lane);
+            asm volatile("" : "+v"(pos_t));
+            if (act) t_late = p.tok_t[tile.begin + (int)pos_t];
         }
 
         if (MODE == MODE_SAMPLE && dense_mask) {
             // problem 2 for the tokens whose coin chose it: DPP row g (16 lanes) serves the g-th of up to four tokens
-            dense_count += (uint32_t)__builtin_popcountll(dense_mask);
+            if (lane == 0) atomicAdd(&wg_dense, (unsigned int)__builtin_popcountll(dense_mask));   // statistic only
             const float xd = u1 * sum_w;
             const int g = lane >> 4, li = lane & 15;
             while (dense_mask) {
@@ -570,11 +749,13 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
 
         if (act) {
             if (MODE == MODE_SAMPLE) {
-                reinterpret_cast<ZT *>(p.z)[p.z_rel + (int64_t)t] = (ZT)my_z;
+                reinterpret_cast<ZT *>(p.z)[p.z_rel + (int64_t)t_late] = (ZT)my_z;
                 // the second copy, in word-major order, is what CountByVZ reads (coalesced here and there)
-                reinterpret_cast<ZT *>(p.z_wm)[tile.wm_begin + (int64_t)(i - tile.begin)] = (ZT)my_z;
+                uint32_t pos = (uint32_t)(batch + lane);   // of the token inside the tile
+                asm volatile("" : "+v"(pos));
+                reinterpret_cast<ZT *>(p.z_wm)[tile.wm_begin + (int64_t)pos] = (ZT)my_z;
             } else if (MODE == MODE_PROBS) {
-                p.out_S[t] = my_S; p.out_Q[t] = Q;
+                p.out_S[t_late] = my_S; p.out_Q[t_late] = Q;
             } else {
                 ll_acc += log((double)(my_S + Q));
             }
@@ -582,7 +763,6 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
     }
 
     if (MODE == MODE_SAMPLE) {
-        if (lane == 0 && dense_count) atomicAdd(&wg_dense, dense_count);
         __syncthreads();
         if (threadIdx.x == 0 && wg_dense) atomicAdd(p.n_dense + (blockIdx.x & (kDenseSlots - 1)), (unsigned long long)wg_dense);
     }

@@ -177,6 +177,44 @@ def test_mixed_row_lengths_in_one_tile():
     assert_estep_parity(g, o)
 
 
+@pytest.mark.parametrize("V", [3, 40, 900])
+def test_short_rows_share_a_wavefront(V):
+    """Rows of at most 64 entries are sampled four at a time (one per 16 lanes), rows of at most 128 entries two at
+    a time, longer ones with all 64 lanes.  Documents of 1 to 700 tokens over a vocabulary of V words: with V = 3
+    a (word, document) run holds up to a few hundred tokens, far more than the 16 or 32 a group of lanes collects in
+    one piece; with V = 900 nearly every run is a single token.  Every way of dividing the rows among the three
+    layouts must give the assignments of the plain one-run-per-wavefront layout, which is held against the oracle."""
+    rng = np.random.default_rng(V)
+    lens = np.r_[rng.integers(1, 60, 150), rng.integers(60, 130, 150), rng.integers(130, 260, 60), rng.integers(260, 700, 25)]
+    rng.shuffle(lens)
+    doc_ptr = np.r_[0, np.cumsum(lens)].astype(np.int64)
+    word_ids = np.minimum((V * rng.random(int(doc_ptr[-1])) ** 1.5).astype(np.int32), V - 1)
+    K, alpha, beta, seed = 2000, 0.02, 0.01, 5
+    pk = saber()
+    g = pk.Saber(doc_ptr, word_ids, V, K, alpha, beta, seed, quarter_row_entries=-1, half_row_entries=-1)
+    o = oracle.Model(doc_ptr, word_ids, V, K, alpha, beta, seed)
+    kd = np.diff(o.cd[0])
+    assert (kd <= 64).sum() > 50 and ((kd > 64) & (kd <= 128)).sum() > 50 and (kd > 128).sum() > 50
+    assert_estep_parity(g, o)
+    assert_estep_parity(g, o)
+    z_ref, ll_ref = g.get_z(), g.loglik()
+    S_ref = g.token_probs(np.arange(o.T, dtype=np.int64))[0]
+    g.close()
+    for opts in [{}, {"half_row_entries": -1}, {"quarter_row_entries": -1}, {"quarter_row_entries": 20, "half_row_entries": 70},
+                 {"quarter_row_entries": 64, "half_row_entries": 64}, {"tile_tokens": 64}, {"n_chunks": 3, "stream_workers": 2},
+                 {"block_threads": 64, "light_word_tokens": -1}]:
+        g = pk.Saber(doc_ptr, word_ids, V, K, alpha, beta, seed, **opts)
+        g.iterate(2)
+        assert np.array_equal(g.get_z(), z_ref), opts
+        if set(opts) <= {"quarter_row_entries", "half_row_entries"}:
+            assert g.loglik() == ll_ref, opts                                      # same sums in the same order
+        else:
+            assert abs(g.loglik() - ll_ref) <= 1e-12 * abs(ll_ref), opts           # tiles and chunks regroup the sum
+        assert np.array_equal(g.token_probs(np.arange(o.T, dtype=np.int64))[0], S_ref), opts
+        g.close()
+    o.close()
+
+
 def test_large_counts_in_a_row():
     """Few topics and documents of 6,000 to 30,000 tokens: single entries of A with counts of many thousands next
     to ordinary rows (16/16 packing is used up to its limit of 65,535 tokens per document)."""
@@ -274,7 +312,8 @@ def test_results_do_not_depend_on_layout_options():
     for opts in [{}, {"n_chunks": 4}, {"tile_tokens": 64, "block_threads": 128}, {"stage_phi": 0},
                  {"long_doc_tokens": 16, "dz_lds_entries": 8}, {"stage_min_tokens": 65, "light_block_threads": 128},
                  {"stage_min_tokens": 100000}, {"light_word_tokens": -1}, {"light_word_tokens": 1 << 20},
-                 {"light_word_tokens": 30, "n_chunks": 2}]:
+                 {"light_word_tokens": 30, "n_chunks": 2}, {"quarter_row_entries": -1}, {"half_row_entries": 40},
+                 {"quarter_row_entries": 10, "half_row_entries": -1}]:
         g = pk.Saber(c.doc_ptr, c.word_ids, c.spec.V, 300, 0.2, 0.01, 77, **opts)
         g.iterate(3)
         z = g.get_z()
@@ -413,6 +452,8 @@ def test_random_shapes_and_options(test_seed):
         if rng.random() < 0.3: opts["long_doc_tokens"] = int(rng.choice([8, 64]))
         if rng.random() < 0.3: opts["dz_lds_entries"] = int(rng.choice([4, 64]))
         if rng.random() < 0.2: opts["stage_phi"] = 0
+        if rng.random() < 0.3: opts["quarter_row_entries"] = int(rng.choice([-1, 4, 30, 64]))
+        if rng.random() < 0.3: opts["half_row_entries"] = int(rng.choice([-1, 8, 100, 128]))
         mode = rng.random()
         if mode < 0.25: opts["stream_workers"] = int(rng.integers(1, 5))
         elif mode < 0.45: opts["ablation"] = int(rng.integers(1, 4))
