@@ -191,6 +191,20 @@ int saber_counts(saber_ctx *ctx, int64_t *cd_row_ptr, int32_t *cd_topic, int32_t
 int saber_loglik(saber_ctx *ctx, double *per_token_ll);
 
 /*
+ * saber_loglik for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the same kernels and the same order of additions, hence the same number, but the
+ * work space of the reduction (per-workgroup partial sums) is a static device array of the library instead of memory
+ * of the context, and the call itself allocates nothing on host or device.
+ *   d_result  DEVICE pointer to one double, owned by the caller; written on the context's stream, which the call
+ *             waits for before it returns
+ * Limit: at most 2^20 sampling workgroups per document chunk (8 MB of static work space per GPU, held until the
+ * process ends); more is refused with ERANGE.  All calls on one GPU share that array: it keeps the last call's
+ * contents (nothing in it has to start at zero), and calls that overlap in time on one GPU race.
+ * Errors: EINVAL, ERANGE, ESTATE (the context's device has no work space), EDEVICE.
+ */
+int saber_loglik_static(saber_ctx *ctx, double *d_result);
+
+/*
  * Holdout log-likelihood per token of held-out documents, "partially-observed document" approach (the quality
  * metric of Sec. 4; the paper prints no formula, the reading taken is document completion).  The model of ctx
  * (Bhat, trees) stays frozen and ctx is not changed.

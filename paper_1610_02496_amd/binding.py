@@ -18,7 +18,7 @@ _STATUS = {0: "SABER_OK", -1: "SABER_EINVAL", -2: "SABER_ENOMEM", -3: "SABER_EDE
 
 # every symbol include/saber.h declares
 EXPORTS = ["saber_set_hooks", "saber_options_default", "saber_init_ex", "saber_init", "saber_iterate", "saber_counts_nnz",
-           "saber_counts", "saber_loglik", "saber_holdout_loglik", "saber_free", "saber_last_error", "saber_get_z", "saber_set_z",
+           "saber_counts", "saber_loglik", "saber_loglik_static", "saber_holdout_loglik", "saber_free", "saber_last_error", "saber_get_z", "saber_set_z",
            "saber_get_iteration", "saber_token_probs", "saber_get_phi", "saber_get_stats", "saber_reset_stats",
            "saber_get_stream", "saber_bandwidth_probe", "saber_alias_build_probe"]
 
@@ -79,6 +79,7 @@ def load_library():
         "saber_counts_nnz": (ctypes.c_int, [vp, vp]),
         "saber_counts": (ctypes.c_int, [vp, vp, vp, vp, vp, vp]),
         "saber_loglik": (ctypes.c_int, [vp, vp]),
+        "saber_loglik_static": (ctypes.c_int, [vp, vp]),
         "saber_holdout_loglik": (ctypes.c_int, [vp, vp, vp, vp, i64, i32, u64, vp, vp, vp, vp]),
         "saber_free": (None, [vp]),
         "saber_last_error": (ctypes.c_char_p, []),
@@ -226,6 +227,14 @@ class Saber:
         v = ctypes.c_double()
         _check(load_library().saber_loglik(self._h, ctypes.addressof(v)))
         return v.value
+
+    def loglik_static(self) -> float:
+        """saber_loglik_static: the same number through the entry point that allocates nothing; the result lands in
+        device memory of the caller (a torch tensor here) and is read back."""
+        import torch
+        out = torch.zeros(1, dtype=torch.float64, device="cuda")
+        _check(load_library().saber_loglik_static(self._h, ctypes.c_void_p(out.data_ptr())))
+        return float(out.cpu()[0])
 
     def holdout_loglik(self, doc_ptr, word_ids, observed, n_foldin, seed, z_init=None):
         """Document-completion log-likelihood of held-out documents; returns (ll per scored token, scored tokens,

@@ -964,6 +964,8 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     return SABER_OK;
 }
 
+static int static_scratch_init(int device);
+
 // saber_init_ex, or with `parent` a context for held-out documents that borrows the parent's model
 static int create_ctx(saber_ctx **out, const int64_t *doc_ptr, const int32_t *word_ids, int64_t D, int32_t V,
                       int32_t K, float alpha, float beta, uint64_t seed, const saber_options *opt_in,
@@ -1045,6 +1047,7 @@ static int create_ctx(saber_ctx **out, const int64_t *doc_ptr, const int32_t *wo
     if (!c) return fail(SABER_ENOMEM, "saber_init: out of host memory");
     c->hooks = parent ? parent->hooks : g_hooks;
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; return fail(SABER_EDEVICE, "saber_init: hipGetDevice failed"); }
+    { const int rc0 = static_scratch_init(c->device); if (rc0 != SABER_OK) { delete c; return rc0; } }
     c->D = D; c->T = T; c->V = V; c->K = K; c->alpha = alpha; c->beta = beta; c->seed = seed; c->opt = opt;
     c->parent = parent; c->no_state = no_state;
     c->n_slots = std::max(0, opt.stream_workers);
@@ -1311,6 +1314,41 @@ extern "C" int saber_loglik(saber_ctx *c, double *out) {
     SABER_TRY(sync_all(c));
     HIP_TRY(hipMemcpy(out, ws.result, sizeof(double), hipMemcpyDeviceToHost));
     return SABER_OK;
+}
+
+// ---- the same reduction for callers that must not allocate ----
+// The work space is a file-scope device array instead of the context's allocation.  Every device has its own copy of
+// the array at its own address, looked up once per device (saber_init does it, with that device current); host code
+// uses that address only, never the array's name.
+constexpr size_t kStaticLlTiles = (size_t)1 << 20;   // per-tile sums of one chunk: 8 MB
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) double g_ll_static[kStaticLlTiles + kLlTail];
+static double *g_ll_static_ptr[kMaxDevices] = {};
+
+static int static_scratch_init(int device) {
+    if (device < 0 || device >= kMaxDevices) return fail(SABER_ERANGE, "device %d is beyond the %d devices the library keeps work space for", device, kMaxDevices);
+    if (g_ll_static_ptr[device]) return SABER_OK;
+    double *ptr = nullptr;
+    HIP_TRY(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(g_ll_static)));
+    if (!ptr) return fail(SABER_EDEVICE, "hipGetSymbolAddress returned no address for the static work space");
+    g_ll_static_ptr[device] = ptr;
+    return SABER_OK;
+}
+
+extern "C" int saber_loglik_static(saber_ctx *c, double *d_result) {
+    if (!c || !d_result) return fail(SABER_EINVAL, "saber_loglik_static: null argument");
+    if ((size_t)c->max_chunk_tiles > kStaticLlTiles)
+        return fail(SABER_ERANGE, "saber_loglik_static: a chunk of %lld sampling workgroups exceeds the static work space of %zu "
+                    "(use saber_loglik, or more chunks)", (long long)c->max_chunk_tiles, kStaticLlTiles);
+    double *base = (c->device >= 0 && c->device < kMaxDevices) ? g_ll_static_ptr[c->device] : nullptr;
+    if (!base) return fail(SABER_ESTATE, "saber_loglik_static: no static work space on device %d", c->device);
+    if (c->T == 0) {
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(64), 0, c->stream, reinterpret_cast<uint32_t *>(d_result), 0u, (size_t)2);
+        HIP_TRY(hipGetLastError());
+    } else {
+        SABER_TRY(launch_loglik(c, c, ll_scratch(base, kStaticLlTiles), d_result));
+    }
+    return sync_all(c);
 }
 
 // ------------------------------------------------------------------------------------------------
