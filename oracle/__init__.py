@@ -56,6 +56,10 @@ def lib():
         "orc_sample": (c_i32, [c_i32, c_void_p, c_void_p, c_void_p, c_void_p, c_i32, c_f64, c_f64, c_f64, c_void_p]),
         "orc_estep": (None, [c_i64, c_void_p, c_void_p, c_i32, c_f32, c_void_p, c_void_p, c_void_p, c_void_p,
                              c_void_p, c_void_p, c_u64, c_u32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int]),
+        "orc_alias_build": (None, [c_void_p, c_i32, c_void_p, c_void_p]),
+        "orc_alias_draw": (c_i32, [c_void_p, c_void_p, c_i32, c_u32, c_void_p]),
+        "orc_estep_alias": (None, [c_i64, c_void_p, c_void_p, c_i32, c_f32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p,
+                                   c_void_p, c_void_p, c_u64, c_u32, c_void_p, c_void_p, c_void_p, c_int]),
         "orc_loglik": (c_f64, [c_i64, c_void_p, c_void_p, c_i32, c_f32, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p]),
         "orc_model_create": (c_void_p, [c_void_p, c_void_p, c_i64, c_i32, c_i32, c_f32, c_f32, c_u64]),
         "orc_model_free": (None, [c_void_p]),
@@ -178,6 +182,30 @@ def sample(topic, count, phi_w, c32_w, Q, u0, u1):
     return k, det
 
 
+def alias_build(p):
+    """Alias table (Walker's method, sweep construction) of one weight vector: (prob float32[K], alias int32[K])."""
+    p = np.ascontiguousarray(p, dtype=np.float32)
+    prob = np.empty(p.size, dtype=np.float32); alias = np.empty(p.size, dtype=np.int32)
+    lib().orc_alias_build(_p(p), p.size, _p(prob), _p(alias))
+    return prob, alias
+
+
+def alias_draw(prob, alias, bits24):
+    """Walker's draw for the uniform bits24 * 2^-24; returns (item, margin)."""
+    prob = np.ascontiguousarray(prob, dtype=np.float32); alias = np.ascontiguousarray(alias, dtype=np.int32)
+    m = c_f64()
+    k = lib().orc_alias_draw(_p(prob), _p(alias), prob.size, int(bits24), ctypes.addressof(m))
+    return k, m.value
+
+
+def alias_mass(prob, alias):
+    """The distribution a table encodes: (prob[k] + sum of (1 - prob[b]) over buckets b whose alias is k) / K."""
+    prob = np.asarray(prob, dtype=np.float64)
+    mass = prob.copy()
+    np.add.at(mass, np.asarray(alias), 1.0 - prob)
+    return mass / prob.size
+
+
 # ----------------------------------------------------------------------------- whole model
 class Model:
     """Alg. 1 as a stateful object: iteration 0 = Philox-initialised z and a first M-step."""
@@ -230,6 +258,27 @@ class Model:
 
     def loglik(self):
         return lib().orc_model_loglik(self._h)
+
+    def alias_tables(self):
+        """Alias tables of all V rows of the current Bhat: (prob float32[V,K], alias int32[V,K])."""
+        phi = self.phi
+        prob = np.empty((self.V, self.K), dtype=np.float32); alias = np.empty((self.V, self.K), dtype=np.int32)
+        for v in range(self.V):
+            lib().orc_alias_build(phi[v].ctypes.data, self.K, prob[v].ctypes.data, alias[v].ctypes.data)
+        return prob, alias
+
+    def estep_alias(self, prob, alias, nthreads=1):
+        """One E-step from the current state (iteration iter+1) with the dense term drawn from the given alias tables;
+        the state is not changed.  Returns (z, branch, margin)."""
+        prob = np.ascontiguousarray(prob, dtype=np.float32); alias = np.ascontiguousarray(alias, dtype=np.int32)
+        assert prob.shape == (self.V, self.K) and alias.shape == (self.V, self.K)
+        z = np.empty(self.T, dtype=np.int32); br = np.empty(self.T, dtype=np.int8); mg = np.empty(self.T)
+        cd_ptr, cd_topic, cd_count = self.cd
+        cd_topic = np.ascontiguousarray(cd_topic); cd_count = np.ascontiguousarray(cd_count)
+        lib().orc_estep_alias(self.D, _p(self.doc_ptr), _p(self.word_ids), self.K, np.float32(self.alpha), _p(cd_ptr),
+                              _p(cd_topic), _p(cd_count), _p(self.phi), _p(self.sum64), _p(prob), _p(alias),
+                              self.seed, self.iter + 1, _p(z), _p(br), _p(mg), nthreads)
+        return z, br, mg
 
     def holdout_loglik(self, doc_ptr, word_ids, observed, n_fold, seed, z_init=None, nthreads=1):
         """Document-completion log-likelihood of held-out documents under this model's frozen Bhat: fold in the

@@ -41,7 +41,9 @@
  * for several W, the split sampler's induced measure and chi-square against the
  * dense Eq. 1, planted-topic recovery, dense evaluation of the log-likelihood;
  * holdout log-likelihood: K=1 closed form, the no-observation closed form, dense
- * evaluation from the returned assignments, improvement under fold-in.
+ * evaluation from the returned assignments, improvement under fold-in; alias tables:
+ * two hand-worked tables, the mass every table must encode, the measure a grid of
+ * draws induces, chi-square of the alias E-step against the dense Eq. 1.
  * The realised sample path z itself has no printed reference in the paper:
  * "parity unpinned" beyond the distributional and invariant pins above.
  */
@@ -278,6 +280,105 @@ void orc_estep(int64_t D, const int64_t *doc_ptr, const int32_t *word_ids, int32
             if (out_p) out_p[t] = det.p_sparse;
             if (out_branch) out_branch[t] = (int8_t)det.branch;
             if (out_margin) out_margin[t] = det.margin;
+        }
+    }
+}
+
+/* ------------------------------------------------------------------ alias table (the other per-word structure)
+ * Sec. 3.2.3 weighs the alias table (Walker's method: O(1) per draw, O(K) sequential construction) against the
+ * W-ary tree for the dense term alpha * Bhat_v.  The paper does not say how its table was built; the reading
+ * taken here is the sweep construction, which is deterministic given the weights:
+ *   q_k = K p_k / sum_j p_j;  items with q_k <= 1 are light, the others heavy; both kinds are visited in index
+ *   order.  j = current heavy item, r = what is left of its weight (q_j at first).
+ *     while r > 1 and a light item i remains:  bucket i keeps i with probability q_i, else yields j;
+ *                                              r -= 1 - q_i;  next light
+ *     when r <= 1 and another heavy j' exists: bucket j keeps j with probability r, else yields j';
+ *                                              r = q_j' - (1 - r);  j = j'
+ *   the last heavy item's bucket is full (r = 1 up to rounding); a light item that finds every heavy one used up
+ *   (rounding only) is paired with the last heavy item.
+ * Every bucket then holds mass 1/K: bucket k yields k with probability prob[k] and alias[k] otherwise, so that
+ * P(k) = (prob[k] + sum over buckets b with alias[b] = k of (1 - prob[b])) / K = p_k / sum p.
+ * Arithmetic in binary64; prob is stored rounded to binary32. */
+void orc_alias_build(const float *p, int32_t K, float *prob, int32_t *alias) {
+    double total = 0.0;
+    for (int32_t k = 0; k < K; k++) total += (double)p[k];
+    const double scale = (double)K / total;
+    int32_t i = 0, j = 0, last_heavy = -1;           /* next light, current heavy */
+    while (j < K && !((double)p[j] * scale > 1.0)) j++;
+    double r = j < K ? (double)p[j] * scale : 0.0;
+    for (;;) {
+        while (i < K && (double)p[i] * scale > 1.0) i++;              /* next light item */
+        if (j >= K) break;                                            /* no heavy item (left) */
+        if (r > 1.0 && i < K) {
+            const double q = (double)p[i] * scale;
+            prob[i] = (float)q; alias[i] = j;
+            r -= 1.0 - q;
+            i++;
+        } else {
+            int32_t jn = j + 1;
+            while (jn < K && !((double)p[jn] * scale > 1.0)) jn++;    /* next heavy item */
+            last_heavy = j;
+            if (jn >= K || !(r <= 1.0)) { prob[j] = 1.0f; alias[j] = j; j = jn; if (jn >= K) break; r = (double)p[jn] * scale; continue; }
+            prob[j] = (float)(r < 0.0 ? 0.0 : r); alias[j] = jn;
+            r = (double)p[jn] * scale - (1.0 - r);
+            j = jn;
+        }
+    }
+    for (; i < K; i++) {                                              /* light items left over */
+        if ((double)p[i] * scale > 1.0) continue;
+        const double q = (double)p[i] * scale;
+        prob[i] = last_heavy >= 0 ? (float)q : 1.0f; alias[i] = last_heavy >= 0 ? last_heavy : i;
+    }
+}
+
+/* Walker's draw with the 24 random bits behind u (u = bits * 2^-24): bucket b = floor(u K), taken in integers;
+ * the bucket's own item if the fraction of u K lies below prob[b], its alias otherwise.  *margin (may be NULL):
+ * distance of u from the boundary prob[b] inside the bucket, in units of u. */
+int32_t orc_alias_draw(const float *prob, const int32_t *alias, int32_t K, uint32_t bits24, double *margin) {
+    const uint64_t prod = (uint64_t)bits24 * (uint64_t)K;
+    const int32_t b = (int32_t)(prod >> 24);
+    const float frac = (float)(prod & 0xffffffu) * (1.0f / 16777216.0f);
+    if (margin) *margin = fabs((double)frac - (double)prob[b]) / (double)K;
+    return frac < prob[b] ? b : alias[b];
+}
+
+/* Alg. 2 with the dense term drawn from alias tables (prob, alias: [V][K]); otherwise as orc_estep. */
+void orc_estep_alias(int64_t D, const int64_t *doc_ptr, const int32_t *word_ids, int32_t K, float alpha,
+                     const int64_t *cd_ptr, const int32_t *cd_topic, const int32_t *cd_count,
+                     const float *phi, const double *sum64, const float *prob, const int32_t *alias,
+                     uint64_t seed, uint32_t iter, int32_t *z_new, int8_t *out_branch, double *out_margin, int nthreads) {
+    if (nthreads < 1) nthreads = 1;
+#pragma omp parallel for schedule(dynamic, 16) num_threads(nthreads)
+    for (int64_t d = 0; d < D; d++) {
+        const int64_t a = cd_ptr[d]; const int32_t nnz = (int32_t)(cd_ptr[d + 1] - a);
+        const int32_t *topic = cd_topic + a, *count = cd_count + a;
+        for (int64_t t = doc_ptr[d]; t < doc_ptr[d + 1]; t++) {
+            const int32_t w = word_ids[t];
+            const float *phi_w = phi + (size_t)w * (size_t)K;
+            double u0, u1; orc_token_uniforms(seed, (uint64_t)t, iter, &u0, &u1);
+            const double Q = (double)alpha * sum64[w];
+            double S = 0.0;
+            for (int32_t j = 0; j < nnz; j++) S += (double)count[j] * (double)phi_w[topic[j]];
+            const double thr = S / (S + Q);
+            double margin = fabs(u0 - thr); int32_t result; int branch;
+            if (u0 < thr) {                                           /* problem 1, as in orc_sample */
+                branch = 1;
+                double x = u1 * S, run = 0.0, prev = 0.0; int32_t j = 0;
+                for (; j < nnz; j++) { prev = run; run += (double)count[j] * (double)phi_w[topic[j]]; if (run >= x) break; }
+                if (j >= nnz) j = nnz - 1;
+                result = topic[j];
+                const double m = fmin(fabs(x - prev), fabs(run - x)) / S;
+                if (m < margin) margin = m;
+            } else {                                                  /* problem 2 from the word's alias table */
+                branch = 2;
+                double m;
+                result = orc_alias_draw(prob + (size_t)w * (size_t)K, alias + (size_t)w * (size_t)K, K,
+                                        (uint32_t)(u1 * 16777216.0), &m);
+                if (m < margin) margin = m;
+            }
+            z_new[t] = result;
+            if (out_branch) out_branch[t] = (int8_t)branch;
+            if (out_margin) out_margin[t] = margin;
         }
     }
 }
