@@ -85,7 +85,12 @@ typedef struct saber_options {
                                    word order (the layout before Sec. 3.1.3: the row of A is fetched once per document,
                                    Bhat is gathered from global memory; every word then keeps a dense row and
                                    stream_workers must be 0); bit 1 rebuilds A by a radix sort of all (document, topic)
-                                   pairs instead of the segmented count of Sec. 3.3.  Results are the same. */
+                                   pairs instead of the segmented count of Sec. 3.3.  Results are the same.
+                                   Bit 2 draws the dense term from per-word alias tables instead of the prefix-sum tree
+                                   (the alternative Sec. 3.2.3 weighs): every word keeps a dense row, the tables (8 K
+                                   bytes per word) are rebuilt after every M-step, K <= 13,500, not with bit 0.  This
+                                   variant maps the uniform draw to another topic than the tree does: its assignments
+                                   differ from the default path's and follow the same distribution. */
     int32_t device_mem_limit_mb;/* device memory the automatic choice above may plan with, in MB; 0 (default): what
                                    hipMemGetInfo reports as free */
     int32_t quarter_row_entries;/* rows of A of at most this many entries (default and at most 64) are sampled four at a time,

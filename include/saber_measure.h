@@ -23,6 +23,14 @@ extern "C" {
 int saber_alias_build_probe(saber_ctx *ctx, const int32_t *words, int32_t m, float *prob, int32_t *alias,
                             double *ms_build, int32_t *rows_built);
 
+/* The alias tables of the variant saber_options.ablation bit 2 (Sec. 3.2.3: the alias table as the per-word structure
+ * for the dense term instead of the tree), for the m words listed (host array): prob[m][K] and alias[m][K] (host):
+ * bucket k yields topic k with probability prob, else topic alias; a dense-branch token with uniform u1 takes bucket
+ * floor(u1 K) and keeps the bucket's own topic if the fraction of u1 K is below prob.  The tables are rebuilt after
+ * every M-step by one workgroup per word (prefix sums and binary searches instead of Vose's pairing chain).
+ * Errors: ESTATE (the context was not created with ablation bit 2), EINVAL, ENOMEM, EDEVICE. */
+int saber_get_alias(saber_ctx *ctx, const int32_t *words, int32_t m, float *prob, int32_t *alias);
+
 /* Measurement aid, independent of any context: copies `bytes` bytes device-to-device `reps` times with a
  * plain streaming kernel and reports read+write bandwidth in GB/s (the achievable-HBM yardstick, and the
  * kernel the profiler's FETCH_SIZE / WRITE_SIZE counters are calibrated against). */

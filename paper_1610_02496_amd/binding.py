@@ -20,7 +20,7 @@ _STATUS = {0: "SABER_OK", -1: "SABER_EINVAL", -2: "SABER_ENOMEM", -3: "SABER_EDE
 EXPORTS = ["saber_set_hooks", "saber_options_default", "saber_init_ex", "saber_init", "saber_iterate", "saber_counts_nnz",
            "saber_counts", "saber_loglik", "saber_loglik_static", "saber_holdout_loglik", "saber_free", "saber_last_error", "saber_get_z", "saber_set_z",
            "saber_get_iteration", "saber_token_probs", "saber_get_phi", "saber_get_stats", "saber_reset_stats",
-           "saber_get_stream", "saber_bandwidth_probe", "saber_alias_build_probe"]
+           "saber_get_stream", "saber_bandwidth_probe", "saber_alias_build_probe", "saber_get_alias"]
 
 
 class SaberError(RuntimeError):
@@ -93,6 +93,7 @@ def load_library():
         "saber_get_stream": (ctypes.c_int, [vp, vp]),
         "saber_bandwidth_probe": (ctypes.c_int, [i64, i32, vp]),
         "saber_alias_build_probe": (ctypes.c_int, [vp, vp, i32, vp, vp, vp, vp]),
+        "saber_get_alias": (ctypes.c_int, [vp, vp, i32, vp, vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -267,6 +268,13 @@ class Saber:
         _check(load_library().saber_alias_build_probe(self._h, _ptr(words) if m else None, m, _ptr(prob), _ptr(alias),
                                                       ctypes.addressof(ms), ctypes.addressof(rows)))
         return ms.value, rows.value, prob[:m], alias[:m]
+
+    def get_alias(self, words):
+        """Alias tables (prob[m][K], alias[m][K]) of the listed words; needs ablation bit 2."""
+        words = np.ascontiguousarray(words, dtype=np.int32)
+        prob = np.zeros((words.size, self.K), dtype=np.float32); alias = np.zeros((words.size, self.K), dtype=np.int32)
+        _check(load_library().saber_get_alias(self._h, _ptr(words), words.size, _ptr(prob), _ptr(alias)))
+        return prob, alias
 
     def get_z(self):
         z = np.zeros(self.T, dtype=np.int32)

@@ -195,6 +195,7 @@ struct saber_ctx {
     void *sort_tmp = nullptr;
     size_t sort_tmp_bytes = 0;
     unsigned sort_end_bit = 0;
+    uint2 *alias_table = nullptr;     // [V_dense][K] {prob bits, alias} when the dense term is drawn from alias tables
 };
 
 static inline int grid_for(int64_t n, int block, int cap = 65535 * 16) {
@@ -240,7 +241,7 @@ extern "C" void saber_free(saber_ctx *c) {
     }
     release(c->doc_blocks); release(c->ne_doc);
     release(c->word_ids_d); release(c->word_row_d); release(c->sort_keys); release(c->sort_keys_out);
-    release(c->sort_rank); release(c->sort_tmp);
+    release(c->sort_rank); release(c->sort_tmp); release(c->alias_table);
     if (c->h_tok_t) (void)hipHostFree(c->h_tok_t);
     if (c->stream && c->own_stream) (void)hipStreamDestroy(c->stream);
     delete c;
@@ -277,6 +278,7 @@ static EStepParams make_params(saber_ctx *c, const Chunk &ch, int slot = -1) {
     p.z = zv.z; p.z_rel = ch.t0 - zv.first;
     p.base = c->phi + (size_t)c->V_dense * (size_t)c->Kpad;
     p.wrec = c->wrec; p.lw_ent = c->lw_ent; p.lw_phi = c->lw_phi; p.z_wm = c->z_wm;
+    p.alias_table = c->alias_table;
     p.t_base = ch.t0; p.K = c->K; p.Kpad = c->Kpad; p.n3 = c->n3; p.n3pad = c->n3pad;
     p.topic_bits = c->topic_bits; p.topic_mask = c->topic_mask; p.alpha = c->alpha;
     p.seed_lo = (uint32_t)c->seed; p.seed_hi = (uint32_t)(c->seed >> 32); p.iter = c->iter;
@@ -518,12 +520,22 @@ static int launch_topic_totals(saber_ctx *c) {
     return SABER_OK;
 }
 
+// LDS of one workgroup of the alias-table build: K + 1 prefix sums (binary64) and K item numbers
+static size_t alias_lds_bytes(int K) { return ((size_t)K + 1) * sizeof(double) + (size_t)K * sizeof(uint32_t); }
+
 static int launch_phi(saber_ctx *c) {
     hipLaunchKernelGGL(denominators_kernel, dim3(grid_for(c->K, 256)), dim3(256), 0, c->stream, c->ck, c->denom, c->K, c->vbeta);
     HIP_TRY(hipGetLastError());
     hipLaunchKernelGGL(phi_tree_kernel, dim3((unsigned)(c->V_dense + 1)), dim3(256), 0, c->stream, c->cwk, c->denom, c->phi,
                        c->l3, c->l3_64, c->sumphi, c->row_word, c->K, c->Kpad, c->n3, c->n3pad, c->beta, 1);
     HIP_TRY(hipGetLastError());
+    if (c->alias_table && c->V_dense > 0) {   // measurement variant: an alias table per word on top of the tree level
+        const size_t lds = alias_lds_bytes(c->K);
+        if (lds > 64 * 1024)
+            HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(alias_sweep_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        hipLaunchKernelGGL(alias_sweep_kernel, dim3((unsigned)c->V_dense), dim3(kAliasThreads), lds, c->stream, c->phi, c->K, c->Kpad, c->alias_table);
+        HIP_TRY(hipGetLastError());
+    }
     return SABER_OK;
 }
 
@@ -921,6 +933,8 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
         if (T) HIP_TRY(hipMemcpy(c->word_ids_d, word_ids, sizeof(int32_t) * (size_t)T, hipMemcpyHostToDevice));
         HIP_TRY(hipMemcpy(c->word_row_d, c->h_word_row.data(), sizeof(int32_t) * (size_t)V, hipMemcpyHostToDevice));
     }
+    if (c->opt.ablation & 4)
+        SABER_TRY(dev_alloc(c->hooks, &c->alias_table, (size_t)std::max(c->V_dense, 1) * (size_t)K));
     if (c->opt.ablation & 2) {
         unsigned dbits = 1; while (dbits < 32 && (1ll << dbits) < std::max<int64_t>(D, 1)) dbits++;
         c->sort_end_bit = c->topic_bits + dbits;
@@ -1024,9 +1038,12 @@ static int create_ctx(saber_ctx **out, const int64_t *doc_ptr, const int32_t *wo
     if (opt.stream_workers < -1 || opt.stream_workers > kMaxSlots)
         return fail(SABER_EINVAL, "saber_init: stream_workers must be in [-1,%d]", kMaxSlots);
     if (parent) { opt.stream_workers = 0; opt.ablation = 0; }   // held-out documents are few: always resident, regular kernels
-    if (opt.ablation < 0 || opt.ablation > 3) return fail(SABER_EINVAL, "saber_init: ablation must be in [0,3]");
+    if (opt.ablation < 0 || opt.ablation > 7 || (opt.ablation & 5) == 5)
+        return fail(SABER_EINVAL, "saber_init: ablation must be in [0,7], and document order (bit 0) excludes alias tables (bit 2)");
     if (opt.ablation && opt.stream_workers) return fail(SABER_EINVAL, "saber_init: the ablation variants need stream_workers = 0");
-    if (opt.ablation & 1) opt.light_word_tokens = -1;   // document order gathers Bhat from dense rows
+    if (opt.ablation & 5) opt.light_word_tokens = -1;   // document order gathers Bhat from dense rows; alias tables are built from them
+    if ((opt.ablation & 4) && alias_lds_bytes(K) > 159 * 1024)
+        return fail(SABER_ERANGE, "saber_init: the alias-table variant needs 12 K bytes of LDS per workgroup, K = %d is beyond 13,500", K);
     if (opt.light_word_tokens == 0) opt.light_word_tokens = std::max(1, K / 2);   // < 0 keeps every word dense
     // automatic: chunks of at most 128 M tokens.  The sampling pass of a chunk reads every row of A of the chunk once
     // per word of the document; at about 0.4 non-zeros per token these rows (4 bytes per entry) then fit the 256 MB
@@ -1635,6 +1652,25 @@ extern "C" int saber_alias_build_probe(saber_ctx *c, const int32_t *words, int32
     cleanup();
     if (e != hipSuccess) return fail(SABER_EDEVICE, "saber_alias_build_probe: %s", hipGetErrorString(e));
     *ms_build = (double)ms;
+    return SABER_OK;
+}
+
+extern "C" int saber_get_alias(saber_ctx *c, const int32_t *words, int32_t m, float *prob, int32_t *alias) {
+    if (!c || m < 0 || (m > 0 && (!words || !prob || !alias))) return fail(SABER_EINVAL, "saber_get_alias: bad argument");
+    if (!c->alias_table) return fail(SABER_ESTATE, "saber_get_alias: the context keeps no alias tables (saber_options.ablation bit 2)");
+    try {
+        std::vector<uint2> rowbuf((size_t)c->K);
+        for (int32_t i = 0; i < m; i++) {
+            if (words[i] < 0 || words[i] >= c->V) return fail(SABER_EINVAL, "saber_get_alias: word %d is outside [0,%d)", words[i], c->V);
+            const int32_t row = c->h_word_row[(size_t)words[i]];
+            if (row < 0) return fail(SABER_ESTATE, "saber_get_alias: word %d keeps a sparse row", words[i]);
+            HIP_TRY(hipMemcpy(rowbuf.data(), c->alias_table + (size_t)row * (size_t)c->K, sizeof(uint2) * (size_t)c->K, hipMemcpyDeviceToHost));
+            for (int32_t k = 0; k < c->K; k++) {   // format conversion only
+                memcpy(&prob[(size_t)i * (size_t)c->K + (size_t)k], &rowbuf[(size_t)k].x, sizeof(float));
+                alias[(size_t)i * (size_t)c->K + (size_t)k] = (int32_t)rowbuf[(size_t)k].y;
+            }
+        }
+    } catch (const std::bad_alloc &) { return fail(SABER_ENOMEM, "saber_get_alias: out of host memory"); }
     return SABER_OK;
 }
 

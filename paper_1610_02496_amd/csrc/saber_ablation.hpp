@@ -235,6 +235,92 @@ __global__ void __launch_bounds__(256) alias_build_kernel(const float *__restric
     while (nl > 0) { const int l = stack[(size_t)(K - nl) * n + r]; nl--; prob[(size_t)l * n + r] = 1.f; alias[(size_t)l * n + r] = l; }
 }
 
+// ---- alias tables built by a whole workgroup, and sampled from (saber_options.ablation bit 2) ----
+// The sweep construction visits light items (K p_k / sum p <= 1) and heavy items in index order: the current heavy
+// item fills light buckets until less than one bucket of it is left, then takes its own bucket and the next heavy
+// item makes up the shortfall.  Written with prefix sums it needs no chain: with l_a = what the first a light items
+// lack of a full bucket and h_b = what the first b heavy items have beyond one,
+//   light item a is filled by the first heavy item b with h_(b+1) > l_a;
+//   heavy item b keeps 1 + h_(b+1) - l_a of its own bucket, a = the first a with l_a >= h_(b+1), and hands the
+//   rest to heavy item b + 1 (the last heavy item keeps a full bucket).
+// So every item finds its partner by a binary search in the other kind's prefix sums, all items at once: the
+// "vectorised" construction, against the serial pairing chain of Vose's algorithm above.
+// One workgroup of 1,024 threads per row (the LDS it needs leaves room for one workgroup per CU); thread t owns the
+// items [t c, (t+1) c), c = ceil(K / 1024), so that both
+// kinds keep their index order.  LDS: K + 1 binary64 prefix sums (l_0..l_nL, then h_1..h_nH) and K item numbers
+// (light ones first).  table[row][k] = {prob as binary32 bits, alias}: bucket k yields k with probability prob.
+constexpr int kAliasThreads = 1024, kAliasWaves = kAliasThreads / kWave;
+__device__ __forceinline__ void block_excl_scan2(double &a, double &b, uint32_t &n, double (*sd)[kAliasWaves + 1], uint32_t *su) {
+    // exclusive scan of (a, b, n) over the workgroup's threads; totals come back in sd[0..1][kAliasWaves], su[kAliasWaves]
+    const int lane = lane_id(), wave = threadIdx.x / kWave;
+    const double ia = wave_incl_scan(a), ib = wave_incl_scan(b);
+    const uint32_t in = wave_incl_scan(n);
+    if (lane == kWave - 1) { sd[0][wave] = ia; sd[1][wave] = ib; su[wave] = in; }
+    __syncthreads();
+    double oa = 0.0, ob = 0.0, ta = 0.0, tb = 0.0; uint32_t on = 0u, tn = 0u;
+    for (int w = 0; w < kAliasWaves; w++) {
+        if (w < wave) { oa += sd[0][w]; ob += sd[1][w]; on += su[w]; }
+        ta += sd[0][w]; tb += sd[1][w]; tn += su[w];
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) { sd[0][kAliasWaves] = ta; sd[1][kAliasWaves] = tb; su[kAliasWaves] = tn; }
+    __syncthreads();
+    a = oa + ia - a; b = ob + ib - b; n = on + in - n;
+}
+
+__global__ void __launch_bounds__(kAliasThreads) alias_sweep_kernel(const float *__restrict__ phi, int K, int Kpad, uint2 *table) {
+    extern __shared__ double lds_pre[];
+    __shared__ double sd[2][kAliasWaves + 1];
+    __shared__ uint32_t su[kAliasWaves + 1];
+    double *pre = lds_pre;
+    uint32_t *idx = reinterpret_cast<uint32_t *>(lds_pre + K + 1);
+    const float *__restrict__ row = phi + (size_t)blockIdx.x * (size_t)Kpad;
+    uint2 *__restrict__ out = table + (size_t)blockIdx.x * (size_t)K;
+    const int tid = (int)threadIdx.x, c = (K + kAliasThreads - 1) / kAliasThreads;
+    const int k0 = min(K, tid * c), k1 = min(K, k0 + c);
+    double part = 0.0, zero = 0.0; uint32_t none = 0u;
+    for (int k = k0; k < k1; k++) part += (double)row[k];
+    block_excl_scan2(part, zero, none, sd, su);
+    const double scale = (double)K / sd[0][kAliasWaves];
+    __syncthreads();                                   // sd is reused below
+    double lack = 0.0, extra = 0.0; uint32_t nlight = 0u;
+    for (int k = k0; k < k1; k++) {
+        const double q = (double)row[k] * scale;
+        if (q > 1.0) extra += q - 1.0; else { lack += 1.0 - q; nlight++; }
+    }
+    block_excl_scan2(lack, extra, nlight, sd, su);     // now: what the items before this thread's lack / have beyond
+    const int nL = (int)su[kAliasWaves], nH = K - nL;
+    int a = (int)nlight, b = k0 - (int)nlight;
+    for (int k = k0; k < k1; k++) {
+        const double q = (double)row[k] * scale;
+        if (q > 1.0) { extra += q - 1.0; idx[nL + b] = (uint32_t)k; pre[nL + 1 + b] = extra; b++; }
+        else { idx[a] = (uint32_t)k; pre[a] = lack; lack += 1.0 - q; a++; }
+    }
+    if (tid == 0) pre[nL] = sd[0][kAliasWaves];
+    __syncthreads();
+    for (int i = tid; i < nL; i += kAliasThreads) {              // light items
+        const int k = (int)idx[i];
+        const double q = (double)row[k] * scale, l = pre[i];
+        int lo = 0, hi = nH;
+        while (lo < hi) { const int mid = (lo + hi) >> 1; if (pre[nL + 1 + mid] > l) hi = mid; else lo = mid + 1; }
+        if (lo >= nH) lo = nH - 1;                     // rounding used up every heavy item: the last one
+        out[k] = nH > 0 ? make_uint2(__float_as_uint((float)q), idx[nL + lo]) : make_uint2(__float_as_uint(1.0f), (uint32_t)k);
+    }
+    for (int i = tid; i < nH; i += kAliasThreads) {              // heavy items
+        const int k = (int)idx[nL + i];
+        const double h = pre[nL + 1 + i];
+        int lo = 0, hi = nL + 1;
+        while (lo < hi) { const int mid = (lo + hi) >> 1; if (pre[mid] >= h) hi = mid; else lo = mid + 1; }
+        if (lo <= nL && i + 1 < nH) {
+            double r = 1.0 + h - pre[lo];
+            r = r < 0.0 ? 0.0 : (r > 1.0 ? 1.0 : r);
+            out[k] = make_uint2(__float_as_uint((float)r), idx[nL + i + 1]);
+        } else {
+            out[k] = make_uint2(__float_as_uint(1.0f), (uint32_t)k);
+        }
+    }
+}
+
 // the tables of the rows listed, as [m][K]
 __global__ void alias_export_kernel(const int32_t *rows, int m, int nrows, int K, const float *prob, const int32_t *alias,
                                     float *out_prob, int32_t *out_alias) {

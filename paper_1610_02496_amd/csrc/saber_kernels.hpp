@@ -198,6 +198,8 @@ struct EStepParams {
     const uint32_t *lw_ent;     // packed (topic, count) rows of B for the light words, ascending topic
     const float *lw_phi;        // Bhat value of every such entry
     void *z_wm;                 // [T] new assignments in word-major order (light words first): input of CountByVZ
+    const uint2 *alias_table;   // null, or [dense rows][K] {prob bits, alias}: the dense term is then drawn from these
+                                // alias tables instead of the prefix-sum tree (measurement variant, Sec. 3.2.3)
     float *out_S;               // probs mode: S per token of the chunk, indexed by the token's position in the chunk
     float *out_Q;               // probs mode: Q likewise
     double *out_ll;             // loglik mode: one partial sum per tile
@@ -500,7 +502,11 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
             uint32_t zero = 0u;
             asm volatile("" : "+s"(zero));   // (keeps the compiler from running the set-up below ahead of this test)
             const int npass = (nruns + NG - 1) / NG;
-            const uint32_t gi = (uint32_t)lane >> LG, li = (uint32_t)lane & (uint32_t)(G - 1), li16 = li << 4;
+            // (an opaque copy of the lane number: values derived from it are formed here, per class, instead of once
+            // per kernel and then held in registers the kernel does not have to spare)
+            uint32_t ln = (uint32_t)lane;
+            asm volatile("" : "+v"(ln));
+            const uint32_t gi = ln >> LG, li = ln & (uint32_t)(G - 1), li16 = li << 4;
             const uint32_t rank = bits_up_to_lane(cm);          // pieces of the class that start at this lane or before
             // slots: a piece's first lane writes to slot rank - 1; all other lanes write to lane 63, which is a slot
             // only if every lane starts a piece
@@ -728,8 +734,24 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
         if (MODE == MODE_SAMPLE && dense_mask) {
             // problem 2 for the tokens whose coin chose it: DPP row g (16 lanes) serves the g-th of up to four tokens
             if (lane == 0) atomicAdd(&wg_dense, (unsigned int)__builtin_popcountll(dense_mask));   // statistic only
+            if (!LIGHT && p.alias_table != nullptr) {
+                // Walker's alias method for all these tokens at once: the bucket is floor(u1 K), taken in integers from
+                // the 24 random bits behind u1; the bucket's own topic if the fraction of u1 K lies below its
+                // probability, its alias otherwise
+                const uint32_t bits24 = (uint32_t)(u1 * 16777216.0f);
+                const uint32_t lo = bits24 * (uint32_t)K, hi = __umulhi(bits24, (uint32_t)K);
+                const uint32_t bucket = (hi << 8) | (lo >> 24);
+                const float frac = (float)(lo & 0xffffffu) * (1.0f / 16777216.0f);
+                if (__builtin_amdgcn_inverse_ballot_w64(dense_mask)) {
+                    const uint2 e = p.alias_table[(size_t)tile.row * (size_t)K + bucket];
+                    my_z = frac < __uint_as_float(e.x) ? bucket : e.y;
+                }
+                dense_mask = 0ull;
+            }
             const float xd = u1 * sum_w;
-            const int g = lane >> 4, li = lane & 15;
+            int ln = lane;
+            asm volatile("" : "+v"(ln));               // (as above: lane-derived values formed where they are used)
+            const int g = ln >> 4, li = ln & 15;
             while (dense_mask) {
                 int tl[4];
 #pragma unroll

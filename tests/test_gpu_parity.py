@@ -393,6 +393,78 @@ def test_ablation_variants_match_oracle_and_default_path(ablation):
         pk.Saber(dp, w, 5, 7, 0.3, 0.01, 11, ablation=ablation, stream_workers=2)
 
 
+@pytest.mark.parametrize("K,ablation", [(300, 4), (64, 4), (1000, 6), (5000, 4)])
+def test_alias_variant_matches_the_oracles_alias_mode(K, ablation):
+    """The dense term drawn from per-word alias tables (Sec. 3.2.3's alternative to the tree): the tables, built by
+    one workgroup per word from prefix sums, against the oracle's sweep construction, and the E-step against the
+    oracle's alias mode, which draws from the oracle's own tables.  The sparse branch and every count are those of
+    the default path."""
+    c = corpusgen.tiny(80 + K % 9, 300, 500, 20, 70.0)
+    alpha = 50.0 / K
+    g, o = make_pair(c, K, alpha, 0.01, 31, ablation=ablation)
+    assert np.array_equal(g.get_z(), o.z)
+    assert_counts_equal(g, o)
+    words = np.arange(c.spec.V, dtype=np.int32)
+    for step in range(2):
+        prob_o, alias_o = o.alias_tables()
+        prob, alias = g.get_alias(words)
+        # the same construction in another order of additions: probabilities within a binary32 ulp, partners equal
+        # wherever a bucket hands over a share that matters
+        assert np.all(np.abs(prob.astype(np.float64) - prob_o) <= np.spacing(np.maximum(prob_o, np.float32(1e-30))).astype(np.float64))
+        assert (prob != prob_o).mean() < 1e-3
+        share = 1.0 - prob_o.astype(np.float64) > 1e-6
+        assert np.array_equal(alias[share], alias_o[share])
+        for v in (0, 1, c.spec.V - 1):
+            want = o.phi[v].astype(np.float64) / o.phi[v].astype(np.float64).sum()
+            assert np.abs(oracle.alias_mass(prob[v], alias[v]) - want).max() < 1e-7
+        tok = np.arange(o.T, dtype=np.int64)
+        S, Q, p = g.token_probs(tok)
+        _, S_ref, p_ref, _, _ = o.estep_detail(nthreads=4)
+        assert np.allclose(S, S_ref, rtol=1e-5, atol=0) and np.allclose(p, p_ref, rtol=1e-5, atol=0)
+        z_ref, br, margin = o.estep_alias(prob_o, alias_o, nthreads=4)
+        assert (br == 1).any() and (br == 2).any()
+        g.iterate(1)
+        z = g.get_z()
+        bad = np.nonzero(z != z_ref)[0]
+        assert bad.size <= 1e-3 * o.T and np.all(margin[bad] < 1e-5)
+        o.set_z(z, it=g.get_iteration())
+        assert_counts_equal(g, o)
+        assert_phi_equal(g, o)
+    # the same chain with the tree: other assignments (another map from the uniform draw to the topic) ...
+    t = saber().Saber(c.doc_ptr, c.word_ids, c.spec.V, K, alpha, 0.01, 31)
+    t.iterate(1)
+    o2 = oracle.Model(c.doc_ptr, c.word_ids, c.spec.V, K, alpha, 0.01, 31)
+    a = saber().Saber(c.doc_ptr, c.word_ids, c.spec.V, K, alpha, 0.01, 31, ablation=ablation)
+    a.iterate(1)
+    _, _, _, br_tree, _ = o2.estep_detail(nthreads=4)
+    za, zt = a.get_z(), t.get_z()
+    assert np.array_equal(za[br_tree == 1], zt[br_tree == 1])        # ... on the dense branch only
+    assert (za[br_tree == 2] != zt[br_tree == 2]).any()
+    # ... with the same distribution: topic totals of the dense-branch tokens, alias against tree, chi-square on the
+    # topics that hold enough of them
+    ha = np.bincount(za[br_tree == 2], minlength=K).astype(np.float64); ht = np.bincount(zt[br_tree == 2], minlength=K).astype(np.float64)
+    if K <= 300:
+        big = (ha + ht) >= 20
+        stat = (((ha - ht) ** 2) / (ha + ht))[big].sum()
+        from scipy.stats import chi2 as chi2_dist
+        assert stat < chi2_dist.ppf(1 - 1e-4, int(big.sum()))
+
+
+def test_alias_variant_argument_checks():
+    pk = saber()
+    c = corpusgen.tiny(90, 30, 60, 5, 20.0)
+    with pytest.raises(pk.SaberError) as e:
+        pk.Saber(c.doc_ptr, c.word_ids, c.spec.V, 50, 0.5, 0.01, 1, ablation=5)
+    assert e.value.code == pk.binding.SABER_EINVAL
+    with pytest.raises(pk.SaberError) as e:
+        pk.Saber(c.doc_ptr, c.word_ids, c.spec.V, 14000, 0.5, 0.01, 1, ablation=4)
+    assert e.value.code == pk.binding.SABER_ERANGE
+    g = pk.Saber(c.doc_ptr, c.word_ids, c.spec.V, 50, 0.5, 0.01, 1)
+    with pytest.raises(pk.SaberError) as e:
+        g.get_alias([0])
+    assert e.value.code == pk.binding.SABER_ESTATE
+
+
 def test_alias_tables_encode_the_word_distributions():
     """The alias-table build (measurement aid for Sec. 3.2.3): any valid table is accepted, what is checked is the
     distribution it encodes, bucket by bucket in binary64, against the oracle's Bhat rows: p_k = Bhat_vk / sum."""
