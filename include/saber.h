@@ -50,12 +50,14 @@ typedef enum saber_status {
 
 /* Tunables; none of them changes any result.  Zero / negative means "library default". */
 typedef struct saber_options {
-    int32_t n_chunks;       /* document chunks the corpus is cut into (Sec. 3.1.2); 0 (default): one chunk per
-                               128 M tokens, so that the rows of A a chunk's sampling pass re-reads stay in the
-                               256 MB Infinity Cache; always at least one chunk per 2^30 tokens */
+    int32_t n_chunks;       /* document chunks the corpus is cut into (Sec. 3.1.2); 0 (default): chunks of about
+                               80 M tokens (T / 80 M rounded to the nearest whole number, at least 1), so that the rows of A
+                               a chunk's sampling pass re-reads stay in the 256 MB Infinity Cache; always at least one
+                               chunk per 2^30 tokens */
     int32_t block_threads;  /* threads per workgroup of the sampling kernel (multiple of 64 up to 1024);
                                default: the size that lets a CU hold the most wavefronts given the LDS the Bhat row takes */
-    int32_t tile_tokens;    /* most tokens of one word handled by one workgroup; default 8192 */
+    int32_t tile_tokens;    /* most tokens of one word handled by one workgroup; default 0: a 2560th of a chunk's tokens,
+                               not below 8,192 and not above 32,768 */
     int32_t stage_phi;      /* 1: keep the word's Bhat row in LDS when it fits (up to 150 KB: K <= 37,800), 0: always
                                gather from global; default 1 */
     int32_t profile;        /* 1: time every kernel group with HIP events (see saber_get_stats); default 0 */

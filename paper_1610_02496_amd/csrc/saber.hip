@@ -119,6 +119,7 @@ struct saber_ctx {
     uint32_t iter = 0, topic_bits = 0, topic_mask = 0;
     bool z16 = false, staged = false, b16 = false;
     saber_options opt{};
+    int32_t tile_tokens_asked = 0;    // the caller's tile_tokens (0: automatic), before the default was filled in
     int64_t max_doc_len = 0;
     hipStream_t stream = nullptr;
     // device arrays
@@ -214,7 +215,7 @@ extern "C" int saber_set_hooks(void *(*alloc)(size_t), void (*dealloc)(void *), 
 extern "C" void saber_options_default(saber_options *opt) {
     if (!opt) return;
     memset(opt, 0, sizeof(*opt));
-    opt->n_chunks = 0; opt->block_threads = 0; opt->tile_tokens = 8192; opt->stage_phi = 1; opt->profile = 0;
+    opt->n_chunks = 0; opt->block_threads = 0; opt->tile_tokens = 0; opt->stage_phi = 1; opt->profile = 0;
     opt->quarter_row_entries = 64; opt->half_row_entries = 128;
     opt->long_doc_tokens = 512; opt->dz_lds_entries = 2048; opt->stage_min_tokens = 0; opt->light_block_threads = 0; opt->light_word_tokens = 0;
 }
@@ -1045,10 +1046,12 @@ static int create_ctx(saber_ctx **out, const int64_t *doc_ptr, const int32_t *wo
     if ((opt.ablation & 4) && alias_lds_bytes(K) > 159 * 1024)
         return fail(SABER_ERANGE, "saber_init: the alias-table variant needs 12 K bytes of LDS per workgroup, K = %d is beyond 13,500", K);
     if (opt.light_word_tokens == 0) opt.light_word_tokens = std::max(1, K / 2);   // < 0 keeps every word dense
-    // automatic: chunks of at most 128 M tokens.  The sampling pass of a chunk reads every row of A of the chunk once
-    // per word of the document; at about 0.4 non-zeros per token these rows (4 bytes per entry) then fit the 256 MB
-    // Infinity Cache, and a corpus of several hundred million tokens samples 20 % faster than in one chunk
-    if (opt.n_chunks <= 0) opt.n_chunks = (int32_t)std::max<int64_t>(1, (T + (128ll << 20) - 1) / (128ll << 20));
+    // automatic: chunks of about 80 M tokens (T / 80 M, rounded to the nearest whole number).  The sampling pass of a
+    // chunk reads every row of A of the chunk once per word of the document; at 0.4 to 0.7 non-zeros per token these rows
+    // (4 bytes per entry) then fit the 256 MB Infinity Cache, and a corpus of several hundred million tokens samples
+    // 20 % faster than in one chunk.  (Every chunk stages every word's Bhat row again: a 100 M-token corpus is fastest
+    // in one chunk, and below 60 M tokens per chunk a large one slows down again.)
+    if (opt.n_chunks <= 0) opt.n_chunks = (int32_t)std::max<int64_t>(1, (T + (40ll << 20)) / (80ll << 20));
     if (opt.n_chunks > 65536) return fail(SABER_EINVAL, "saber_init: n_chunks too large");
     if (opt.quarter_row_entries > 64 || opt.half_row_entries > 128)
         return fail(SABER_EINVAL, "saber_init: quarter_row_entries must not exceed 64 and half_row_entries 128");
@@ -1056,6 +1059,15 @@ static int create_ctx(saber_ctx **out, const int64_t *doc_ptr, const int32_t *wo
     // token positions inside a chunk are 32-bit: keep every chunk below 2^30 tokens (documents are far shorter)
     opt.n_chunks = (int32_t)std::max<int64_t>(opt.n_chunks, (T >> 30) + 1);
     if ((int64_t)opt.n_chunks > std::max<int64_t>(D, 1)) opt.n_chunks = (int32_t)std::max<int64_t>(D, 1);
+    // automatic tile size: a heavy word's Bhat row is staged once per tile, so larger tiles stage less; but a tile is
+    // the work of one workgroup, and with about a thousand workgroups in flight a tile of chunk / 2560 tokens takes 40 %
+    // of the chunk's pass (heavy tiles are launched first; at chunk / 1500 the pass waits for them: + 5 to 20 %).
+    // Between 8,192 and 32,768 tokens.
+    const int32_t tile_tokens_asked = opt.tile_tokens;
+    if (opt.tile_tokens <= 0) {
+        const int64_t per_chunk = T / std::max(1, opt.n_chunks);
+        opt.tile_tokens = (int32_t)std::min<int64_t>(32768, std::max<int64_t>(8192, (per_chunk / 2560) & ~255ll));
+    }
 
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return fail(SABER_EDEVICE, "saber_init: no HIP device available");
@@ -1065,7 +1077,7 @@ static int create_ctx(saber_ctx **out, const int64_t *doc_ptr, const int32_t *wo
     c->hooks = parent ? parent->hooks : g_hooks;
     if (hipGetDevice(&c->device) != hipSuccess) { delete c; return fail(SABER_EDEVICE, "saber_init: hipGetDevice failed"); }
     { const int rc0 = static_scratch_init(c->device); if (rc0 != SABER_OK) { delete c; return rc0; } }
-    c->D = D; c->T = T; c->V = V; c->K = K; c->alpha = alpha; c->beta = beta; c->seed = seed; c->opt = opt;
+    c->D = D; c->T = T; c->V = V; c->K = K; c->alpha = alpha; c->beta = beta; c->seed = seed; c->opt = opt; c->tile_tokens_asked = tile_tokens_asked;
     c->parent = parent; c->no_state = no_state;
     c->n_slots = std::max(0, opt.stream_workers);
     c->Kpad = (K + 63) / 64 * 64;
@@ -1412,7 +1424,7 @@ extern "C" int saber_holdout_loglik(saber_ctx *m, const int64_t *doc_ptr, const 
             optr[(size_t)d + 1] = (int64_t)ow.size(); sptr[(size_t)d + 1] = (int64_t)sw.size();
         }
         saber_options opt = m->opt;
-        opt.profile = 0; opt.n_chunks = 1;
+        opt.profile = 0; opt.n_chunks = 1; opt.tile_tokens = m->tile_tokens_asked;   // (0: sized for these documents)
         rc = create_ctx(&obs, optr.data(), ow.data(), D, m->V, m->K, m->alpha, m->beta, seed, &opt, m, false);
         if (rc == SABER_OK && z_init) rc = saber_set_z(obs, z_init, 0);
         if (rc == SABER_OK) rc = foldin_iterate(obs, n_foldin);

@@ -284,6 +284,53 @@ __device__ __forceinline__ uint32_t dense_query4(const float *phi_row, int phi_l
     return (uint32_t)min(k, K - 1);
 }
 
+// How many of the 16 lanes of this lane's DPP row satisfy pred (row_shift = 16 * row): one compare into a
+// wave-wide mask, the row's 16 bits of it, a bit count.
+__device__ __forceinline__ uint32_t row16_count(bool pred, uint32_t row_shift) {
+    const unsigned long long m = __builtin_amdgcn_ballot_w64(pred);
+    return (uint32_t)__builtin_popcount((uint32_t)(m >> row_shift) & 0xffffu);
+}
+
+// dense_query4 for a workgroup that holds the word's Bhat row and tree level in LDS, laid out as the sampling
+// kernel stages them: the row from byte 0 to phi_bytes (K rounded to 4 floats), four control words of which the
+// last is zero, then l3 from byte l3_addr = phi_bytes + 16.  Same numbers and same decisions as dense_query4; what
+// differs is how they are fetched and counted.  Nothing is read conditionally: l3[-1] is the zero word before l3[0];
+// a lane whose four columns lie past the row's end (last block only) reads the row's last four instead and is left
+// out of the count afterwards (its sums would not be below x, and a prefix scan hands nothing of it to the lanes
+// before it).  The descent's strides are powers of 16, applied as shifts (top_shift = 4 * number of levels above
+// the lowest), and a row's count of entries below x comes from one wave-wide compare mask instead of four DPP additions.
+__device__ __forceinline__ uint32_t dense_query4_staged(uint32_t phi_bytes, uint32_t l3_addr, const double *__restrict__ l3_64,
+                                                        int n3, int top_shift, int K, float x, uint32_t li, uint32_t row_shift) {
+    typedef __attribute__((address_space(3))) const float lds_cfloat;
+    typedef float quad_t __attribute__((ext_vector_type(4)));
+    typedef __attribute__((address_space(3))) const quad_t lds_cquad;
+    uint32_t blk = 0;
+    for (int sh = top_shift; sh >= 0; sh -= 4) {
+        const uint32_t probe = min(blk + ((li + 1u) << sh), (uint32_t)n3);   // 1 + index of the entry this lane tests
+        const float c = *reinterpret_cast<lds_cfloat *>(l3_addr - 4u + (probe << 2));
+        blk += min(row16_count(c < x, row_shift), 15u) << sh;
+    }
+    blk = min(blk, (uint32_t)n3 - 1u);                      // rounding left no block: the last one
+    const uint32_t col_bytes = (blk << 8) + (li << 4);
+    const bool in_row = col_bytes < phi_bytes;
+    const quad_t f = *reinterpret_cast<lds_cquad *>(min(col_bytes, phi_bytes - 16u));
+    const float before = *reinterpret_cast<lds_cfloat *>(l3_addr - 4u + (blk << 2));
+    const float t0 = f.x, t1 = t0 + f.y, t2 = t1 + f.z, t3 = t2 + f.w;
+    const float a2 = before + (row16_incl_scan(t3) - t3);
+    const float c0 = a2 + t0, c1 = a2 + t1, c2 = a2 + t2, c3 = a2 + t3;
+    uint32_t below = (c0 < x ? 1u : 0u) + (c1 < x ? 1u : 0u) + (c2 < x ? 1u : 0u) + (c3 < x ? 1u : 0u);
+    const float nearest = fminf(fminf(fabsf(c0 - x), fabsf(c1 - x)), fminf(fabsf(c2 - x), fabsf(c3 - x)));
+    if (__builtin_amdgcn_ballot_w64(in_row && nearest <= x * 1.5e-6f)) {   // wave-uniform: some entry is too close to x to call
+        const double base = blk > 0 ? l3_64[blk - 1] : 0.0;
+        const double s0 = (double)f.x, s1 = s0 + (double)f.y, s2 = s1 + (double)f.z, s3 = s2 + (double)f.w;
+        const double b2 = base + (row16_incl_scan(s3) - s3);
+        below = ((float)(b2 + s0) < x ? 1u : 0u) + ((float)(b2 + s1) < x ? 1u : 0u) +
+                ((float)(b2 + s2) < x ? 1u : 0u) + ((float)(b2 + s3) < x ? 1u : 0u);
+    }
+    const uint32_t k = (blk << 6) + min(row16_allsum(in_row ? below : 0u), (uint32_t)kWave - 1u);
+    return min(k, (uint32_t)K - 1u);
+}
+
 // ---------------------------------------------------------------------------------------------
 // E-step (Alg. 2).  One workgroup per tile; the word's Bhat row and the upper tree level are staged in
 // LDS (STAGED) or read from global memory.  Each wavefront takes a batch of up to 64 tokens: the
@@ -422,23 +469,25 @@ template <int MODE, bool STAGED, typename ZT, bool B16, bool LIGHT>
 __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
     extern __shared__ float4 lds_f4[];
     // LDS, all of it dynamic so that the Bhat row starts at address 0 and a gather needs no base added:
-    //   STAGED: [K rounded to 4] floats: the word's Bhat row; [n3 rounded to 4] floats: the tree level above the bottom
-    //   [4] words: batch ticket, dense-branch tokens of the workgroup;  LOGLIK: [16] doubles, one per wavefront
+    //   STAGED: [K rounded to 4] floats: the word's Bhat row
+    //   [4] words: batch ticket, dense-branch tokens of the workgroup, 0, 0 (the last one doubles as the tree level's
+    //           entry "before the first", which the dense branch reads for the first block)
+    //   STAGED: [n3 rounded to 4] floats: the tree level above the bottom;  LOGLIK: [16] doubles, one per wavefront
     // The footprint is kept minimal because it decides how many wavefronts a CU can hold: at K = 10,000 it is
     // 40,656 bytes, which lets four 512-thread workgroups (32 wavefronts) share the 160 KB of a CU.
     const int K4 = STAGED ? (p.K + 3) & ~3 : 0;
     float *lds_phi = reinterpret_cast<float *>(lds_f4);
-    float *lds_l3 = lds_phi + K4;
-    int *ctrl = reinterpret_cast<int *>(lds_l3 + (STAGED ? (p.n3 + 3) & ~3 : 0));
+    int *ctrl = reinterpret_cast<int *>(lds_phi + K4);
+    float *lds_l3 = lds_phi + K4 + 4;
     int &next_batch = ctrl[0];   // batches of a tile are handed out to wavefronts as they become free
     unsigned int &wg_dense = reinterpret_cast<unsigned int *>(ctrl)[1];   // dense-branch tokens of this workgroup
-    double *ll_wave = reinterpret_cast<double *>(ctrl + 4);
+    double *ll_wave = reinterpret_cast<double *>(lds_l3 + (STAGED ? (p.n3 + 3) & ~3 : 0));
     const Tile tile = p.tiles[blockIdx.x];
     const int K = p.K;
     const float *__restrict__ phi_row = LIGHT ? p.base : p.phi + (size_t)tile.row * (size_t)p.Kpad;
     const float *__restrict__ l3_row = p.l3 + (size_t)tile.word * (size_t)p.n3pad;
     const double *__restrict__ l3_64_row = p.l3_64 + (size_t)tile.word * (size_t)p.n3;
-    if (threadIdx.x == 0) { next_batch = 0; wg_dense = 0u; }
+    if (threadIdx.x == 0) { next_batch = 0; wg_dense = 0u; ctrl[2] = 0; ctrl[3] = 0; }
     if (STAGED) {
         const float4 *src = reinterpret_cast<const float4 *>(phi_row);
         float4 *dst = reinterpret_cast<float4 *>(lds_phi);
@@ -458,6 +507,8 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
     }
     const float sum_w = p.sumphi[tile.word];
     const float Q = p.alpha * sum_w;
+    int l3_top_shift = 0;                      // the dense branch's descent over l3 starts with stride 16^(l3_top_shift / 4)
+    while ((16 << l3_top_shift) < p.n3) l3_top_shift += 4;
     const int lane = lane_id(), nwaves = blockDim.x / kWave;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
     const uint32_t bits = B16 ? 16u : p.topic_bits, tmask = B16 ? 0xffffu : p.topic_mask;
@@ -527,7 +578,13 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
             uint32_t ln = (uint32_t)lane;
             asm volatile("" : "+v"(ln));
             const uint32_t gi = ln >> LG, li = ln & (uint32_t)(G - 1), li16 = li << 4;
-            const uint32_t rank = bits_up_to_lane(cm);          // pieces of the class that start at this lane or before
+            // Slot order: the pieces of one token first, the longer ones after them, each kind in batch order.  A pass
+            // runs as many search steps as its longest piece has tokens, so like goes with like.  `rank` = 1 + slot of
+            // the piece this lane belongs to.
+            const unsigned long long sing = cm & ((cuts >> 1) | (1ull << (n - 1)));   // a piece that ends where the next begins
+            const uint32_t nsing = (uint32_t)__builtin_popcountll(sing);
+            const uint32_t rank = __builtin_amdgcn_inverse_ballot_w64(sing) ? bits_up_to_lane(sing)
+                                                                            : nsing + bits_up_to_lane(cm & ~sing);
             // slots: a piece's first lane writes to slot rank - 1; all other lanes write to lane 63, which is a slot
             // only if every lane starts a piece
             const uint32_t dst4 = __builtin_amdgcn_inverse_ballot_w64(cm) ? (rank - 1u) << 2 : 252u + zero;
@@ -769,9 +826,31 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
                 dense_mask = 0ull;
             }
             const float xd = u1 * sum_w;
-            int ln = lane;
+            uint32_t ln = (uint32_t)lane;
             asm volatile("" : "+v"(ln));               // (as above: lane-derived values formed where they are used)
-            const int g = ln >> 4, li = ln & 15;
+            const uint32_t g = ln >> 4, li = ln & 15u;
+            if (STAGED) {
+                while (dense_mask) {
+                    // the next four tokens (fewer at the end: the spare rows then repeat the first token's query, and
+                    // arrive at the same answer)
+                    const unsigned long long before = dense_mask;
+                    uint32_t tl[4];
+#pragma unroll
+                    for (int q = 0; q < 4; q++) {
+                        tl[q] = dense_mask ? (uint32_t)__builtin_ctzll(dense_mask) : tl[0];
+                        if (dense_mask) dense_mask = clear_bit(dense_mask, (int)tl[q]);
+                    }
+                    // lane number * 4 of the row's token: the four of them packed into one scalar, a byte each
+                    const uint32_t packed = (tl[0] | (tl[1] << 8) | (tl[2] << 16) | (tl[3] << 24)) << 2;
+                    const uint32_t mine4 = __builtin_amdgcn_ubfe(packed, g << 3, 8u);
+                    const float x = lane_pull(xd, mine4);
+                    const uint32_t k = dense_query4_staged((uint32_t)K4 * 4u, (uint32_t)K4 * 4u + 16u, l3_64_row, p.n3, l3_top_shift, K,
+                                                           x, li, ln & 48u);
+                    // all 16 lanes of a row hold the row's answer and send it to the row's token
+                    const uint32_t got = lane_push(k, mine4);
+                    my_z = __builtin_amdgcn_inverse_ballot_w64(before ^ dense_mask) ? got : my_z;
+                }
+            }
             while (dense_mask) {
                 int tl[4];
 #pragma unroll
@@ -781,8 +860,7 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
                 }
                 const int mine = g == 0 ? tl[0] : g == 1 ? tl[1] : g == 2 ? tl[2] : tl[3];
                 const float x = __int_as_float(__builtin_amdgcn_ds_bpermute((mine < 0 ? lane : mine) << 2, __float_as_int(xd)));
-                const uint32_t k = dense_query4(STAGED ? lds_phi : phi_row, STAGED ? K4 : p.Kpad, STAGED ? lds_l3 : l3_row,
-                                                l3_64_row, p.n3, K, x, li);
+                const uint32_t k = dense_query4(phi_row, p.Kpad, l3_row, l3_64_row, p.n3, K, x, (int)li);
 #pragma unroll
                 for (int q = 0; q < 4; q++)
                     if (tl[q] >= 0) my_z = llvm_amdgcn_writelane_u32(readlane_u32(k, 16 * q), (unsigned)tl[q], my_z);

@@ -33,7 +33,7 @@ def test_struct_layouts_match_header():
     assert ctypes.sizeof(pk.Options) == 16 * 4
     assert ctypes.sizeof(pk.Stats) == 23 * 8
     o = pk.options_default()
-    assert (o.n_chunks, o.block_threads, o.tile_tokens, o.stage_phi, o.profile) == (0, 0, 8192, 1, 0)
+    assert (o.n_chunks, o.block_threads, o.tile_tokens, o.stage_phi, o.profile) == (0, 0, 0, 1, 0)
 
 
 def header_struct_fields(name):
