@@ -272,6 +272,47 @@ def test_empty_documents_and_single_tokens():
         assert_estep_parity(g, o, min_agree=0.0)
 
 
+@pytest.mark.parametrize("K", [7, 300, 70000])
+def test_short_segments_counted_in_registers(K):
+    """Segments of at most 64 and of 65 to 128 assignments are sorted and counted in a wavefront's registers, longer
+    ones with the LDS bitmap: documents and (light) words on both sides of each limit, with planted assignments that
+    make every key different (rows of 64 and 128 entries), all keys equal, and two keys alternating; K = 70,000 takes
+    the 32-bit assignments.  CountByDZ and CountByVZ (Alg. 1, Sec. 3.3) must equal the oracle's bit for bit."""
+    lens = [1, 2, 3, 63, 64, 65, 66, 127, 128, 129, 130, 200, 64, 128, 64, 128, 64, 128, 100, 0, 5]
+    doc_ptr = np.r_[0, np.cumsum(lens)].astype(np.int64)
+    T = int(doc_ptr[-1])
+    rng = np.random.default_rng(K)
+    V = 40
+    # word lengths (segments of z_wm) hit the same limits: words 0..5 get 64, 65, 128, 129, 1, 2 tokens
+    want = [64, 65, 128, 129, 1, 2]
+    word_ids = rng.integers(len(want), V, T).astype(np.int32)
+    free = rng.permutation(T)
+    at = 0
+    for w, n in enumerate(want):
+        word_ids[free[at:at + n]] = w; at += n
+    pk = saber()
+    g = pk.Saber(doc_ptr, word_ids, V, K, 0.2, 0.01, 3)
+    o = oracle.Model(doc_ptr, word_ids, V, K, 0.2, 0.01, 3)
+    assert np.array_equal(g.get_z(), o.z)
+    assert_counts_equal(g, o)
+    z = rng.integers(0, K, T).astype(np.int32)
+    for d, kind in ((12, "distinct"), (13, "distinct"), (14, "equal"), (15, "equal"), (16, "two"), (17, "two"), (11, "distinct")):
+        b, e = int(doc_ptr[d]), int(doc_ptr[d + 1])
+        if kind == "distinct" and K >= e - b:
+            z[b:e] = rng.permutation(K)[: e - b]
+        elif kind == "equal":
+            z[b:e] = K - 1
+        elif kind == "two":
+            z[b:e] = np.where(np.arange(e - b) % 2 == 0, K - 1, 0)
+    g.set_z(z, 1); o.set_z(z, 1)
+    if K >= 200:
+        assert np.diff(o.cd[0])[[12, 13]].tolist() == [64, 128]
+    assert_counts_equal(g, o)
+    for _ in range(2):
+        assert_estep_parity(g, o, min_agree=0.0)
+    g.close(); o.close()
+
+
 def test_empty_corpus():
     pk = saber()
     g = pk.Saber(np.zeros(4, dtype=np.int64), np.zeros(0, dtype=np.int32), 3, 4, 0.1, 0.01, 1)
