@@ -505,17 +505,19 @@ static int launch_topic_totals(saber_ctx *c) {
     HIP_TRY(hipGetLastError());
     if (c->T == 0) return SABER_OK;
     const int use_lds = (size_t)c->K * 4 <= 60 * 1024;
-    const int64_t per_block = 65536;
+    // every workgroup ends with up to K atomics into the K totals: few, large workgroups (about 500 of them, each
+    // over at least 65,536 and at most 2^20 assignments) keep those from dominating
+    const int64_t per_block = std::min<int64_t>(1 << 20, std::max<int64_t>(65536, ((c->T / 512 + 4095) / 4096) * 4096));
     const int64_t nblocks = (c->T + per_block - 1) / per_block;
     const size_t lds = use_lds ? (size_t)c->K * 4 : 0;
     // a histogram of all assignments: their order does not matter, and with host streaming the word-major copy is
     // the one that is resident
     const void *zsrc = c->n_slots ? c->z_wm : c->z;
     if (c->z16)
-        hipLaunchKernelGGL((topic_totals_kernel<uint16_t>), dim3((unsigned)nblocks), dim3(256), lds, c->stream,
+        hipLaunchKernelGGL((topic_totals_kernel<uint16_t>), dim3((unsigned)nblocks), dim3(1024), lds, c->stream,
                            (const uint16_t *)zsrc, c->T, per_block, c->ck, c->K, use_lds);
     else
-        hipLaunchKernelGGL((topic_totals_kernel<int32_t>), dim3((unsigned)nblocks), dim3(256), lds, c->stream,
+        hipLaunchKernelGGL((topic_totals_kernel<int32_t>), dim3((unsigned)nblocks), dim3(1024), lds, c->stream,
                            (const int32_t *)zsrc, c->T, per_block, c->ck, c->K, use_lds);
     HIP_TRY(hipGetLastError());
     return SABER_OK;
@@ -770,7 +772,7 @@ static int build(saber_ctx *c, const int64_t *doc_ptr, const int32_t *word_ids) 
     {
         for (int32_t li = 0; li < c->V_light; li++) wm_ptr[(size_t)h_light_words[(size_t)li]] = h_light_tok_ptr[(size_t)li];
         int64_t pos = c->T_light;
-        const int64_t slab = 32768;
+        const int64_t slab = 131072;
         for (int32_t r = 0; r < c->V_dense; r++) {
             const int32_t v = h_row_word[(size_t)r];
             wm_ptr[(size_t)v] = pos;

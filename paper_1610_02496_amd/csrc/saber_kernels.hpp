@@ -1200,7 +1200,8 @@ __global__ void __launch_bounds__(1024) count_dz_kernel(const int32_t *doc_list,
 // column sums of B at K = 10^4).  LDS histogram when K fits, else global atomics.
 // ---------------------------------------------------------------------------------------------
 template <typename ZT>
-__global__ void topic_totals_kernel(const ZT *z, int64_t T, int64_t per_block, unsigned long long *ck, int K, int use_lds) {
+__global__ void __launch_bounds__(1024) topic_totals_kernel(const ZT *z, int64_t T, int64_t per_block, unsigned long long *ck, int K,
+                                                            int use_lds) {
     extern __shared__ uint32_t hist[];
     const int64_t b = (int64_t)blockIdx.x * per_block;
     int64_t e = b + per_block; if (e > T) e = T;

@@ -546,7 +546,7 @@ def test_random_shapes_and_options(test_seed):
         D = int(rng.integers(1, 120))
         V = int(rng.choice([1, 2, 7, 50, 400]))
         K = int(rng.choice(k_pool))
-        mean_len = float(rng.choice([0.5, 3.0, 40.0, 300.0]))
+        mean_len = float(rng.choice([0.5, 3.0, 40.0, 90.0, 300.0]))
         lens = rng.poisson(mean_len, D) * (rng.random(D) > 0.1)
         if rng.random() < 0.3:
             lens[int(rng.integers(0, D))] += int(rng.integers(600, 3000))      # one long document
