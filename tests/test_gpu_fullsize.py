@@ -29,7 +29,7 @@ def corpus_for(name):
     """C3: the benchmark corpus (100M tokens).  C4p: the first million documents of the PubMed-shaped
     workload (short documents, 90M tokens, V=141K), fitted with its K=5,000.  C5p: the first 820,000 documents of
     the ClueWeb12-subset-shaped workload (long, heavy-tailed documents, 300M tokens), fitted with its K=10,000:
-    the library cuts it into three document chunks by itself (Sec. 3.1.2), as it cuts the full workload into 53."""
+    the library cuts it into four document chunks by itself (Sec. 3.1.2), as it cuts the full workload into 85."""
     if name not in _CORPORA:
         _CORPORA.clear()                       # one large corpus in memory at a time
         t = time.time()
