@@ -34,7 +34,7 @@ def log(*a):
 
 
 def algorithmic_bytes(st, K, z_bytes):
-    """HBM bytes the sampling kernel must move for the iterations counted in ``st`` (model stated in the design doc).
+    """HBM bytes the sampling kernel must move for the iterations counted in ``st`` (the model is the list below).
 
     per token : 4 (document id) + 4 (token index) + 8 (row descriptor) + 2 * z_bytes (the assignment, written in
                 canonical order and again in word-major order for CountByVZ)
@@ -265,8 +265,8 @@ def main():
                     help="documents scored by the holdout log-likelihood after the timed region (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        log("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path shards by document, "
-            "see DESIGN.md, but no multi-GPU code is part of it)" % args.gpus)
+        log("bench.py: this build runs on ONE GPU; --gpus %d is not supported (the path would shard by document, "
+            "but no multi-GPU code is part of it)" % args.gpus)
         sys.exit(2)
     import torch
     if not torch.cuda.is_available():
