@@ -256,7 +256,7 @@ def main():
     ap.add_argument("--probe-bytes", type=int, default=1 << 30, help="size of the copy-bandwidth probe (0 = skip)")
     ap.add_argument("--opt", action="append", default=[], metavar="NAME=INT",
                     help="any other field of saber_options, for experiments (e.g. --opt dz_lds_entries=2048)")
-    ap.add_argument("--streaming", default="3:4", metavar="WORKERS:CHUNKS",
+    ap.add_argument("--streaming", default="3:2", metavar="WORKERS:CHUNKS",
                     help="also time the iterations with host streaming in this configuration ('' = skip)")
     ap.add_argument("--topic-conc", type=float, default=0.0,
                     help="override the mean per-word Dirichlet concentration of the planted topics (the workloads use "
@@ -277,7 +277,7 @@ def main():
     spec = corpusgen.SPECS[args.workload]
     if args.workload in ("C4", "C5"):
         os.environ.setdefault("LDA_CORPUS_PROGRESS", "2000000")   # the generator reports on stderr while it works
-        if args.streaming == "3:4":
+        if args.streaming == "3:2":
             args.streaming = "3:0"                                 # chunks as the library cuts them
     if args.docs:
         spec = corpusgen.scaled(spec, args.docs)

@@ -130,7 +130,7 @@ def test_full_size_parity(name, K):
 
 
 def test_full_size_streaming_and_variants_equal_default():
-    """At the benchmark's size: host streaming (the configuration bench.py times: 3 workers, 4 chunks) and the two
+    """At the benchmark's size: host streaming (the configuration bench.py times: 3 workers, 2 chunks; and others) and the two
     ablation variants give the assignments of the default path bit for bit, which the test above holds against the
     oracle; the chains are compared after two iterations."""
     import paper_1610_02496_amd as pk
@@ -143,7 +143,8 @@ def test_full_size_streaming_and_variants_equal_default():
     z_ref, ll_ref = g.get_z(), g.loglik()
     ck_ref = g.counts(want_cd=False, want_cwk=False)[4]
     g.close()
-    for label, opts in [("streaming 3x4", {"stream_workers": 3, "n_chunks": 4}), ("streaming 2x7", {"stream_workers": 2, "n_chunks": 7}),
+    for label, opts in [("streaming 3x2", {"stream_workers": 3, "n_chunks": 2}), ("streaming 3x4", {"stream_workers": 3, "n_chunks": 4}),
+                        ("streaming 2x7", {"stream_workers": 2, "n_chunks": 7}),
                         ("A by sorting", {"ablation": 2}), ("document order", {"ablation": 1})]:
         t = time.time()
         g = pk.Saber(*args, **opts)
