@@ -1157,25 +1157,26 @@ __global__ void __launch_bounds__(1024) count_dz_kernel(const int32_t *doc_list,
     __syncthreads();
     block_for_each_z(zd, (int64_t)len, [&](uint32_t k) { atomicOr(&bitmap[k >> 5], 1u << (k & 31u)); });
     __syncthreads();
-    // ranks: exclusive prefix of popcounts over the bitmap words
-    uint32_t carry = 0;
-    for (int w0 = 0; w0 < nwords; w0 += blockDim.x) {
-        const int w = w0 + threadIdx.x;
-        const uint32_t pc = (w < nwords) ? (uint32_t)__popc(bitmap[w]) : 0u;
-        uint32_t total;
-        const uint32_t ex = block_excl_scan(pc, scan_scratch, &total);
-        if (w < nwords) wpre[w] = carry + ex;
-        carry += total;
-    }
-    const int kd = (int)carry;
+    // ranks: exclusive prefix of popcounts over the bitmap words.  Every thread takes a contiguous piece of the
+    // bitmap (ascending topics), so one scan over the threads' totals serves all words
+    const int wpt = (nwords + (int)blockDim.x - 1) / (int)blockDim.x;
+    const int wb = min((int)threadIdx.x * wpt, nwords), we = min(wb + wpt, nwords);
+    uint32_t mine = 0;
+    for (int w = wb; w < we; w++) mine += (uint32_t)__popc(bitmap[w]);
+    uint32_t total;
+    const uint32_t first = block_excl_scan(mine, scan_scratch, &total);
+    const int kd = (int)total;
     uint32_t *row = cd_ent + (size_t)docrec[d].x * 32u;
     const bool in_lds = kd <= lds_entries;
     uint32_t *ent = in_lds ? ent_lds : row;
-    __syncthreads();
-    // slot r of the row starts as (topic, count 0): enumerate the set bits of every bitmap word
-    for (int w = threadIdx.x; w < nwords; w += blockDim.x) {
-        uint32_t m = bitmap[w]; uint32_t r = wpre[w];
-        while (m) { const int b = __ffs((int)m) - 1; m &= m - 1u; ent[r++] = (uint32_t)(w * 32 + b); }
+    // slot r of the row starts as (topic, count 0): enumerate the set bits of the thread's words
+    {
+        uint32_t r = first;
+        for (int w = wb; w < we; w++) {
+            uint32_t m = bitmap[w];
+            wpre[w] = r;
+            while (m) { const int b = __ffs((int)m) - 1; m &= m - 1u; ent[r++] = (uint32_t)(w * 32 + b); }
+        }
     }
     __syncthreads();
     block_for_each_z(zd, (int64_t)len, [&](uint32_t k) {
