@@ -489,9 +489,22 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
     const double *__restrict__ l3_64_row = p.l3_64 + (size_t)tile.word * (size_t)p.n3;
     if (threadIdx.x == 0) { next_batch = 0; wg_dense = 0u; ctrl[2] = 0; ctrl[3] = 0; }
     if (STAGED) {
-        const float4 *src = reinterpret_cast<const float4 *>(phi_row);
-        float4 *dst = reinterpret_cast<float4 *>(lds_phi);
-        for (int i = threadIdx.x; i < K4 / 4; i += blockDim.x) dst[i] = src[i];
+        // eight 16-byte loads per thread are requested before the first of them is written to LDS: one load, one
+        // wait, one write at a time left a workgroup's start waiting for memory five times over at K = 10,000.
+        // (No branch inside: past the end, the last piece is read and written once more.)
+        typedef float quad_t __attribute__((ext_vector_type(4)));
+        const quad_t *qsrc = reinterpret_cast<const quad_t *>(phi_row);
+        quad_t *qdst = reinterpret_cast<quad_t *>(lds_phi);
+        const int nq = K4 / 4, step = (int)blockDim.x;
+        for (int i0 = threadIdx.x; i0 < nq; i0 += 8 * step) {
+            const quad_t q0 = qsrc[min(i0, nq - 1)], q1 = qsrc[min(i0 + step, nq - 1)], q2 = qsrc[min(i0 + 2 * step, nq - 1)],
+                         q3 = qsrc[min(i0 + 3 * step, nq - 1)], q4 = qsrc[min(i0 + 4 * step, nq - 1)],
+                         q5 = qsrc[min(i0 + 5 * step, nq - 1)], q6 = qsrc[min(i0 + 6 * step, nq - 1)],
+                         q7 = qsrc[min(i0 + 7 * step, nq - 1)];
+            qdst[min(i0, nq - 1)] = q0; qdst[min(i0 + step, nq - 1)] = q1; qdst[min(i0 + 2 * step, nq - 1)] = q2;
+            qdst[min(i0 + 3 * step, nq - 1)] = q3; qdst[min(i0 + 4 * step, nq - 1)] = q4; qdst[min(i0 + 5 * step, nq - 1)] = q5;
+            qdst[min(i0 + 6 * step, nq - 1)] = q6; qdst[min(i0 + 7 * step, nq - 1)] = q7;
+        }
         if (MODE == MODE_SAMPLE)
             for (int i = threadIdx.x; i < p.n3; i += blockDim.x) lds_l3[i] = l3_row[i];
     }
