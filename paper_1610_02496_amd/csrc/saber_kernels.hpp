@@ -487,7 +487,23 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
     const float *__restrict__ phi_row = LIGHT ? p.base : p.phi + (size_t)tile.row * (size_t)p.Kpad;
     const float *__restrict__ l3_row = p.l3 + (size_t)tile.word * (size_t)p.n3pad;
     const double *__restrict__ l3_64_row = p.l3_64 + (size_t)tile.word * (size_t)p.n3;
-    if (threadIdx.x == 0) { next_batch = 0; wg_dense = 0u; ctrl[2] = 0; ctrl[3] = 0; }
+    const int lane = lane_id(), nwaves = blockDim.x / kWave;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
+    // batch size: 64 tokens per wavefront, fewer when the tile is too small to keep every wavefront busy
+    int bs = (tile.count + nwaves - 1) / nwaves;
+    bs = __builtin_amdgcn_readfirstlane(bs > kWave ? kWave : bs);   // wave-uniform: keep it in a scalar register
+    // The first batch of every wavefront is fixed (wavefront w takes batch w; the ticket counter starts behind these),
+    // so its token records are requested here, before the word's row is staged, and the row records of their
+    // documents before the workgroup waits at the barrier: for a small tile (one batch per wavefront) two of the three
+    // dependent memory accesses in front of the first row then pass under the staging.
+    int batch = wave * bs;
+    int d = -1;
+    uint32_t t = 0u;
+    if (lane < min(bs, tile.count - batch)) {
+        d = p.tok_doc[tile.begin + batch + lane];
+        t = p.tok_t[tile.begin + batch + lane];
+    }
+    if (threadIdx.x == 0) { next_batch = nwaves; wg_dense = 0u; ctrl[2] = 0; ctrl[3] = 0; }
     if (STAGED) {
         // eight 16-byte loads per thread are requested before the first of them is written to LDS: one load, one
         // wait, one write at a time left a workgroup's start waiting for memory five times over at K = 10,000.
@@ -508,6 +524,8 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
         if (MODE == MODE_SAMPLE)
             for (int i = threadIdx.x; i < p.n3; i += blockDim.x) lds_l3[i] = l3_row[i];
     }
+    uint2 rec = make_uint2(p.row_unit0, 0u);
+    if (d >= 0) rec = p.docrec[d];
     __syncthreads();
     if (LIGHT) {
         // the staged row is the base vector so far; overwrite the topics this word has counts for
@@ -522,30 +540,18 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
     const float Q = p.alpha * sum_w;
     int l3_top_shift = 0;                      // the dense branch's descent over l3 starts with stride 16^(l3_top_shift / 4)
     while ((16 << l3_top_shift) < p.n3) l3_top_shift += 4;
-    const int lane = lane_id(), nwaves = blockDim.x / kWave;
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x / kWave));
     const uint32_t bits = B16 ? 16u : p.topic_bits, tmask = B16 ? 0xffffu : p.topic_mask;
     // all rows of A of the chunk behind one buffer descriptor: a row is addressed by its 32-bit byte offset
     const __amdgpu_buffer_rsrc_t rows = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(p.cd_rows), (short)0,
                                                                           (int)p.rows_bytes, 0x00020000);
     double ll_acc = 0.0;
-    // batch size: 64 tokens per wavefront, fewer when the tile is too small to keep every wavefront busy
-    int bs = (tile.count + nwaves - 1) / nwaves;
-    bs = __builtin_amdgcn_readfirstlane(bs > kWave ? kWave : bs);   // wave-uniform: keep it in a scalar register
 
+    // `batch`, and d, t, rec of its tokens, are in hand at the top of every turn: those of the first batch from above,
+    // those of the later ones from the bottom of the turn before
     for (int round = 0;; round++) {
-        int ticket = 0;
-        if (MODE == MODE_LOGLIK) ticket = round * nwaves + wave;   // fixed assignment: the sums come out bit-identical every time
-        else if (lane == 0) ticket = atomicAdd(&next_batch, 1);
-        const int batch = __builtin_amdgcn_readfirstlane(ticket) * bs;   // wave-uniform: loop control stays scalar
         if (batch >= tile.count) break;
         const int n = __builtin_amdgcn_readfirstlane(min(bs, tile.count - batch));   // wave-uniform by construction
         const bool act = lane < n;
-        const int i = tile.begin + batch + lane;
-        const int d = act ? p.tok_doc[i] : -1;
-        const uint32_t t = act ? p.tok_t[i] : 0u;
-        uint2 rec = make_uint2(p.row_unit0, 0u);
-        if (act) rec = p.docrec[d];
         float u0 = 0.f, u1 = 0.f;
         if (MODE == MODE_SAMPLE) {
             Rand2 r = philox_token(p.seed_lo, p.seed_hi, (uint64_t)(p.t_base + (int64_t)t), p.iter);
@@ -892,6 +898,18 @@ __global__ void __launch_bounds__(1024, 8) estep_kernel(EStepParams p) {
             } else {
                 ll_acc += log((double)(my_S + Q));
             }
+        }
+        // the next batch: taken from the ticket counter, as wavefronts become free.  (Asking for it and for its tokens'
+        // records earlier, before the dense branch, changed nothing.)
+        int ticket = 0;
+        if (MODE == MODE_LOGLIK) ticket = (round + 1) * nwaves + wave;   // fixed assignment: the sums come out bit-identical every time
+        else if (lane == 0) ticket = atomicAdd(&next_batch, 1);
+        batch = __builtin_amdgcn_readfirstlane(ticket) * bs;   // wave-uniform: loop control stays scalar
+        d = -1; t = 0u; rec = make_uint2(p.row_unit0, 0u);
+        if (lane < min(bs, tile.count - batch)) {
+            d = p.tok_doc[tile.begin + batch + lane];
+            t = p.tok_t[tile.begin + batch + lane];
+            rec = p.docrec[d];
         }
     }
 
